@@ -1,0 +1,123 @@
+/*
+ * oea.h - C ABI of the MI355X (gfx950) decode-time MoE layer with Opportunistic Expert
+ * Activation (OEA, arxiv 2511.02237).
+ *
+ * Conventions for every entry point
+ *   - Pointers are DEVICE pointers (HBM of the current HIP device) unless the name starts with h_.
+ *   - The caller owns every buffer; the library allocates no device memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue
+ *     work and return; results are valid once the caller has synchronised the stream.  Nothing
+ *     is read back to the host, so a call sequence can be captured into a HIP graph.
+ *   - Return value: OEA_OK (0) or a negative oea_status.  On error nothing was enqueued.
+ *   - All matrices are row-major, expert ids are 0-based (the paper counts from 1).
+ *   - Non-finite router logits give unspecified routing, but never an out-of-range index.
+ */
+#ifndef OEA_H_
+#define OEA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  OEA_OK = 0,
+  OEA_ERR_NULL = -1,      /* a required pointer is NULL */
+  OEA_ERR_SHAPE = -2,     /* B<1, N<1, d or I not a positive multiple of 8, or above the limits below */
+  OEA_ERR_K = -3,         /* not (1 <= k0 <= k <= min(N, OEA_MAX_K)) */
+  OEA_ERR_ALIGN = -4,     /* x / weight / workspace pointer not 16-byte aligned */
+  OEA_ERR_WORKSPACE = -5, /* workspace_bytes < oea_workspace_bytes(...) */
+  OEA_ERR_DTYPE = -6,     /* unknown oea_dtype */
+  OEA_ERR_HIP = -7        /* a HIP runtime call failed (no device, launch failure) */
+} oea_status;
+
+/* storage type of x, W_router, W_gate, W_up, W_down (all the same) */
+typedef enum { OEA_F32 = 0, OEA_BF16 = 1 } oea_dtype;
+
+#define OEA_MAX_N 512  /* experts */
+#define OEA_MAX_K 32   /* experts per token */
+#define OEA_MAX_B 1024 /* tokens per decode batch */
+#define OEA_MAX_D 8192 /* embedding dimension and expert hidden dimension */
+
+/* Host, pure.  Static text for a status code. */
+const char *oea_status_string(int status);
+
+/* Host, pure.  Bytes of device workspace moe_decode needs for these sizes (0 on bad sizes). */
+size_t oea_workspace_bytes(int B, int d, int N, int I, int k);
+
+/*
+ * Prepare a workspace: enqueues a fill kernel that zeroes its control words.  Call once after
+ * allocating (or re-using for something else) a workspace, before the first moe_decode on it.
+ * Each moe_decode leaves the control words zero again, so one call serves any number of layers.
+ */
+int oea_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * OEA routing of one decode batch from given router logits: Algorithm 1 of the paper
+ * (Phase 1: each token keeps its k0 best experts; Phase 2: in rank order it adds experts that are
+ * in the union of all tokens' Phase-1 sets, until it holds k), followed by the weighting of
+ * Section 3.2 "Weighting after rerouting" (softmax scores renormalised over the final set, Eq. 1).
+ * k0 == k is the unmodified top-k router.
+ *
+ *   router_logits [B,N] fp32   router pre-activations; ranking is by descending logit, equal
+ *                              logits by ascending expert id (-0.0 == +0.0)
+ *   expert_idx    [B,k] int32  S_i in rank order, -1 in unused slots
+ *   gate_w        [B,k] fp32   weights, 0 in unused slots, each row sums to 1
+ *   n_sel         [B]   int32  |S_i| = min(k, T)
+ *   active_list   [N]   int32  the union S^base, ascending; entries >= T are -1
+ *   n_active      [1]   int32  T = |S^base|
+ * Limits: N <= OEA_MAX_N, k <= OEA_MAX_K, B <= OEA_MAX_B.
+ */
+int oea_route(const float *router_logits, int B, int N, int k, int k0, int32_t *expert_idx,
+              float *gate_w, int32_t *n_sel, int32_t *active_list, int32_t *n_active,
+              void *stream);
+
+/*
+ * One decode-time MoE layer (Section 2, Eq. 1) with OEA routing (Algorithm 1):
+ *   logits = x W_router^T -> routing as in oea_route -> out[i] = sum_{e in S_i} g_{i,e} E_e(x_i),
+ *   E_e(x) = W_down[e] ( silu(W_gate[e] x) * (W_up[e] x) )      (Section 4: SwiGLU expert)
+ * Only the T experts of the union are read from memory, each once.
+ *
+ *   x        [B,d]    dt      token embeddings
+ *   W_router [N,d]    dt
+ *   W_gate   [N,I,d]  dt      per expert [I,d]: row j produces hidden unit j
+ *   W_up     [N,I,d]  dt
+ *   W_down   [N,d,I]  dt      per expert [d,I]: row c produces output coordinate c
+ *   out      [B,d]    fp32    overwritten
+ *   workspace         device scratch of >= oea_workspace_bytes(B,d,N,I,k) bytes, 16-byte aligned,
+ *                     prepared once by oea_workspace_init.  Two calls that share a workspace must
+ *                     be ordered on the same stream.
+ * Arithmetic: router logits are accumulated in fp64 and rounded once to fp32; expert mat-vecs
+ * multiply in the storage type and accumulate in fp32; with bf16 storage the hidden vector is
+ * rounded to bf16 between the two mat-vecs (as a bf16 model does).
+ * Limits: d, I multiples of 8 and <= OEA_MAX_D; N, k, B as for oea_route.
+ */
+int moe_decode(const void *x, const void *W_router, const void *W_gate, const void *W_up,
+               const void *W_down, float *out, int B, int d, int N, int I, int k, int k0,
+               oea_dtype dt, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Optional inputs and taps for moe_decode_ex; every pointer may be NULL. */
+typedef struct {
+  const float *router_bias;   /* [N] fp32 added to the logits (synthetic skewed-popularity workload) */
+  const uint8_t *token_mask;  /* [B] 0 = padding token: selects nothing, adds nothing to the union,
+                                 out row = 0 (Section 6, "A note on padding") */
+  float *logits_out;          /* [B,N] the fp32 logits the routing was taken on */
+  int32_t *expert_idx_out;    /* [B,k] */
+  float *gate_w_out;          /* [B,k] */
+  int32_t *n_sel_out;         /* [B]   */
+  int32_t *active_list_out;   /* [N]   */
+  int32_t *n_active_out;      /* [1]   */
+} oea_decode_ex;
+
+/* moe_decode with the extras above (ex == NULL behaves as moe_decode). */
+int moe_decode_ex(const void *x, const void *W_router, const void *W_gate, const void *W_up,
+                  const void *W_down, float *out, int B, int d, int N, int I, int k, int k0,
+                  oea_dtype dt, void *workspace, size_t workspace_bytes, void *stream,
+                  const oea_decode_ex *ex);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OEA_H_ */

@@ -1,0 +1,172 @@
+"""Thin ctypes binding over liboea.so: argument marshalling only.
+
+Every step of the layer runs in the HIP kernels of the library; torch is used for device memory
+and for the current stream handle, nothing else.  There is no CPU fallback: if the library is
+missing or fails to load this module raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liboea.so")
+
+OEA_F32, OEA_BF16 = 0, 1
+OEA_OK = 0
+STATUS = {"OEA_ERR_NULL": -1, "OEA_ERR_SHAPE": -2, "OEA_ERR_K": -3, "OEA_ERR_ALIGN": -4,
+          "OEA_ERR_WORKSPACE": -5, "OEA_ERR_DTYPE": -6, "OEA_ERR_HIP": -7}
+EXPORTS = ("oea_status_string", "oea_workspace_bytes", "oea_workspace_init", "oea_route", "moe_decode",
+           "moe_decode_ex")
+
+
+class OeaError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("liboea: %s (%d)" % (text, code))
+        self.code = code
+
+
+class DecodeEx(ctypes.Structure):
+    _fields_ = [("router_bias", ctypes.c_void_p), ("token_mask", ctypes.c_void_p),
+                ("logits_out", ctypes.c_void_p), ("expert_idx_out", ctypes.c_void_p),
+                ("gate_w_out", ctypes.c_void_p), ("n_sel_out", ctypes.c_void_p),
+                ("active_list_out", ctypes.c_void_p), ("n_active_out", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """Load liboea.so (built by `python -m paper_2511_02237_amd.build`).  Raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise OeaError(-100, "HIP library %s is not built; run python -m paper_2511_02237_amd.build" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+        L.oea_status_string.restype = ctypes.c_char_p
+        L.oea_status_string.argtypes = [ci]
+        L.oea_workspace_bytes.restype = sz
+        L.oea_workspace_bytes.argtypes = [ci] * 5
+        L.oea_workspace_init.restype = ci
+        L.oea_workspace_init.argtypes = [vp, sz, vp]
+        L.oea_route.restype = ci
+        L.oea_route.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
+        L.moe_decode.restype = ci
+        L.moe_decode.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp]
+        L.moe_decode_ex.restype = ci
+        L.moe_decode_ex.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp, ctypes.POINTER(DecodeEx)]
+        _lib = L
+    return _lib
+
+
+def status_string(code):
+    return lib().oea_status_string(int(code)).decode()
+
+
+def _check(code):
+    if code != OEA_OK:
+        raise OeaError(code, status_string(code))
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float32:
+        return OEA_F32
+    if t.dtype == torch.bfloat16:
+        return OEA_BF16
+    raise TypeError("x and weights must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def workspace_bytes(B, d, N, I, k):
+    return int(lib().oea_workspace_bytes(B, d, N, I, k))
+
+
+def new_workspace(B, d, N, I, k, device="cuda", stream=None):
+    """Allocate (torch) and prepare (library) a workspace for moe_decode."""
+    n = workspace_bytes(B, d, N, I, k)
+    if n == 0:
+        raise OeaError(STATUS["OEA_ERR_SHAPE"], status_string(STATUS["OEA_ERR_SHAPE"]))
+    ws = torch.empty(n, dtype=torch.uint8, device=device)
+    _check(lib().oea_workspace_init(_ptr(ws), n, _stream(stream)))
+    return ws
+
+
+def oea_route(router_logits, k, k0, stream=None, out=None):
+    """router_logits [B,N] float32 cuda -> dict(expert_idx, gate_w, n_sel, active_list, n_active) on device."""
+    assert router_logits.is_cuda and router_logits.dtype == torch.float32 and router_logits.is_contiguous()
+    B, N = router_logits.shape
+    dev = router_logits.device
+    if out is None:
+        out = dict(expert_idx=torch.empty((B, k), dtype=torch.int32, device=dev),
+                   gate_w=torch.empty((B, k), dtype=torch.float32, device=dev),
+                   n_sel=torch.empty((B,), dtype=torch.int32, device=dev),
+                   active_list=torch.empty((N,), dtype=torch.int32, device=dev),
+                   n_active=torch.empty((1,), dtype=torch.int32, device=dev))
+    _check(lib().oea_route(_ptr(router_logits), B, N, int(k), int(k0), _ptr(out["expert_idx"]),
+                           _ptr(out["gate_w"]), _ptr(out["n_sel"]), _ptr(out["active_list"]),
+                           _ptr(out["n_active"]), _stream(stream)))
+    return out
+
+
+def moe_decode(x, w_router, w_gate, w_up, w_down, k, k0, workspace, out=None, stream=None,
+               router_bias=None, token_mask=None, taps=False):
+    """One decode-time MoE layer with OEA routing.  Returns out [B,d] float32 (and a dict of routing
+    taps when taps=True)."""
+    for t in (x, w_router, w_gate, w_up, w_down):
+        assert t.is_cuda and t.is_contiguous()
+    dt = _dtype_code(x)
+    for t in (w_router, w_gate, w_up, w_down):
+        assert _dtype_code(t) == dt
+    B, d = x.shape
+    N, I, d2 = w_gate.shape
+    assert d2 == d and tuple(w_router.shape) == (N, d) and tuple(w_up.shape) == (N, I, d)
+    assert tuple(w_down.shape) == (N, d, I)
+    dev = x.device
+    if out is None:
+        out = torch.empty((B, d), dtype=torch.float32, device=dev)
+    args = [_ptr(x), _ptr(w_router), _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(out), B, d, N, I, int(k),
+            int(k0), dt, _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)]
+    if not taps and router_bias is None and token_mask is None:
+        _check(lib().moe_decode(*args))
+        return out
+    ex = DecodeEx()
+    tap = None
+    if router_bias is not None:
+        assert router_bias.is_cuda and router_bias.dtype == torch.float32 and router_bias.numel() == N
+        ex.router_bias = router_bias.data_ptr()
+    if token_mask is not None:
+        assert token_mask.is_cuda and token_mask.dtype == torch.uint8 and token_mask.numel() == B
+        ex.token_mask = token_mask.data_ptr()
+    if taps:
+        tap = dict(logits=torch.empty((B, N), dtype=torch.float32, device=dev),
+                   expert_idx=torch.empty((B, k), dtype=torch.int32, device=dev),
+                   gate_w=torch.empty((B, k), dtype=torch.float32, device=dev),
+                   n_sel=torch.empty((B,), dtype=torch.int32, device=dev),
+                   active_list=torch.empty((N,), dtype=torch.int32, device=dev),
+                   n_active=torch.empty((1,), dtype=torch.int32, device=dev))
+        ex.logits_out = tap["logits"].data_ptr()
+        ex.expert_idx_out = tap["expert_idx"].data_ptr()
+        ex.gate_w_out = tap["gate_w"].data_ptr()
+        ex.n_sel_out = tap["n_sel"].data_ptr()
+        ex.active_list_out = tap["active_list"].data_ptr()
+        ex.n_active_out = tap["n_active"].data_ptr()
+    _check(lib().moe_decode_ex(*args, ctypes.byref(ex)))
+    return (out, tap) if taps else out
+
+
+def to_device(a, device="cuda"):
+    """numpy array from `workloads` (float32, or uint16 bf16 bits) -> torch tensor on the device."""
+    import numpy as np
+
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(a).to(device)

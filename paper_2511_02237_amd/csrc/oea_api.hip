@@ -1,0 +1,154 @@
+// C ABI of liboea: argument checks, workspace carving, kernel enqueue.  See include/oea.h.
+#include <hip/hip_runtime.h>
+
+#include "oea_internal.h"
+
+namespace oea {
+
+static size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
+
+WsLayout ws_layout(int B, int d, int N, int I, int k, int elem_bytes) {
+  (void)d;
+  WsLayout w{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t at = off;
+    off = align256(off + bytes);
+    return at;
+  };
+  const size_t P = (size_t)B * k;
+  w.ctrl = take(64 * sizeof(uint32_t));
+  w.logits = take((size_t)B * N * sizeof(float));
+  w.expert_idx = take(P * sizeof(int32_t));
+  w.gate_w = take(P * sizeof(float));
+  w.n_sel = take((size_t)B * sizeof(int32_t));
+  w.active_list = take((size_t)N * sizeof(int32_t));
+  w.n_active = take(sizeof(int32_t));
+  w.grp_off = take((size_t)(N + 1) * sizeof(int32_t));
+  w.grp_tok = take(P * sizeof(int32_t));
+  w.grp_gw = take(P * sizeof(float));
+  w.h = take(P * (size_t)I * elem_bytes);
+  w.total = off;
+  return w;
+}
+
+static int check_route_sizes(int B, int N, int k, int k0) {
+  if (B < 1 || B > OEA_MAX_B || N < 1 || N > OEA_MAX_N) return OEA_ERR_SHAPE;
+  if (k0 < 1 || k0 > k || k > N || k > OEA_MAX_K) return OEA_ERR_K;
+  return OEA_OK;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace oea
+
+using namespace oea;
+
+extern "C" const char* oea_status_string(int status) {
+  switch (status) {
+    case OEA_OK: return "ok";
+    case OEA_ERR_NULL: return "a required pointer is NULL";
+    case OEA_ERR_SHAPE: return "shape out of range (B, N, d or I)";
+    case OEA_ERR_K: return "need 1 <= k0 <= k <= min(N, OEA_MAX_K)";
+    case OEA_ERR_ALIGN: return "pointer not 16-byte aligned";
+    case OEA_ERR_WORKSPACE: return "workspace too small";
+    case OEA_ERR_DTYPE: return "unknown dtype";
+    case OEA_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+static int elem_bytes_of(int dt) { return dt == OEA_F32 ? 4 : dt == OEA_BF16 ? 2 : 0; }
+
+static int check_decode_sizes(int B, int d, int N, int I, int k, int k0, int dt) {
+  const int eb = elem_bytes_of(dt);
+  if (eb == 0) return OEA_ERR_DTYPE;
+  int rc = check_route_sizes(B, N, k, k0);
+  if (rc != OEA_OK) return rc;
+  // fp32 rows are twice as many 16-byte granules: half the bf16 limit
+  const int max_dim = dt == OEA_F32 ? OEA_MAX_D / 2 : OEA_MAX_D;
+  if (d < 8 || I < 8 || (d % 8) != 0 || (I % 8) != 0 || d > max_dim || I > max_dim) return OEA_ERR_SHAPE;
+  return OEA_OK;
+}
+
+extern "C" size_t oea_workspace_bytes(int B, int d, int N, int I, int k) {
+  if (B < 1 || B > OEA_MAX_B || N < 1 || N > OEA_MAX_N || k < 1 || k > OEA_MAX_K || d < 1 || I < 1 ||
+      d > OEA_MAX_D || I > OEA_MAX_D)
+    return 0;
+  return ws_layout(B, d, N, I, k, 4).total;  // sized for the wider storage type
+}
+
+extern "C" int oea_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+  if (!workspace) return OEA_ERR_NULL;
+  if (!aligned16(workspace)) return OEA_ERR_ALIGN;
+  if (workspace_bytes < 64 * sizeof(uint32_t)) return OEA_ERR_WORKSPACE;
+  hipError_t e = launch_fill_zero(static_cast<uint32_t*>(workspace), 64, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? OEA_OK : OEA_ERR_HIP;
+}
+
+extern "C" int oea_route(const float* router_logits, int B, int N, int k, int k0, int32_t* expert_idx,
+                         float* gate_w, int32_t* n_sel, int32_t* active_list, int32_t* n_active,
+                         void* stream) {
+  if (!router_logits || !expert_idx || !gate_w || !n_sel || !active_list || !n_active) return OEA_ERR_NULL;
+  int rc = check_route_sizes(B, N, k, k0);
+  if (rc != OEA_OK) return rc;
+  RouteOut o{expert_idx, gate_w, n_sel, active_list, n_active, nullptr, nullptr, nullptr};
+  hipError_t e = launch_route(router_logits, nullptr, B, N, k, k0, o, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? OEA_OK : OEA_ERR_HIP;
+}
+
+extern "C" int moe_decode_ex(const void* x, const void* W_router, const void* W_gate, const void* W_up,
+                             const void* W_down, float* out, int B, int d, int N, int I, int k, int k0,
+                             oea_dtype dt, void* workspace, size_t workspace_bytes, void* stream,
+                             const oea_decode_ex* ex) {
+  if (!x || !W_router || !W_gate || !W_up || !W_down || !out || !workspace) return OEA_ERR_NULL;
+  int rc = check_decode_sizes(B, d, N, I, k, k0, (int)dt);
+  if (rc != OEA_OK) return rc;
+  if (!aligned16(x) || !aligned16(W_router) || !aligned16(W_gate) || !aligned16(W_up) || !aligned16(W_down) ||
+      !aligned16(out) || !aligned16(workspace))
+    return OEA_ERR_ALIGN;
+  if (workspace_bytes < oea_workspace_bytes(B, d, N, I, k)) return OEA_ERR_WORKSPACE;
+
+  const WsLayout w = ws_layout(B, d, N, I, k, elem_bytes_of(dt));
+  char* ws = static_cast<char*>(workspace);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  float* logits = reinterpret_cast<float*>(ws + w.logits);
+  RouteOut ro{reinterpret_cast<int32_t*>(ws + w.expert_idx), reinterpret_cast<float*>(ws + w.gate_w),
+              reinterpret_cast<int32_t*>(ws + w.n_sel),      reinterpret_cast<int32_t*>(ws + w.active_list),
+              reinterpret_cast<int32_t*>(ws + w.n_active),   reinterpret_cast<int32_t*>(ws + w.grp_off),
+              reinterpret_cast<int32_t*>(ws + w.grp_tok),    reinterpret_cast<float*>(ws + w.grp_gw)};
+  Grouping g{ro.active_list, ro.n_active, ro.grp_off, ro.grp_tok, ro.grp_gw};
+  void* h = ws + w.h;
+
+  hipError_t e = launch_router_and_route(x, W_router, ex ? ex->router_bias : nullptr,
+                                         ex ? ex->token_mask : nullptr, B, d, N, k, k0, dt, logits, out,
+                                         reinterpret_cast<uint32_t*>(ws + w.ctrl), ro, s);
+  if (e != hipSuccess) return OEA_ERR_HIP;
+  e = launch_expert_gate_up(x, W_gate, W_up, h, B, d, N, I, k, dt, g, s);
+  if (e != hipSuccess) return OEA_ERR_HIP;
+  e = launch_expert_down(h, W_down, out, B, d, N, I, k, dt, g, s);
+  if (e != hipSuccess) return OEA_ERR_HIP;
+
+  if (ex) {  // taps: device-to-device copies in stream order
+    const size_t P = (size_t)B * k;
+    struct { void* dst; const void* src; size_t bytes; } taps[] = {
+        {ex->logits_out, logits, (size_t)B * N * sizeof(float)},
+        {ex->expert_idx_out, ro.expert_idx, P * sizeof(int32_t)},
+        {ex->gate_w_out, ro.gate_w, P * sizeof(float)},
+        {ex->n_sel_out, ro.n_sel, (size_t)B * sizeof(int32_t)},
+        {ex->active_list_out, ro.active_list, (size_t)N * sizeof(int32_t)},
+        {ex->n_active_out, ro.n_active, sizeof(int32_t)},
+    };
+    for (auto& t : taps)
+      if (t.dst && hipMemcpyAsync(t.dst, t.src, t.bytes, hipMemcpyDeviceToDevice, s) != hipSuccess)
+        return OEA_ERR_HIP;
+  }
+  return OEA_OK;
+}
+
+extern "C" int moe_decode(const void* x, const void* W_router, const void* W_gate, const void* W_up,
+                          const void* W_down, float* out, int B, int d, int N, int I, int k, int k0,
+                          oea_dtype dt, void* workspace, size_t workspace_bytes, void* stream) {
+  return moe_decode_ex(x, W_router, W_gate, W_up, W_down, out, B, d, N, I, k, k0, dt, workspace,
+                       workspace_bytes, stream, nullptr);
+}

@@ -1,0 +1,64 @@
+// Internal declarations shared by the translation units of liboea (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "oea.h"
+
+namespace oea {
+
+// Carving of the caller's workspace.  All offsets are multiples of 256 bytes.
+struct WsLayout {
+  size_t ctrl;         // uint32[64]; [0] = arrival counter of the router kernel (zero between calls)
+  size_t logits;       // float [B,N]
+  size_t expert_idx;   // int32 [B,k]
+  size_t gate_w;       // float [B,k]
+  size_t n_sel;        // int32 [B]
+  size_t active_list;  // int32 [N]
+  size_t n_active;     // int32 [1]
+  size_t grp_off;      // int32 [N+1]  CSR offsets, indexed by position in active_list
+  size_t grp_tok;      // int32 [B*k]  token of each (expert, token) pair, grouped by expert
+  size_t grp_gw;       // float [B*k]  gate weight of that pair
+  size_t h;            // storage type [B*k, I]  hidden activations of each pair
+  size_t total;
+};
+
+WsLayout ws_layout(int B, int d, int N, int I, int k, int elem_bytes);
+
+// Device-side view of the routing results that the expert kernels consume.
+struct Grouping {
+  const int32_t* active_list;
+  const int32_t* n_active;
+  const int32_t* grp_off;
+  const int32_t* grp_tok;
+  const float* grp_gw;
+};
+
+struct RouteOut {
+  int32_t* expert_idx;
+  float* gate_w;
+  int32_t* n_sel;
+  int32_t* active_list;
+  int32_t* n_active;
+  int32_t* grp_off;  // may be nullptr (routing-only entry point)
+  int32_t* grp_tok;  // may be nullptr
+  float* grp_gw;     // may be nullptr
+};
+
+// launchers (each returns the hipError_t of the launch)
+hipError_t launch_fill_zero(uint32_t* p, size_t n_words, hipStream_t s);
+hipError_t launch_route(const float* logits, const uint8_t* token_mask, int B, int N, int k, int k0,
+                        RouteOut o, hipStream_t s);
+hipError_t launch_router_and_route(const void* x, const void* w_router, const float* bias,
+                                   const uint8_t* token_mask, int B, int d, int N, int k, int k0,
+                                   oea_dtype dt, float* logits, float* out_to_zero, uint32_t* counter,
+                                   RouteOut o, hipStream_t s);
+hipError_t launch_expert_gate_up(const void* x, const void* w_gate, const void* w_up, void* h, int B,
+                                 int d, int N, int I, int k, oea_dtype dt, Grouping g, hipStream_t s);
+hipError_t launch_expert_down(const void* h, const void* w_down, float* out, int B, int d, int N, int I,
+                              int k, oea_dtype dt, Grouping g, hipStream_t s);
+
+size_t route_lds_bytes(int B, int N);
+
+}  // namespace oea

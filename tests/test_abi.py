@@ -1,0 +1,116 @@
+"""The C-ABI library: loads, exports every declared symbol, host-side argument checks (no GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "oea.h")
+LIB = os.path.join(ROOT, "paper_2511_02237_amd", "liboea.so")
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(LIB):
+        from paper_2511_02237_amd import build
+        build.build(force=True)
+    lib = ctypes.CDLL(LIB)
+    vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    lib.oea_status_string.restype = ctypes.c_char_p
+    lib.oea_status_string.argtypes = [ci]
+    lib.oea_workspace_bytes.restype = sz
+    lib.oea_workspace_bytes.argtypes = [ci] * 5
+    lib.oea_workspace_init.argtypes = [vp, sz, vp]
+    lib.oea_route.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
+    lib.moe_decode.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp]
+    lib.moe_decode_ex.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp, vp]
+    return lib
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(\w+)\s*\([^;{}]*\)\s*;", text)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = declared_functions()
+    assert {"oea_route", "moe_decode", "moe_decode_ex", "oea_workspace_bytes", "oea_workspace_init",
+            "oea_status_string"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_status_strings(L):
+    seen = set()
+    for code in range(0, -8, -1):
+        s = L.oea_status_string(code).decode()
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 8
+    assert L.oea_status_string(-99).decode() == "unknown status"
+
+
+def test_workspace_bytes_is_pure_and_monotone(L):
+    a = L.oea_workspace_bytes(16, 2048, 128, 768, 8)
+    assert a == L.oea_workspace_bytes(16, 2048, 128, 768, 8)
+    # the hidden buffer B*k*I in the wider type must fit
+    assert a >= 16 * 8 * 768 * 4 + 16 * 128 * 4
+    assert a < 2 * 1024 * 1024
+    assert L.oea_workspace_bytes(32, 2048, 128, 768, 8) > a
+    assert a % 256 == 0
+    for bad in [(0, 2048, 128, 768, 8), (16, 2048, 0, 768, 8), (16, 2048, 128, 768, 0),
+                (16, 2048, 513, 768, 8), (16, 9000, 128, 768, 8), (2000, 2048, 128, 768, 8)]:
+        assert L.oea_workspace_bytes(*bad) == 0
+
+
+P = 0x10000  # fake, 16-byte aligned, never dereferenced: every check below fails before any enqueue
+
+
+def test_route_argument_checks(L):
+    ok = [P, 16, 128, 8, 3, P, P, P, P, P, None]
+    def call(**kw):
+        a = list(ok)
+        for i, v in kw.items():
+            a[int(i[1:])] = v
+        return L.oea_route(*a)
+    assert call(a0=None) == -1 and call(a5=None) == -1 and call(a9=None) == -1
+    assert call(a1=0) == -2 and call(a1=1025) == -2 and call(a2=0) == -2 and call(a2=513) == -2
+    assert call(a4=0) == -3 and call(a4=9) == -3 and call(a3=129) == -3 and call(a3=33, a4=33) == -3
+
+
+def test_decode_argument_checks(L):
+    big = 1 << 30
+    ok = [P, P, P, P, P, P, 16, 2048, 128, 768, 8, 3, 1, P, big, None]
+    def call(**kw):
+        a = list(ok)
+        for i, v in kw.items():
+            a[int(i[1:])] = v
+        return L.moe_decode(*a)
+    for i in (0, 1, 2, 3, 4, 5, 13):
+        assert call(**{"a%d" % i: None}) == -1
+    assert call(a6=0) == -2 and call(a7=2052) == -2 and call(a9=4) == -2 and call(a7=16384) == -2
+    assert call(a12=0, a7=8192) == -2  # fp32 rows: half the bf16 limit
+    assert call(a10=200) == -3 and call(a11=0) == -3 and call(a11=9) == -3
+    assert call(a12=7) == -6
+    for i in (0, 1, 2, 3, 4, 5, 13):
+        assert call(**{"a%d" % i: P + 2}) == -4
+    assert call(a14=1024) == -5
+    need = L.oea_workspace_bytes(16, 2048, 128, 768, 8)
+    assert call(a14=need - 1) == -5
+    # moe_decode_ex shares the checks
+    assert L.moe_decode_ex(*(ok[:14] + [16, None, None])) == -5
+
+
+def test_workspace_init_argument_checks(L):
+    assert L.oea_workspace_init(None, 1024, None) == -1
+    assert L.oea_workspace_init(P + 4, 1024, None) == -4
+    assert L.oea_workspace_init(P, 8, None) == -5
+
+
+def test_binding_module_names_match_the_abi():
+    from paper_2511_02237_amd import binding
+    assert set(binding.EXPORTS) == set(declared_functions())
+    for n in ("oea_route", "moe_decode", "workspace_bytes", "new_workspace", "status_string"):
+        assert hasattr(binding, n)

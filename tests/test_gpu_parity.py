@@ -1,0 +1,230 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bar: routing indices, counts and active lists bit-exact; gate weights |d| <= 1e-6; layer outputs
+max|d| / max|ref| <= 5e-3 for bf16 storage (fp32 accumulation; the hidden vector is rounded to bf16
+as a bf16 model does) and <= 2e-5 for fp32 storage.
+
+Routing is a function of the fp32 logits.  The library accumulates them in fp64 like the oracle, so
+they are expected to agree bit for bit; should a logit ever differ (summation order, last place),
+the test still requires (i) |d| within one fp32 ulp and (ii) routing identical to the oracle's
+routing OF THE LOGITS THE GPU USED, and compares the output under that routing.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2511_02237_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"bf16": 5e-3, "f32": 2e-5}
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as _t
+    assert _t.cuda.is_available(), "no GPU visible"
+    return _t
+
+
+@pytest.fixture(scope="module")
+def B_():
+    from paper_2511_02237_amd import binding
+    binding.lib()  # raises if the HIP library is missing
+    return binding
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def route_gpu(torch, B_, lg, k, k0):
+    res = B_.oea_route(torch.from_numpy(lg).cuda(), k, k0)
+    torch.cuda.synchronize()
+    return {n: v.cpu().numpy() for n, v in res.items()}
+
+
+def assert_routing_equal(got, ref, ctx):
+    assert int(got["n_active"][0] if np.ndim(got["n_active"]) else got["n_active"]) == ref["n_active"], ctx
+    assert np.array_equal(got["active_list"], ref["active_list"]), ctx
+    assert np.array_equal(got["n_sel"], ref["n_sel"]), ctx
+    assert np.array_equal(got["expert_idx"], ref["expert_idx"]), ctx
+    assert np.abs(got["gate_w"].astype(np.float64) - ref["gate_w"]).max() <= 1e-6, ctx
+
+
+ROUTE_CASES = [(B, N, k, k0, kind, seed)
+               for (B, N, k) in [(4, 16, 4), (16, 128, 8), (3, 7, 5), (33, 64, 6), (1, 128, 8), (128, 128, 8),
+                                 (16, 100, 8), (7, 200, 12), (5, 512, 32), (200, 130, 8), (16, 1, 1)]
+               for k0 in sorted({1, max(1, k // 2), k})
+               for kind in W.LOGIT_KINDS
+               for seed in (0, 1)]
+
+
+def test_route_bit_exact(torch, B_, oracle):
+    n = 0
+    for (B, N, k, k0, kind, seed) in ROUTE_CASES:
+        ctx = "route B=%d N=%d k=%d k0=%d kind=%s seed=%d" % (B, N, k, k0, kind, seed)
+        lg = W.make_logits(B, N, seed, kind)
+        got = route_gpu(torch, B_, lg, k, k0)
+        assert_routing_equal(got, oracle.route(lg, k, k0), ctx)
+        n += 1
+    say("route cases checked:", n)
+
+
+def test_route_many_seeds_qwen_shape(torch, B_, oracle):
+    for seed in range(64):
+        lg = W.make_logits(16, 128, 9000 + seed, "gaussian" if seed % 2 == 0 else "skew")
+        for k0 in (1, 3, 5, 8):
+            assert_routing_equal(route_gpu(torch, B_, lg, 8, k0), oracle.route(lg, 8, k0), "seed %d k0 %d" % (seed, k0))
+
+
+def test_route_non_finite_logits_stay_in_range(torch, B_):
+    lg = W.make_logits(16, 128, 5, "gaussian")
+    lg[0, :5] = np.nan
+    lg[1, 3] = np.inf
+    lg[2, :] = -np.inf
+    lg[3, :] = np.nan
+    got = route_gpu(torch, B_, lg, 8, 3)
+    idx = got["expert_idx"]
+    assert ((idx >= -1) & (idx < 128)).all()
+    T = int(got["n_active"][0])
+    assert 0 < T <= 128 and ((got["active_list"][:T] >= 0) & (got["active_list"][:T] < 128)).all()
+    assert (got["n_sel"] >= 0).all() and (got["n_sel"] <= 8).all()
+
+
+def run_layer(torch, B_, L, k0, ws=None, bias=None, mask=None):
+    dev = {f: B_.to_device(getattr(L, f)) for f in ("x", "w_router", "w_gate", "w_up", "w_down")}
+    return run_layer_dev(torch, B_, L, dev, k0, ws, bias, mask)
+
+
+def run_layer_dev(torch, B_, L, dev, k0, ws=None, bias=None, mask=None):
+    if ws is None:
+        ws = B_.new_workspace(L.B, L.d, L.N, L.I, L.k)
+    out, tap = B_.moe_decode(dev["x"], dev["w_router"], dev["w_gate"], dev["w_up"], dev["w_down"], L.k, k0, ws,
+                             router_bias=None if bias is None else torch.from_numpy(bias).cuda(),
+                             token_mask=None if mask is None else torch.from_numpy(mask).cuda(), taps=True)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), {n: v.cpu().numpy() for n, v in tap.items()}
+
+
+def check_layer(oracle, L, k0, out, tap, ctx, bias=None, mask=None):
+    ref = oracle.moe_decode(L.x, L.w_router, L.w_gate, L.w_up, L.w_down, L.k, k0, router_bias=bias,
+                            token_mask=mask)
+    lg_gpu, lg_ref = tap["logits"], ref["logits"]
+    same_bits = np.array_equal(lg_gpu.view(np.uint32), lg_ref.view(np.uint32))
+    if not same_bits:
+        ulp = np.spacing(np.abs(lg_ref))
+        assert (np.abs(lg_gpu.astype(np.float64) - lg_ref.astype(np.float64)) <= ulp).all(), ctx
+        say("note: %s: %d logits differ in the last place" % (ctx, int((lg_gpu != lg_ref).sum())))
+    # routing is exact as a function of the logits the GPU used
+    r_gpu_logits = oracle.route(lg_gpu, L.k, k0, token_mask=mask)
+    assert_routing_equal(tap, r_gpu_logits, ctx)
+    if same_bits or np.array_equal(r_gpu_logits["expert_idx"], ref["expert_idx"]):
+        ref_out = ref["out"]
+    else:  # a last-place logit difference flipped a near-tie: compare under the GPU's routing
+        ref_out = oracle.moe_combine(L.x, L.w_gate, L.w_up, L.w_down, r_gpu_logits["expert_idx"],
+                                     r_gpu_logits["gate_w"])
+    scale = np.abs(ref_out).max()
+    err = np.abs(out.astype(np.float64) - ref_out).max() / scale
+    assert np.isfinite(out).all(), ctx
+    assert err <= TOL[L.dtype], "%s: max|d|/max|ref| = %.3e" % (ctx, err)
+    return err, ref
+
+
+@pytest.mark.parametrize("name", ["toy", "mid_bf16", "mid_f32"])
+def test_small_layers_all_k0(torch, B_, oracle, name):
+    for seed in range(4):
+        L = W.make_layer(name, 100 + seed)
+        for k0 in L.k0s:
+            ctx = "%s seed=%d k0=%d" % (name, seed, k0)
+            out, tap = run_layer(torch, B_, L, k0)
+            err, _ = check_layer(oracle, L, k0, out, tap, ctx)
+            say(ctx, "T=%d err=%.2e" % (int(tap["n_active"][0]), err))
+
+
+@pytest.mark.parametrize("B", [1, 2, 5, 16, 33, 64])
+def test_batch_sizes_mid_shape(torch, B_, oracle, B):
+    L = W.make_layer("mid_bf16", 200 + B, B=B)
+    for k0 in (1, 3, 6):
+        out, tap = run_layer(torch, B_, L, k0)
+        check_layer(oracle, L, k0, out, tap, "mid_bf16 B=%d k0=%d" % (B, k0))
+
+
+def test_ragged_shapes(torch, B_, oracle):
+    # d, I multiples of 8 only: ragged last chunk in both stages; N not a multiple of 32 or 64
+    for (d, I, N, B, k, dtype) in [(8, 8, 3, 2, 2, "bf16"), (72, 24, 5, 3, 3, "bf16"), (136, 264, 9, 6, 4, "bf16"),
+                                   (24, 40, 7, 4, 3, "f32"), (1032, 520, 6, 3, 2, "bf16"), (2056, 8, 4, 2, 2, "bf16"),
+                                   (520, 1032, 6, 3, 2, "f32"),
+                                   # more tokens per expert than fit in LDS at once: several passes
+                                   (2048, 64, 4, 80, 2, "bf16"), (4096, 16, 2, 40, 2, "bf16")]:
+        L = W.make_layer("toy", 300, d=d, I=I, N=N, B=B, k=k, dtype=dtype)
+        for k0 in (1, k):
+            out, tap = run_layer(torch, B_, L, k0)
+            check_layer(oracle, L, k0, out, tap, "ragged d=%d I=%d N=%d B=%d k0=%d %s" % (d, I, N, B, k0, dtype))
+
+
+def test_bias_and_padding_mask(torch, B_, oracle):
+    L = W.make_layer("mid_bf16", 400, skew=True)
+    mask = np.ones(L.B, np.uint8)
+    mask[[1, 4, 10]] = 0
+    for k0 in (2, 4):
+        out, tap = run_layer(torch, B_, L, k0, bias=L.router_bias, mask=mask)
+        check_layer(oracle, L, k0, out, tap, "skew+mask k0=%d" % k0, bias=L.router_bias, mask=mask)
+        assert (out[[1, 4, 10]] == 0).all() and (tap["n_sel"][[1, 4, 10]] == 0).all()
+    # all tokens padded: nothing active, output zero
+    out, tap = run_layer(torch, B_, L, 2, mask=np.zeros(L.B, np.uint8))
+    assert int(tap["n_active"][0]) == 0 and (out == 0).all()
+
+
+def test_workspace_reuse_and_repeatability(torch, B_, oracle):
+    big = W.make_layer("mid_bf16", 500, B=16)
+    small = W.make_layer("toy", 501)
+    ws = B_.new_workspace(16, big.d, big.N, big.I, big.k)
+    o1, t1 = run_layer(torch, B_, big, 3, ws=ws)
+    o2, t2 = run_layer(torch, B_, small, 2, ws=ws)
+    o3, t3 = run_layer(torch, B_, big, 3, ws=ws)
+    check_layer(oracle, big, 3, o1, t1, "reuse 1")
+    check_layer(oracle, small, 2, o2, t2, "reuse 2")
+    check_layer(oracle, big, 3, o3, t3, "reuse 3")
+    assert np.array_equal(t1["expert_idx"], t3["expert_idx"]) and np.array_equal(t1["logits"], t3["logits"])
+    # the down projection accumulates with fp32 atomics: order may differ in the last places only
+    assert np.abs(o1 - o3).max() <= 1e-5 * np.abs(o1).max()
+
+
+@pytest.mark.parametrize("name,seeds", [("qwen3_30b", (0, 1)), ("qwen3_30b_skew", (0,))])
+def test_full_size_30b_shape(torch, B_, oracle, name, seeds):
+    """The configuration the benchmark times (B=16, d=2048, N=128, I=768, k=8), every output element."""
+    for seed in seeds:
+        L = W.make_layer(name, 2000 + seed)
+        dev = {f: B_.to_device(getattr(L, f)) for f in ("x", "w_router", "w_gate", "w_up", "w_down")}
+        ws = B_.new_workspace(L.B, L.d, L.N, L.I, L.k)
+        for k0 in ((1, 3, 5, 8) if name == "qwen3_30b" else L.k0s):
+            ctx = "%s seed=%d k0=%d" % (name, seed, k0)
+            out, tap = run_layer_dev(torch, B_, L, dev, k0, ws=ws, bias=L.router_bias)
+            err, ref = check_layer(oracle, L, k0, out, tap, ctx, bias=L.router_bias)
+            say(ctx, "T=%d sum_n_sel=%d err=%.2e" % (ref["n_active"], int(ref["n_sel"].sum()), err))
+
+
+def test_full_size_30b_batch_sweep(torch, B_, oracle):
+    L0 = W.make_layer("qwen3_30b", 2100, B=128)
+    dev_w = {f: B_.to_device(getattr(L0, f)) for f in ("w_router", "w_gate", "w_up", "w_down")}
+    for B in (1, 2, 8, 32, 64, 128):
+        L = W.Layer(**{**L0.__dict__, "B": B, "x": np.ascontiguousarray(L0.x[:B])})
+        dev = dict(dev_w, x=B_.to_device(L.x))
+        for k0 in ((3, 8) if B <= 32 else (3,)):
+            ctx = "30b-shape B=%d k0=%d" % (B, k0)
+            out, tap = run_layer_dev(torch, B_, L, dev, k0)
+            err, ref = check_layer(oracle, L, k0, out, tap, ctx)
+            say(ctx, "T=%d err=%.2e" % (ref["n_active"], err))
+
+
+def test_full_size_235b_shape(torch, B_, oracle):
+    L = W.make_layer("qwen3_235b", 3000)
+    dev = {f: B_.to_device(getattr(L, f)) for f in ("x", "w_router", "w_gate", "w_up", "w_down")}
+    for k0 in (3, 8):
+        ctx = "qwen3_235b k0=%d" % k0
+        out, tap = run_layer_dev(torch, B_, L, dev, k0)
+        err, ref = check_layer(oracle, L, k0, out, tap, ctx)
+        say(ctx, "T=%d err=%.2e" % (ref["n_active"], err))
