@@ -109,6 +109,9 @@ typedef struct {
   int32_t *n_sel_out;         /* [B]   */
   int32_t *active_list_out;   /* [N]   */
   int32_t *n_active_out;      /* [1]   */
+  void **h_kernel_events;     /* HOST array of 6 hipEvent_t (created by the caller): recorded on the
+                                 stream before/after the router+routing kernel [0],[1], the gate/up
+                                 kernel [2],[3] and the down kernel [4],[5].  Measurement aid. */
 } oea_decode_ex;
 
 /* moe_decode with the extras above (ex == NULL behaves as moe_decode). */

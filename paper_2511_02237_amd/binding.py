@@ -30,7 +30,8 @@ class DecodeEx(ctypes.Structure):
     _fields_ = [("router_bias", ctypes.c_void_p), ("token_mask", ctypes.c_void_p),
                 ("logits_out", ctypes.c_void_p), ("expert_idx_out", ctypes.c_void_p),
                 ("gate_w_out", ctypes.c_void_p), ("n_sel_out", ctypes.c_void_p),
-                ("active_list_out", ctypes.c_void_p), ("n_active_out", ctypes.c_void_p)]
+                ("active_list_out", ctypes.c_void_p), ("n_active_out", ctypes.c_void_p),
+                ("h_kernel_events", ctypes.POINTER(ctypes.c_void_p))]
 
 
 _lib = None
@@ -118,7 +119,7 @@ def oea_route(router_logits, k, k0, stream=None, out=None):
 
 
 def moe_decode(x, w_router, w_gate, w_up, w_down, k, k0, workspace, out=None, stream=None,
-               router_bias=None, token_mask=None, taps=False):
+               router_bias=None, token_mask=None, taps=False, kernel_events=None):
     """One decode-time MoE layer with OEA routing.  Returns out [B,d] float32 (and a dict of routing
     taps when taps=True)."""
     for t in (x, w_router, w_gate, w_up, w_down):
@@ -135,11 +136,13 @@ def moe_decode(x, w_router, w_gate, w_up, w_down, k, k0, workspace, out=None, st
         out = torch.empty((B, d), dtype=torch.float32, device=dev)
     args = [_ptr(x), _ptr(w_router), _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(out), B, d, N, I, int(k),
             int(k0), dt, _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)]
-    if not taps and router_bias is None and token_mask is None:
+    if not taps and router_bias is None and token_mask is None and kernel_events is None:
         _check(lib().moe_decode(*args))
         return out
     ex = DecodeEx()
     tap = None
+    if kernel_events is not None:  # ctypes array of 6 hipEvent_t handles
+        ex.h_kernel_events = ctypes.cast(kernel_events, ctypes.POINTER(ctypes.c_void_p))
     if router_bias is not None:
         assert router_bias.is_cuda and router_bias.dtype == torch.float32 and router_bias.numel() == N
         ex.router_bias = router_bias.data_ptr()

@@ -120,14 +120,18 @@ extern "C" int moe_decode_ex(const void* x, const void* W_router, const void* W_
   Grouping g{ro.active_list, ro.n_active, ro.grp_off, ro.grp_tok, ro.grp_gw};
   void* h = ws + w.h;
 
+  hipEvent_t* ev = ex && ex->h_kernel_events ? reinterpret_cast<hipEvent_t*>(ex->h_kernel_events) : nullptr;
+  auto mark = [&](int i) { return !ev || hipEventRecord(ev[i], s) == hipSuccess; };
+
+  if (!mark(0)) return OEA_ERR_HIP;
   hipError_t e = launch_router_and_route(x, W_router, ex ? ex->router_bias : nullptr,
                                          ex ? ex->token_mask : nullptr, B, d, N, k, k0, dt, logits, out,
                                          reinterpret_cast<uint32_t*>(ws + w.ctrl), ro, s);
-  if (e != hipSuccess) return OEA_ERR_HIP;
+  if (e != hipSuccess || !mark(1) || !mark(2)) return OEA_ERR_HIP;
   e = launch_expert_gate_up(x, W_gate, W_up, h, B, d, N, I, k, dt, g, s);
-  if (e != hipSuccess) return OEA_ERR_HIP;
+  if (e != hipSuccess || !mark(3) || !mark(4)) return OEA_ERR_HIP;
   e = launch_expert_down(h, W_down, out, B, d, N, I, k, dt, g, s);
-  if (e != hipSuccess) return OEA_ERR_HIP;
+  if (e != hipSuccess || !mark(5)) return OEA_ERR_HIP;
 
   if (ex) {  // taps: device-to-device copies in stream order
     const size_t P = (size_t)B * k;

@@ -257,18 +257,23 @@ __global__ __launch_bounds__(kRouteThreads) void router_route_kernel(
     }
   }
 
-  __threadfence();
+  // One device-scope release per workgroup (not per thread: each one writes back the L2): the barrier
+  // orders every wavefront's stores before thread 0's fence, the fence before the counter update.
   __syncthreads();
   if (tid == 0) {
+    __threadfence();
     uint32_t old = atomicAdd(counter, 1u);
-    lds[0] = (old == gridDim.x - 1) ? 1u : 0u;
+    const bool is_last = old == gridDim.x - 1;
+    if (is_last) {
+      __threadfence();          // acquire: the other workgroups' logits
+      atomicExch(counter, 0u);  // leave the control word zero for the next call
+    }
+    lds[0] = is_last ? 1u : 0u;
   }
   __syncthreads();
   const bool last = lds[0] != 0u;
   __syncthreads();
   if (!last) return;
-  __threadfence();
-  if (tid == 0) atomicExch(counter, 0u);  // leave the control word zero for the next call
   route_block<NV>(logits, token_mask, B, N, k, k0, o, lds);
 }
 
