@@ -98,6 +98,14 @@ int moe_decode(const void *x, const void *W_router, const void *W_gate, const vo
                const void *W_down, float *out, int B, int d, int N, int I, int k, int k0,
                oea_dtype dt, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Host.  Test aid: which expert-FFN kernels later moe_decode calls of this process use.
+ *   0 = automatic (streaming kernels when the staged token vectors fit in LDS, else generic)
+ *   1 = generic kernels only (any batch size; token vectors staged per expert, in passes)
+ * Returns OEA_OK, or OEA_ERR_SHAPE for another value.  Not thread-safe against running calls.
+ */
+int oea_set_kernel_path(int path);
+
 /* Optional inputs and taps for moe_decode_ex; every pointer may be NULL. */
 typedef struct {
   const float *router_bias;   /* [N] fp32 added to the logits (synthetic skewed-popularity workload) */

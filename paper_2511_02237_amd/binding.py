@@ -17,7 +17,7 @@ OEA_OK = 0
 STATUS = {"OEA_ERR_NULL": -1, "OEA_ERR_SHAPE": -2, "OEA_ERR_K": -3, "OEA_ERR_ALIGN": -4,
           "OEA_ERR_WORKSPACE": -5, "OEA_ERR_DTYPE": -6, "OEA_ERR_HIP": -7}
 EXPORTS = ("oea_status_string", "oea_workspace_bytes", "oea_workspace_init", "oea_route", "moe_decode",
-           "moe_decode_ex")
+           "moe_decode_ex", "oea_set_kernel_path")
 
 
 class OeaError(RuntimeError):
@@ -51,6 +51,8 @@ def lib():
         L.oea_workspace_bytes.argtypes = [ci] * 5
         L.oea_workspace_init.restype = ci
         L.oea_workspace_init.argtypes = [vp, sz, vp]
+        L.oea_set_kernel_path.restype = ci
+        L.oea_set_kernel_path.argtypes = [ci]
         L.oea_route.restype = ci
         L.oea_route.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
         L.moe_decode.restype = ci
@@ -85,6 +87,11 @@ def _dtype_code(t):
     if t.dtype == torch.bfloat16:
         return OEA_BF16
     raise TypeError("x and weights must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def set_kernel_path(path):
+    """0 = automatic, 1 = generic expert kernels only (test aid)."""
+    _check(lib().oea_set_kernel_path(int(path)))
 
 
 def workspace_bytes(B, d, N, I, k):

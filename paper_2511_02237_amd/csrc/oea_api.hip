@@ -78,6 +78,12 @@ extern "C" size_t oea_workspace_bytes(int B, int d, int N, int I, int k) {
   return ws_layout(B, d, N, I, k, 4).total;  // sized for the wider storage type
 }
 
+extern "C" int oea_set_kernel_path(int path) {
+  if (path != 0 && path != 1) return OEA_ERR_SHAPE;
+  set_force_generic(path == 1);
+  return OEA_OK;
+}
+
 extern "C" int oea_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
   if (!workspace) return OEA_ERR_NULL;
   if (!aligned16(workspace)) return OEA_ERR_ALIGN;

@@ -23,7 +23,9 @@ namespace {
 
 constexpr int kFfnThreads = 512;
 constexpr int kFfnWaves = kFfnThreads / 64;
-constexpr size_t kLdsBudget = 128 * 1024;  // bytes of LDS used for the staged token vectors
+constexpr size_t kLdsBudget = 128 * 1024;     // generic kernel: LDS bytes for the staged token vectors
+constexpr size_t kStreamLdsMax = 152 * 1024;  // streaming kernel: most LDS one workgroup may ask for
+bool g_force_generic = false;                 // test hook: route every call to the generic kernel
 
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
 
@@ -88,7 +90,8 @@ struct FfnParams {
   int N;
   int B;
   int pairs_max;     // B*k: size of the grouping arrays
-  int tok_cap;       // token vectors that fit in LDS at once
+  int tok_cap;       // generic kernel: token vectors that fit in LDS at once
+  int cap_vec;       // streaming kernel: capacity of the staged (expert, token) pair list
   Grouping g;
 };
 
@@ -214,6 +217,297 @@ __global__ __launch_bounds__(kFfnThreads) void expert_kernel(FfnParams p) {
   }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Streaming kernel: the fast path.  Same split of the work as above, but
+//   * the token vectors of ALL the (at most kMaxSeg) experts a workgroup touches are staged into
+//     LDS once, before the main loop, so the loop has no barrier;
+//   * every wavefront keeps two weight tiles in registers and always has the next tile's loads in
+//     flight while it computes on the current one (continuous HBM streaming).  The loads are
+//     unconditional (clamped to valid rows/columns, never predicated), so the compiler can count
+//     them and wait only for the older tile.
+// Stage 0 keeps x of the whole batch resident (indexed by token); stage 1 stages the hidden
+// vectors of its experts' pairs (contiguous in the grouped order).
+// FULL: the row length is exactly LPR*EPL*NCH (no ragged last chunk), so no column masks.
+constexpr int kMaxSeg = 3;
+
+// Per-wavefront description of the rows it streams.  All members are wave-uniform scalars; the
+// helpers take it BY VALUE and select between plain scalars only, so it never lives in memory.
+struct SegView {
+  int rows;              // weight rows per expert
+  int a0;                // position (in the active list) of the workgroup's first expert
+  int e0, e1, e2;        // expert ids of the (up to 3) segments
+  int cnt0, cnt1, cnt2;  // (expert, token) pairs per segment
+  int my_hi;             // end of this wavefront's rows (concatenated numbering)
+};
+
+struct TileRef {
+  int e;     // expert id
+  int rloc;  // first row inside the expert
+  int cnt;   // pairs of that expert
+  int vb;    // index of its first pair in the staged lists
+};
+
+__device__ __forceinline__ int seg_of(const SegView sv, int r) {
+  return (r >= (sv.a0 + 1) * sv.rows ? 1 : 0) + (r >= (sv.a0 + 2) * sv.rows ? 1 : 0);
+}
+
+// rows of the tile that starts at concatenated row r: at most trows, never across an expert boundary
+__device__ __forceinline__ int tile_rows(const SegView sv, int r, int trows) {
+  if (r >= sv.my_hi) return 0;
+  int lim = (sv.a0 + seg_of(sv, r) + 1) * sv.rows;
+  lim = lim < sv.my_hi ? lim : sv.my_hi;
+  const int n = lim - r;
+  return n < trows ? n : trows;
+}
+
+__device__ __forceinline__ TileRef tile_ref(const SegView sv, int r) {
+  const int s = seg_of(sv, r);
+  TileRef t;
+  t.e = s == 0 ? sv.e0 : (s == 1 ? sv.e1 : sv.e2);
+  t.cnt = s == 0 ? sv.cnt0 : (s == 1 ? sv.cnt1 : sv.cnt2);
+  t.vb = s == 0 ? 0 : (s == 1 ? sv.cnt0 : sv.cnt0 + sv.cnt1);
+  t.rloc = r - (sv.a0 + s) * sv.rows;
+  return t;
+}
+
+// Always issues NM*RG*NCH loads.  nrows >= 1; lanes of missing rows re-read the tile's last row,
+// columns past the end re-read the row's last granule (their products are masked in compute).
+template <typename WT, int NM, int LPR, int NCH, int RG, bool FULL>
+__device__ __forceinline__ void load_tile(uint4 (&w)[NM][RG][NCH], const WT* wa, const WT* wb, int rows, int L,
+                                          int lsub, int lrow, const TileRef t, int nrows) {
+  constexpr int EPL = 16 / int(sizeof(WT));
+  constexpr int R = 64 / LPR;
+  constexpr int CH = LPR * EPL;
+  const size_t ebase = (size_t)t.e * rows * L;
+#pragma unroll
+  for (int rg = 0; rg < RG; ++rg) {
+    int rr = rg * R + lrow;
+    rr = rr < nrows ? rr : nrows - 1;
+    const size_t rbase = ebase + (size_t)(t.rloc + rr) * L;
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+      int col = ch * CH + lsub * EPL;
+      if (!FULL) col = col < L ? col : L - EPL;
+#pragma unroll
+      for (int m = 0; m < NM; ++m)
+        w[m][rg][ch] = *reinterpret_cast<const uint4*>((m == 0 ? wa : wb) + rbase + col);
+    }
+  }
+}
+
+// one (expert, token) pair against the tile held in w: dot products, reduction over the row's lanes, epilogue
+template <typename WT, int STAGE, int NM, int LPR, int NCH, int RG, bool FULL>
+__device__ __forceinline__ void token_step(const uint4 (&w)[NM][RG][NCH], const int* l_tok, const float* l_gw,
+                                           const uint4* l_vec, WT* h_out, float* out, int rows, int L16, int off0,
+                                           int lsub, int lrow, int rloc, int nrows, int pair) {
+  constexpr int R = 64 / LPR;
+  const int tok = l_tok[pair];
+  const uint4* vq = l_vec + (size_t)(STAGE == 0 ? tok : pair) * L16;
+  uint4 v[NCH];
+#pragma unroll
+  for (int ch = 0; ch < NCH; ++ch) {
+    const int g16 = ch * LPR + lsub;
+    if (FULL) {
+      v[ch] = vq[g16];
+    } else {
+      const uint4 t4 = vq[g16 < L16 ? g16 : L16 - 1];
+      const uint32_t keep = g16 < L16 ? 0xffffffffu : 0u;  // a zero vector element kills the product
+      v[ch] = make_uint4(t4.x & keep, t4.y & keep, t4.z & keep, t4.w & keep);
+    }
+  }
+  float acc[NM][RG];
+#pragma unroll
+  for (int m = 0; m < NM; ++m)
+#pragma unroll
+    for (int rg = 0; rg < RG; ++rg) acc[m][rg] = 0.f;
+#pragma unroll
+  for (int ch = 0; ch < NCH; ++ch)
+#pragma unroll
+    for (int m = 0; m < NM; ++m)
+#pragma unroll
+      for (int rg = 0; rg < RG; ++rg) acc[m][rg] = frag_dot<WT>(w[m][rg][ch], v[ch], acc[m][rg]);
+#pragma unroll
+  for (int rg = 0; rg < RG; ++rg) {
+    const int rr = rg * R + lrow;
+    if (STAGE == 0) {
+      const float gsum = row_sum<LPR>(acc[0][rg]);
+      const float usum = row_sum<LPR>(acc[NM - 1][rg]);
+      if (lsub == 0 && rr < nrows) {
+        const float hval = gsum / (1.f + __expf(-gsum)) * usum;
+        store_h(h_out + (size_t)(off0 + pair) * rows + rloc + rr, hval);
+      }
+    } else {
+      const float y = row_sum<LPR>(acc[0][rg]);
+      if (lsub == 0 && rr < nrows) unsafeAtomicAdd(out + (size_t)tok * rows + rloc + rr, l_gw[pair] * y);
+    }
+  }
+}
+
+// The first kUnrollTok pairs of an expert are handled by straight-line code with forward branches
+// only.  A loop here would make the compiler drain ALL outstanding loads (also the prefetched
+// tile) in the loop pre-header, because the loop stores to memory; the loop form is kept for the
+// rare expert with more pairs than that.
+constexpr int kUnrollTok = 8;
+
+template <typename WT, int STAGE, int NM, int LPR, int NCH, int RG, bool FULL>
+__device__ __forceinline__ void compute_tile(const uint4 (&w)[NM][RG][NCH], const int* l_tok, const float* l_gw,
+                                             const uint4* l_vec, WT* h_out, float* out, int rows, int L16,
+                                             int off0, int lsub, int lrow, const TileRef t, int nrows) {
+#pragma unroll
+  for (int q = 0; q < kUnrollTok; ++q)
+    if (q < t.cnt)
+      token_step<WT, STAGE, NM, LPR, NCH, RG, FULL>(w, l_tok, l_gw, l_vec, h_out, out, rows, L16, off0, lsub, lrow,
+                                                    t.rloc, nrows, t.vb + q);
+  if (t.cnt > kUnrollTok)
+    for (int q = kUnrollTok; q < t.cnt; ++q)
+      token_step<WT, STAGE, NM, LPR, NCH, RG, FULL>(w, l_tok, l_gw, l_vec, h_out, out, rows, L16, off0, lsub, lrow,
+                                                    t.rloc, nrows, t.vb + q);
+}
+
+template <typename WT, int STAGE, int LPR, int NCH, int RG, bool FULL>
+__global__ __launch_bounds__(kFfnThreads) void expert_stream_kernel(FfnParams p) {
+  extern __shared__ uint4 lds4[];
+  constexpr int EPL = 16 / int(sizeof(WT));
+  constexpr int R = 64 / LPR;
+  constexpr int NM = STAGE == 0 ? 2 : 1;
+  constexpr int TROWS = RG * R;  // weight rows per tile
+
+  const int rows = p.rows, L = p.L, N = p.N;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: keeps the row bookkeeping scalar
+  const int lsub = lane % LPR, lrow = lane / LPR;
+  const int L16 = L / EPL;
+  const WT* const vec = static_cast<const WT*>(p.vec);
+
+  // Staging loads are issued as early as possible and in batches of kStageBatch per thread, all in
+  // flight together; they are written to LDS only after the first weight tiles have been requested.
+  constexpr int kStageBatch = 8;
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // a native vector: stays in registers
+  u32x4 stg[kStageBatch];
+  const int n16_x = p.B * L16;  // stage 0: x of the whole batch, needs no routing result
+  if (STAGE == 0) {
+    const u32x4* src = reinterpret_cast<const u32x4*>(vec);
+#pragma unroll
+    for (int j = 0; j < kStageBatch; ++j) {
+      const int i = j * kFfnThreads + tid;
+      stg[j] = src[i < n16_x ? i : n16_x - 1];
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);  // keep the staging loads up here, ahead of everything else
+
+  int T = *p.g.n_active;
+  T = T < 0 ? 0 : (T > N ? N : T);
+  const int total = T * rows;  // <= OEA_MAX_N * OEA_MAX_D: fits an int
+  const int R0 = int((long long)total * blockIdx.x / gridDim.x);
+  const int R1 = int((long long)total * (blockIdx.x + 1) / gridDim.x);
+  if (R0 >= R1) return;
+
+  // ---- the (at most kMaxSeg = 3) experts this workgroup touches: uniform scalar loads
+  const int a0 = R0 / rows;
+  const int nseg = (R1 - 1) / rows - a0 + 1;
+  const int off0 = p.g.grp_off[a0];
+  const int off1 = p.g.grp_off[a0 + 1];
+  const int off2 = nseg > 1 ? p.g.grp_off[a0 + 2] : off1;
+  const int off3 = nseg > 2 ? p.g.grp_off[a0 + 3] : off2;
+  const int e0 = p.g.active_list[a0];
+  const int e1 = nseg > 1 ? p.g.active_list[a0 + 1] : 0;
+  const int e2 = nseg > 2 ? p.g.active_list[a0 + 2] : 0;
+  const int nvec = off3 - off0;
+  // never true after a valid routing; keeps every access in bounds otherwise
+  if (nseg > kMaxSeg || off0 < 0 || off1 < off0 || off2 < off1 || off3 < off2 || nvec > p.cap_vec ||
+      off0 + nvec > p.pairs_max || (unsigned)e0 >= (unsigned)N || (unsigned)e1 >= (unsigned)N ||
+      (unsigned)e2 >= (unsigned)N)
+    return;
+
+  // LDS: [dump slot: 16 B][pair tokens: cap_vec int][pair weights: cap_vec float][vectors].
+  // The dump slot takes the writes of threads that have nothing to stage, so staging is branch-free
+  // and its loads stay where they are issued (ahead of the weight tiles).
+  int* l_tok = reinterpret_cast<int*>(lds4 + 1);
+  float* l_gw = reinterpret_cast<float*>(l_tok + p.cap_vec);
+  uint4* l_vec = lds4 + 1 + (p.cap_vec * 8 + 15) / 16;
+
+  // pair lists and (stage 1) the hidden vectors of this workgroup's pairs: first batch of loads
+  const int n16 = STAGE == 0 ? n16_x : nvec * L16;
+  const uint4* const vsrc = reinterpret_cast<const uint4*>(STAGE == 0 || nvec == 0 ? vec : vec + (size_t)off0 * L);
+  const int i_first = nvec == 0 ? 0 : (tid < nvec ? tid : nvec - 1);
+  const int src_first = off0 + i_first < p.pairs_max ? off0 + i_first : 0;
+  const int tok_first = p.g.grp_tok[src_first];
+  const float gw_first = p.g.grp_gw[src_first];
+  if (STAGE == 1) {
+#pragma unroll
+    for (int j = 0; j < kStageBatch; ++j) {
+      const int i16 = j * kFfnThreads + tid;
+      stg[j] = reinterpret_cast<const u32x4*>(vsrc)[i16 < n16 ? i16 : (n16 > 0 ? n16 - 1 : 0)];
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+
+  // this wavefront's equal share [my_lo, my_hi) of the workgroup's rows (concatenated numbering)
+  const int n_wg = R1 - R0;
+  const int my_lo = R0 + int((long long)n_wg * wave / kFfnWaves);
+  const int my_hi = R0 + int((long long)n_wg * (wave + 1) / kFfnWaves);
+  const bool has_work = my_lo < my_hi;
+
+  const SegView sv{rows, a0, e0, e1, e2, off1 - off0, off2 - off1, off3 - off2, my_hi};
+  const WT* const wa = static_cast<const WT*>(p.wa);
+  const WT* const wb = static_cast<const WT*>(p.wb);
+  WT* const h_out = static_cast<WT*>(p.h_out);
+  float* const out = p.out;
+
+  // ---- prologue: first two tiles in flight, then the staged data goes to LDS
+  uint4 wA[NM][RG][NCH], wB[NM][RG][NCH];
+  // r_first/n_first is also the dummy target of the prefetches past the end; a wavefront without rows
+  // (fewer rows than wavefronts) still issues its loads, on the workgroup's first row, and discards them:
+  // unconditional loads keep the compiler's count of outstanding loads exact.
+  const int r_first = has_work ? my_lo : R0;
+  const int n_first = has_work ? tile_rows(sv, my_lo, TROWS) : 1;
+  int rA = r_first, nA = has_work ? n_first : 0;
+  int rB = rA + nA, nB = tile_rows(sv, rB, TROWS);
+  load_tile<WT, NM, LPR, NCH, RG, FULL>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv, r_first), n_first);
+  load_tile<WT, NM, LPR, NCH, RG, FULL>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv, nB > 0 ? rB : r_first),
+                                        nB > 0 ? nB : n_first);
+
+  __builtin_amdgcn_sched_barrier(0);  // weight tiles are requested before the staged data is consumed
+  {
+    int* const dump_i = reinterpret_cast<int*>(lds4);
+    float* const dump_f = reinterpret_cast<float*>(lds4) + 1;
+    *(tid < nvec ? l_tok + tid : dump_i) = tok_first < 0 ? 0 : (tok_first >= p.B ? p.B - 1 : tok_first);
+    *(tid < nvec ? l_gw + tid : dump_f) = gw_first;
+#pragma unroll
+    for (int j = 0; j < kStageBatch; ++j) {
+      const int i16 = j * kFfnThreads + tid;
+      *reinterpret_cast<u32x4*>(i16 < n16 ? l_vec + i16 : lds4) = stg[j];
+    }
+  }
+  for (int i = tid + kFfnThreads; i < nvec; i += kFfnThreads) {  // only for very large batches
+    int t = p.g.grp_tok[off0 + i];
+    l_tok[i] = t < 0 ? 0 : (t >= p.B ? p.B - 1 : t);
+    l_gw[i] = p.g.grp_gw[off0 + i];
+  }
+  for (int i16 = kStageBatch * kFfnThreads + tid; i16 < n16; i16 += kFfnThreads) l_vec[i16] = vsrc[i16];
+  __syncthreads();
+  if (!has_work) return;
+
+  // ---- main loop: compute on one buffer while the other one's loads are in flight
+  while (true) {
+    compute_tile<WT, STAGE, NM, LPR, NCH, RG, FULL>(wA, l_tok, l_gw, l_vec, h_out, out, rows, L16, off0, lsub, lrow,
+                                                    tile_ref(sv, rA), nA);
+    rA = rB + nB;
+    nA = tile_rows(sv, rA, TROWS);
+    load_tile<WT, NM, LPR, NCH, RG, FULL>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv, nA > 0 ? rA : r_first),
+                                          nA > 0 ? nA : n_first);
+    if (nB <= 0) break;
+    compute_tile<WT, STAGE, NM, LPR, NCH, RG, FULL>(wB, l_tok, l_gw, l_vec, h_out, out, rows, L16, off0, lsub, lrow,
+                                                    tile_ref(sv, rB), nB);
+    rB = rA + nA;
+    nB = tile_rows(sv, rB, TROWS);
+    load_tile<WT, NM, LPR, NCH, RG, FULL>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv, nB > 0 ? rB : r_first),
+                                          nB > 0 ? nB : n_first);
+    if (nA <= 0) break;
+  }
+}
+
 int g_num_cus = 0;
 
 int num_cus() {
@@ -251,16 +545,72 @@ hipError_t launch_lpr(const FfnParams& p, size_t lds_bytes, hipStream_t s) {
   return hipErrorInvalidValue;
 }
 
+template <typename WT, int STAGE, int LPR, int NCH, int RG, bool FULL>
+hipError_t launch_stream_one(const FfnParams& p, size_t lds_bytes, hipStream_t s) {
+  auto kern = expert_stream_kernel<WT, STAGE, LPR, NCH, RG, FULL>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStreamLdsMax);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(num_cus()), dim3(kFfnThreads), lds_bytes, s, p);
+  return hipGetLastError();
+}
+
+template <typename WT, int STAGE, int LPR>
+hipError_t launch_stream_lpr(const FfnParams& p, size_t lds_bytes, hipStream_t s) {
+  constexpr int EPL = 16 / int(sizeof(WT));
+  constexpr int RG = STAGE == 0 ? 1 : 2;
+  if (p.L == LPR * EPL * 8) return launch_stream_one<WT, STAGE, LPR, 8, RG, true>(p, lds_bytes, s);
+  if (p.L == LPR * EPL * 6) return launch_stream_one<WT, STAGE, LPR, 6, RG, true>(p, lds_bytes, s);
+  return launch_stream_one<WT, STAGE, LPR, 8, RG, false>(p, lds_bytes, s);
+}
+
+// Streaming kernel if a row fits 8 chunks of some lanes-per-row and the staged vectors fit LDS.
+// Returns hipErrorNotSupported when the generic kernel has to be used.
 template <typename WT>
-hipError_t launch_stage(int stage, FfnParams p, int B, hipStream_t s) {
-  // LDS: as many token vectors as fit (at most B), at least one workgroup per CU alone on its CU
+hipError_t try_launch_stream(int stage, FfnParams p, int B, int k, hipStream_t s) {
+  constexpr int EPL = 16 / int(sizeof(WT));
+  const int grid = num_cus();
+  const int nseg_max = (p.N + grid - 1) / grid + 1;
+  if (nseg_max > kMaxSeg || p.L > 64 * EPL * 8) return hipErrorNotSupported;
+  long long cap_vec = (long long)nseg_max * B;
+  if (cap_vec > (long long)B * k) cap_vec = (long long)B * k;
+  const size_t list_bytes = 16 + (((size_t)cap_vec * 8 + 15) / 16) * 16;  // dump slot + pair lists
+  const size_t vec_bytes = (size_t)(stage == 0 ? B : cap_vec) * p.L * sizeof(WT);
+  size_t lds_bytes = list_bytes + vec_bytes;
+  if (lds_bytes > kStreamLdsMax) return hipErrorNotSupported;
+  const size_t alone = 84 * 1024;  // more than half of the CU's 160 KB: one workgroup per CU
+  if (lds_bytes < alone) lds_bytes = alone;
+  p.cap_vec = (int)cap_vec;
+  // fewest lanes per row (most rows per tile) that covers a row in at most 8 chunks
+  const int lpr = p.L <= 16 * EPL * 8 ? 16 : (p.L <= 32 * EPL * 8 ? 32 : 64);
+  if (stage == 0) {
+    if (lpr == 16) return launch_stream_lpr<WT, 0, 16>(p, lds_bytes, s);
+    if (lpr == 32) return launch_stream_lpr<WT, 0, 32>(p, lds_bytes, s);
+    return launch_stream_lpr<WT, 0, 64>(p, lds_bytes, s);
+  }
+  if (lpr == 16) return launch_stream_lpr<WT, 1, 16>(p, lds_bytes, s);
+  if (lpr == 32) return launch_stream_lpr<WT, 1, 32>(p, lds_bytes, s);
+  return launch_stream_lpr<WT, 1, 64>(p, lds_bytes, s);
+}
+
+template <typename WT>
+hipError_t launch_stage(int stage, FfnParams p, int B, int k, hipStream_t s) {
+  if (!g_force_generic) {
+    hipError_t e = try_launch_stream<WT>(stage, p, B, k, s);
+    if (e != hipErrorNotSupported) return e;
+  }
+  // generic kernel.  LDS: as many token vectors as fit (at most B), one workgroup per CU
   const size_t vec_bytes = (size_t)p.L * sizeof(WT);
   int cap = int(kLdsBudget / vec_bytes);
   if (cap < 1) return hipErrorInvalidValue;
   if (cap > B) cap = B;
   p.tok_cap = cap;
   size_t lds_bytes = (size_t)cap * vec_bytes;
-  const size_t alone = 84 * 1024;  // more than half of the CU's 160 KB: one workgroup per CU
+  const size_t alone = 84 * 1024;
   if (lds_bytes < alone) lds_bytes = alone;
   constexpr int EPL = 16 / int(sizeof(WT));
   if (stage == 0) return launch_lpr<WT, 0, 16, 1>(p, lds_bytes, s);
@@ -270,6 +620,8 @@ hipError_t launch_stage(int stage, FfnParams p, int B, hipStream_t s) {
 }
 
 }  // namespace
+
+void set_force_generic(bool on) { g_force_generic = on; }
 
 hipError_t launch_expert_gate_up(const void* x, const void* w_gate, const void* w_up, void* h, int B,
                                  int d, int N, int I, int k, oea_dtype dt, Grouping g, hipStream_t s) {
@@ -285,7 +637,7 @@ hipError_t launch_expert_gate_up(const void* x, const void* w_gate, const void* 
   p.L = d;
   p.N = N;
   p.g = g;
-  return dt == OEA_F32 ? launch_stage<float>(0, p, B, s) : launch_stage<uint16_t>(0, p, B, s);
+  return dt == OEA_F32 ? launch_stage<float>(0, p, B, k, s) : launch_stage<uint16_t>(0, p, B, k, s);
 }
 
 hipError_t launch_expert_down(const void* h, const void* w_down, float* out, int B, int d, int N, int I,
@@ -302,7 +654,7 @@ hipError_t launch_expert_down(const void* h, const void* w_down, float* out, int
   p.L = I;
   p.N = N;
   p.g = g;
-  return dt == OEA_F32 ? launch_stage<float>(1, p, B, s) : launch_stage<uint16_t>(1, p, B, s);
+  return dt == OEA_F32 ? launch_stage<float>(1, p, B, k, s) : launch_stage<uint16_t>(1, p, B, k, s);
 }
 
 }  // namespace oea

@@ -60,5 +60,6 @@ hipError_t launch_expert_down(const void* h, const void* w_down, float* out, int
                               int k, oea_dtype dt, Grouping g, hipStream_t s);
 
 size_t route_lds_bytes(int B, int N);
+void set_force_generic(bool on);
 
 }  // namespace oea

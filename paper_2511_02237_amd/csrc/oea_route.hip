@@ -35,13 +35,27 @@ __device__ __forceinline__ uint64_t make_key(float logit, uint32_t id) {
   return (uint64_t(orderable_bits(logit)) << 32) | uint64_t(0xffffffffu - id);
 }
 
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+  return uint32_t(__builtin_amdgcn_update_dpp(0, int(v), CTRL, 0xF, 0xF, true));
+}
+
+template <int CTRL>
+__device__ __forceinline__ uint64_t dpp_max_u64(uint64_t v) {
+  const uint64_t o = (uint64_t(dpp_u32<CTRL>(uint32_t(v >> 32))) << 32) | dpp_u32<CTRL>(uint32_t(v));
+  return o > v ? o : v;
+}
+
+// max over the 64 lanes, result in every lane: 4 DPP steps inside each row of 16, 2 cross-row steps
 __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    uint64_t o = __shfl_xor(v, off, 64);
-    v = o > v ? o : v;
-  }
-  return v;
+  v = dpp_max_u64<0xB1>(v);   // quad_perm [1,0,3,2]
+  v = dpp_max_u64<0x4E>(v);   // quad_perm [2,3,0,1]
+  v = dpp_max_u64<0x141>(v);  // row_half_mirror
+  v = dpp_max_u64<0x140>(v);  // row_mirror
+  uint64_t o = __shfl_xor(v, 16, 64);
+  v = o > v ? o : v;
+  o = __shfl_xor(v, 32, 64);
+  return o > v ? o : v;
 }
 
 __device__ __forceinline__ float wave_sum_f32(float v) {
@@ -66,59 +80,88 @@ __device__ __forceinline__ uint64_t pick_best(uint64_t (&key)[NV], int lane) {
   return best;
 }
 
-// Executed by ONE workgroup of kRouteThreads threads.  lds: see route_lds_bytes().
-template <int NV>
+// LDS words used by route_block
+__host__ __device__ inline size_t route_lds_words(int B, int N) {
+  return 64 + (size_t)N * ((B + 31) / 32) + (size_t)N;
+}
+
+// Executed by ONE workgroup of kRouteThreads threads.  lds: route_lds_words(B,N) words.
+// SINGLE: B <= kRouteWaves, one token per wavefront; its candidate keys stay in registers across
+// the barrier, so Phase 2 continues where Phase 1 stopped instead of starting over.
+template <int NV, bool SINGLE>
 __device__ void route_block(const float* __restrict__ logits, const uint8_t* __restrict__ token_mask,
                             int B, int N, int k, int k0, RouteOut o, uint32_t* lds) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int NW = (N + 31) >> 5;
-  uint32_t* U = lds;              // [16] union bit mask
-  uint32_t* scan = lds + 16;      // [48] scratch for block scans
-  uint32_t* selmask = lds + 64;   // [B*NW] per-token membership of the final sets
+  const int NWB = (B + 31) >> 5;
+  uint32_t* U = lds;                 // [16] union bit mask over experts
+  uint32_t* scan = lds + 16;         // [48] scratch for block scans
+  uint32_t* colmask = lds + 64;      // [N*NWB] per expert: bit mask of the tokens routed to it
+  uint32_t* eoff = colmask + N * NWB;  // [N] per expert: first pair in the grouped order
 
-  for (int i = tid; i < 64 + B * NW; i += kRouteThreads) lds[i] = 0;
+  for (int i = tid; i < int(route_lds_words(B, N)); i += kRouteThreads) lds[i] = 0;
   __syncthreads();
+
+  uint64_t keep[NV];  // SINGLE: this wavefront's keys after Phase 1
+  int my_id = -1;     // lane r holds the expert of rank r (SINGLE: filled from Phase 1 on)
+  float my_logit = 0.f;
+  int n_single = 0;
 
   // ---- pass 1: Phase 1 of Algorithm 1, S_i^base = k0 best experts; U = union over the batch
   for (int t = wave; t < B; t += kRouteWaves) {
-    if (token_mask && token_mask[t] == 0) continue;
+    const bool live = !(token_mask && token_mask[t] == 0);
     uint64_t key[NV];
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       int e = lane + 64 * j;
-      key[j] = e < N ? make_key(logits[(size_t)t * N + e], uint32_t(e)) : 0;
+      key[j] = (live && e < N) ? make_key(logits[(size_t)t * N + e], uint32_t(e)) : 0;
     }
     for (int r = 0; r < k0; ++r) {
       uint64_t best = pick_best<NV>(key, lane);
       if (best == 0) break;
       uint32_t id = 0xffffffffu - uint32_t(best);
       if (lane == 0) atomicOr(&U[id >> 5], 1u << (id & 31));
+      if (SINGLE) {
+        if (lane == r) {
+          my_id = int(id);
+          my_logit = from_orderable(uint32_t(best >> 32));
+        }
+        ++n_single;
+      }
+    }
+    if (SINGLE) {
+#pragma unroll
+      for (int j = 0; j < NV; ++j) keep[j] = key[j];
     }
   }
   __syncthreads();
 
-  // ---- pass 2: Phase 2 in closed form: top-k of the logits restricted to U, then weights
+  // ---- pass 2: Phase 2 in closed form: the token's best members of U up to k in all, then weights.
+  // Every Phase-1 pick is in U and outranks the rest, so SINGLE just continues on the kept keys.
   for (int t = wave; t < B; t += kRouteWaves) {
-    int n = 0;
-    int my_id = -1;
-    float my_logit = 0.f;
-    if (!(token_mask && token_mask[t] == 0)) {
-      uint64_t key[NV];
+    const bool live = !(token_mask && token_mask[t] == 0);
+    int n = SINGLE ? n_single : 0;
+    if (!SINGLE) {
+      my_id = -1;
+      my_logit = 0.f;
+    }
+    uint64_t key[NV];
 #pragma unroll
-      for (int j = 0; j < NV; ++j) {
-        int e = lane + 64 * j;
-        bool cand = e < N && ((U[e >> 5] >> (e & 31)) & 1u);
+    for (int j = 0; j < NV; ++j) {
+      int e = lane + 64 * j;
+      bool cand = live && e < N && ((U[e >> 5] >> (e & 31)) & 1u);
+      if (SINGLE)
+        key[j] = cand ? keep[j] : 0;
+      else
         key[j] = cand ? make_key(logits[(size_t)t * N + e], uint32_t(e)) : 0;
+    }
+    for (int r = n; r < k; ++r) {
+      uint64_t best = pick_best<NV>(key, lane);
+      if (best == 0) break;
+      if (lane == r) {
+        my_id = int(0xffffffffu - uint32_t(best));
+        my_logit = from_orderable(uint32_t(best >> 32));
       }
-      for (int r = 0; r < k; ++r) {
-        uint64_t best = pick_best<NV>(key, lane);
-        if (best == 0) break;
-        if (lane == r) {
-          my_id = int(0xffffffffu - uint32_t(best));
-          my_logit = from_orderable(uint32_t(best >> 32));
-        }
-        ++n;
-      }
+      ++n;
     }
     // g_s = exp(l_s - m) / sum_{s'} exp(l_s' - m): the softmax denominator cancels in Eq. 1
     float m = __shfl(my_logit, 0, 64);
@@ -128,21 +171,20 @@ __device__ void route_block(const float* __restrict__ logits, const uint8_t* __r
       o.expert_idx[(size_t)t * k + lane] = lane < n ? my_id : -1;
       o.gate_w[(size_t)t * k + lane] = lane < n ? w / z : 0.f;
     }
-    if (lane < n) atomicOr(&selmask[t * NW + (my_id >> 5)], 1u << (my_id & 31));
+    if (lane < n) atomicOr(&colmask[my_id * NWB + (t >> 5)], 1u << (t & 31));
     if (lane == 0) o.n_sel[t] = n;
   }
   __syncthreads();
 
-  // ---- pass 3: active list (ascending ids) and expert -> token grouping
+  // ---- pass 3a: active list (ascending ids), pairs per expert, CSR offsets
   const int e = tid;
   const bool in_u = e < N && ((U[e >> 5] >> (e & 31)) & 1u);
   uint64_t ballot = __ballot(in_u);
   if (lane == 0) scan[wave] = uint32_t(__popcll(ballot));
   int cnt = 0;
   if (in_u)
-    for (int t = 0; t < B; ++t) cnt += int((selmask[t * NW + (e >> 5)] >> (e & 31)) & 1u);
-  // inclusive scan of cnt inside the wave
-  int incl = cnt;
+    for (int w = 0; w < NWB; ++w) cnt += __popc(colmask[e * NWB + w]);
+  int incl = cnt;  // inclusive scan of cnt inside the wave
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
     int v = __shfl_up(incl, off, 64);
@@ -165,22 +207,24 @@ __device__ void route_block(const float* __restrict__ logits, const uint8_t* __r
   if (in_u) o.active_list[pos] = e;
   if (e < N && e >= T) o.active_list[e] = -1;
   if (tid == 0) *o.n_active = T;
-  if (o.grp_off) {
-    if (in_u) {
-      o.grp_off[pos] = excl;
-      int p = excl;
-      for (int t = 0; t < B; ++t) {
-        if ((selmask[t * NW + (e >> 5)] >> (e & 31)) & 1u) {
-          float g = 0.f;
-          for (int s = 0; s < k; ++s)
-            if (o.expert_idx[(size_t)t * k + s] == e) g = o.gate_w[(size_t)t * k + s];
-          o.grp_tok[p] = t;
-          o.grp_gw[p] = g;
-          ++p;
-        }
-      }
-    }
-    if (tid == 0) o.grp_off[T] = P;
+  if (!o.grp_off) return;
+  if (in_u) {
+    o.grp_off[pos] = excl;
+    eoff[e] = uint32_t(excl);
+  }
+  if (tid == 0) o.grp_off[T] = P;
+  __syncthreads();
+
+  // ---- pass 3b: one thread per (token, slot) pair; inside an expert, pairs are in token order
+  for (int p = tid; p < B * k; p += kRouteThreads) {
+    const int ex = o.expert_idx[p];
+    if (ex < 0) continue;
+    const int t = p / k;
+    int rank = __popc(colmask[ex * NWB + (t >> 5)] & ((1u << (t & 31)) - 1u));
+    for (int w = 0; w < (t >> 5); ++w) rank += __popc(colmask[ex * NWB + w]);
+    const int dst = int(eoff[ex]) + rank;
+    o.grp_tok[dst] = t;
+    o.grp_gw[dst] = o.gate_w[p];
   }
 }
 
@@ -188,7 +232,10 @@ template <int NV>
 __global__ __launch_bounds__(kRouteThreads) void route_kernel(const float* logits, const uint8_t* token_mask,
                                                               int B, int N, int k, int k0, RouteOut o) {
   extern __shared__ uint32_t lds[];
-  route_block<NV>(logits, token_mask, B, N, k, k0, o, lds);
+  if (B <= kRouteWaves)
+    route_block<NV, true>(logits, token_mask, B, N, k, k0, o, lds);
+  else
+    route_block<NV, false>(logits, token_mask, B, N, k, k0, o, lds);
 }
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
@@ -274,7 +321,10 @@ __global__ __launch_bounds__(kRouteThreads) void router_route_kernel(
   const bool last = lds[0] != 0u;
   __syncthreads();
   if (!last) return;
-  route_block<NV>(logits, token_mask, B, N, k, k0, o, lds);
+  if (B <= kRouteWaves)
+    route_block<NV, true>(logits, token_mask, B, N, k, k0, o, lds);
+  else
+    route_block<NV, false>(logits, token_mask, B, N, k, k0, o, lds);
 }
 
 __global__ void fill_zero_kernel(uint32_t* p, size_t n) {
@@ -289,7 +339,7 @@ int nv_for(int N) {
 
 }  // namespace
 
-size_t route_lds_bytes(int B, int N) { return sizeof(uint32_t) * (64 + (size_t)B * ((N + 31) / 32)); }
+size_t route_lds_bytes(int B, int N) { return sizeof(uint32_t) * route_lds_words(B, N); }
 
 hipError_t launch_fill_zero(uint32_t* p, size_t n_words, hipStream_t s) {
   if (n_words == 0) return hipSuccess;

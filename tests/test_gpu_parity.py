@@ -158,11 +158,34 @@ def test_ragged_shapes(torch, B_, oracle):
                                    (24, 40, 7, 4, 3, "f32"), (1032, 520, 6, 3, 2, "bf16"), (2056, 8, 4, 2, 2, "bf16"),
                                    (520, 1032, 6, 3, 2, "f32"),
                                    # more tokens per expert than fit in LDS at once: several passes
-                                   (2048, 64, 4, 80, 2, "bf16"), (4096, 16, 2, 40, 2, "bf16")]:
+                                   (2048, 64, 4, 80, 2, "bf16"), (4096, 16, 2, 40, 2, "bf16"),
+                                   # exact 6- and 8-chunk rows at every lanes-per-row, more pairs than the unrolled 8
+                                   (768, 1024, 3, 12, 3, "bf16"), (1536, 2048, 3, 12, 3, "bf16"),
+                                   (3072, 4096, 2, 9, 2, "bf16"), (4096, 3072, 2, 3, 2, "bf16"),
+                                   (5000, 4104, 2, 3, 2, "bf16"), (384, 512, 3, 5, 2, "f32"), (2048, 1024, 2, 3, 2, "f32")]:
         L = W.make_layer("toy", 300, d=d, I=I, N=N, B=B, k=k, dtype=dtype)
         for k0 in (1, k):
             out, tap = run_layer(torch, B_, L, k0)
             check_layer(oracle, L, k0, out, tap, "ragged d=%d I=%d N=%d B=%d k0=%d %s" % (d, I, N, B, k0, dtype))
+
+
+def test_generic_kernel_path(torch, B_, oracle):
+    """The generic expert kernels (used when the staged token vectors do not fit in LDS) on shapes the
+    automatic choice would give to the streaming kernels."""
+    B_.set_kernel_path(1)
+    try:
+        for name, seed in (("toy", 600), ("mid_bf16", 601), ("mid_f32", 602)):
+            L = W.make_layer(name, seed)
+            for k0 in L.k0s:
+                out, tap = run_layer(torch, B_, L, k0)
+                check_layer(oracle, L, k0, out, tap, "generic %s k0=%d" % (name, k0))
+        for (d, I, N, B, k, dtype) in [(72, 24, 5, 3, 3, "bf16"), (1032, 520, 6, 3, 2, "bf16"), (2056, 8, 4, 2, 2, "bf16"),
+                                       (2048, 64, 4, 80, 2, "bf16")]:
+            L = W.make_layer("toy", 603, d=d, I=I, N=N, B=B, k=k, dtype=dtype)
+            out, tap = run_layer(torch, B_, L, 1)
+            check_layer(oracle, L, 1, out, tap, "generic ragged d=%d I=%d" % (d, I))
+    finally:
+        B_.set_kernel_path(0)
 
 
 def test_bias_and_padding_mask(torch, B_, oracle):
