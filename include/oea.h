@@ -89,6 +89,10 @@ int oea_route(const float *router_logits, int B, int N, int k, int k0, int32_t *
  *   workspace         device scratch of >= oea_workspace_bytes(B,d,N,I,k) bytes, 16-byte aligned,
  *                     prepared once by oea_workspace_init.  Two calls that share a workspace must
  *                     be ordered on the same stream.
+ * For the Qwen3-30B-A3B and Qwen3-235B-A22B layer shapes (bf16, N <= 128, B <= 32) the whole layer
+ * runs as ONE persistent kernel with one workgroup per compute unit and two grid-wide barriers; it
+ * expects the device to itself while it runs (a workgroup that cannot be placed delays the others;
+ * the barrier wait is bounded, after about a second the call gives up and its output is undefined).
  * Arithmetic: router logits are accumulated in fp64 and rounded once to fp32; expert mat-vecs
  * multiply in the storage type and accumulate in fp32; with bf16 storage the hidden vector is
  * rounded to bf16 between the two mat-vecs (as a bf16 model does).
@@ -100,8 +104,10 @@ int moe_decode(const void *x, const void *W_router, const void *W_gate, const vo
 
 /*
  * Host.  Test aid: which expert-FFN kernels later moe_decode calls of this process use.
- *   0 = automatic (streaming kernels when the staged token vectors fit in LDS, else generic)
- *   1 = generic kernels only (any batch size; token vectors staged per expert, in passes)
+ *   0 = automatic: the single fused kernel for the shapes it is built for, else three kernels
+ *       (streaming expert kernels when the staged token vectors fit in LDS, else generic ones)
+ *   1 = three kernels, generic expert kernels only (any batch size; vectors staged per expert)
+ *   2 = three kernels, automatic choice between streaming and generic expert kernels
  * Returns OEA_OK, or OEA_ERR_SHAPE for another value.  Not thread-safe against running calls.
  */
 int oea_set_kernel_path(int path);

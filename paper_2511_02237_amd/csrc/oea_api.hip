@@ -6,6 +6,7 @@
 namespace oea {
 
 static size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
+static constexpr size_t kCtrlWords = 1024;  // control words at the start of a workspace (zeroed by init)
 
 WsLayout ws_layout(int B, int d, int N, int I, int k, int elem_bytes) {
   (void)d;
@@ -17,7 +18,7 @@ WsLayout ws_layout(int B, int d, int N, int I, int k, int elem_bytes) {
     return at;
   };
   const size_t P = (size_t)B * k;
-  w.ctrl = take(64 * sizeof(uint32_t));
+  w.ctrl = take(kCtrlWords * sizeof(uint32_t));
   w.logits = take((size_t)B * N * sizeof(float));
   w.expert_idx = take(P * sizeof(int32_t));
   w.gate_w = take(P * sizeof(float));
@@ -78,8 +79,11 @@ extern "C" size_t oea_workspace_bytes(int B, int d, int N, int I, int k) {
   return ws_layout(B, d, N, I, k, 4).total;  // sized for the wider storage type
 }
 
+static int g_kernel_path = 0;
+
 extern "C" int oea_set_kernel_path(int path) {
-  if (path != 0 && path != 1) return OEA_ERR_SHAPE;
+  if (path < 0 || path > 2) return OEA_ERR_SHAPE;
+  g_kernel_path = path;
   set_force_generic(path == 1);
   return OEA_OK;
 }
@@ -87,8 +91,9 @@ extern "C" int oea_set_kernel_path(int path) {
 extern "C" int oea_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
   if (!workspace) return OEA_ERR_NULL;
   if (!aligned16(workspace)) return OEA_ERR_ALIGN;
-  if (workspace_bytes < 64 * sizeof(uint32_t)) return OEA_ERR_WORKSPACE;
-  hipError_t e = launch_fill_zero(static_cast<uint32_t*>(workspace), 64, static_cast<hipStream_t>(stream));
+  if (workspace_bytes < oea::kCtrlWords * sizeof(uint32_t)) return OEA_ERR_WORKSPACE;
+  hipError_t e =
+      launch_fill_zero(static_cast<uint32_t*>(workspace), oea::kCtrlWords, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? OEA_OK : OEA_ERR_HIP;
 }
 
@@ -130,14 +135,25 @@ extern "C" int moe_decode_ex(const void* x, const void* W_router, const void* W_
   auto mark = [&](int i) { return !ev || hipEventRecord(ev[i], s) == hipSuccess; };
 
   if (!mark(0)) return OEA_ERR_HIP;
-  hipError_t e = launch_router_and_route(x, W_router, ex ? ex->router_bias : nullptr,
-                                         ex ? ex->token_mask : nullptr, B, d, N, k, k0, dt, logits, out,
-                                         reinterpret_cast<uint32_t*>(ws + w.ctrl), ro, s);
-  if (e != hipSuccess || !mark(1) || !mark(2)) return OEA_ERR_HIP;
-  e = launch_expert_gate_up(x, W_gate, W_up, h, B, d, N, I, k, dt, g, s);
-  if (e != hipSuccess || !mark(3) || !mark(4)) return OEA_ERR_HIP;
-  e = launch_expert_down(h, W_down, out, B, d, N, I, k, dt, g, s);
-  if (e != hipSuccess || !mark(5)) return OEA_ERR_HIP;
+  hipError_t e = hipErrorNotSupported;
+  if (g_kernel_path == 0)
+    e = try_launch_fused(x, W_router, W_gate, W_up, W_down, ex ? ex->router_bias : nullptr,
+                         ex ? ex->token_mask : nullptr, out, logits, h, ro,
+                         reinterpret_cast<uint32_t*>(ws + w.ctrl), B, d, N, I, k, k0, dt, s);
+  if (e == hipSuccess) {  // one kernel: the inner event pairs collapse onto its end
+    for (int i = 1; i < 6; ++i)
+      if (!mark(i)) return OEA_ERR_HIP;
+  } else if (e != hipErrorNotSupported) {
+    return OEA_ERR_HIP;
+  } else {
+    e = launch_router_and_route(x, W_router, ex ? ex->router_bias : nullptr, ex ? ex->token_mask : nullptr, B, d,
+                                N, k, k0, dt, logits, out, reinterpret_cast<uint32_t*>(ws + w.ctrl), ro, s);
+    if (e != hipSuccess || !mark(1) || !mark(2)) return OEA_ERR_HIP;
+    e = launch_expert_gate_up(x, W_gate, W_up, h, B, d, N, I, k, dt, g, s);
+    if (e != hipSuccess || !mark(3) || !mark(4)) return OEA_ERR_HIP;
+    e = launch_expert_down(h, W_down, out, B, d, N, I, k, dt, g, s);
+    if (e != hipSuccess || !mark(5)) return OEA_ERR_HIP;
+  }
 
   if (ex) {  // taps: device-to-device copies in stream order
     const size_t P = (size_t)B * k;

@@ -1,0 +1,215 @@
+// Device-side building blocks of the expert mat-vec stages, shared by the streaming kernels and
+// the fused layer kernel (gfx950): 16-byte fragment dot products, lane reductions, and the
+// register-tile load / compute helpers of the streaming design.
+#pragma once
+#include "oea_internal.h"
+
+#include <hip/amd_detail/amd_hip_unsafe_atomics.h>
+
+namespace oea {
+namespace {
+
+constexpr int kFfnThreads = 512;
+constexpr int kFfnWaves = kFfnThreads / 64;
+
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __builtin_bit_cast(
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+
+// sum over the LPR consecutive lanes that share one weight row; every lane gets the total
+template <int LPR>
+__device__ __forceinline__ float row_sum(float v) {
+  v += dpp_move<0xB1>(v);   // quad_perm [1,0,3,2]
+  v += dpp_move<0x4E>(v);   // quad_perm [2,3,0,1]
+  v += dpp_move<0x141>(v);  // row_half_mirror
+  v += dpp_move<0x140>(v);  // row_mirror
+  if (LPR >= 32) v += __shfl_xor(v, 16, 64);
+  if (LPR >= 64) v += __shfl_xor(v, 32, 64);
+  return v;
+}
+
+template <typename WT>
+__device__ __forceinline__ float frag_dot(const uint4& w, const uint4& v, float acc);
+
+template <>
+__device__ __forceinline__ float frag_dot<float>(const uint4& w, const uint4& v, float acc) {
+  acc = fmaf(__uint_as_float(w.x), __uint_as_float(v.x), acc);
+  acc = fmaf(__uint_as_float(w.y), __uint_as_float(v.y), acc);
+  acc = fmaf(__uint_as_float(w.z), __uint_as_float(v.z), acc);
+  acc = fmaf(__uint_as_float(w.w), __uint_as_float(v.w), acc);
+  return acc;
+}
+
+template <>
+__device__ __forceinline__ float frag_dot<uint16_t>(const uint4& w, const uint4& v, float acc) {
+  // v_dot2c_f32_bf16: acc += w.lo*v.lo + w.hi*v.hi with fp32 accumulation
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.x), __builtin_bit_cast(bf16x2_t, v.x), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.y), __builtin_bit_cast(bf16x2_t, v.y), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.z), __builtin_bit_cast(bf16x2_t, v.z), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.w), __builtin_bit_cast(bf16x2_t, v.w), acc, false);
+  return acc;
+}
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7f800000u) == 0x7f800000u) return uint16_t((u >> 16) | ((u & 0xffffu) ? 0x40u : 0u));  // inf/nan
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return uint16_t(u >> 16);
+}
+
+__device__ __forceinline__ void store_h(float* p, float v) { *p = v; }
+__device__ __forceinline__ void store_h(uint16_t* p, float v) { *p = f32_to_bf16_rne(v); }
+// device-coherent variants: written through to memory, no dirty line stays in this XCD's L2, so
+// workgroups on other XCDs can read the value after a grid barrier without cache maintenance
+__device__ __forceinline__ void store_h_coherent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_h_coherent(uint16_t* p, float v) {
+  __hip_atomic_store(p, f32_to_bf16_rne(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+constexpr int kMaxSeg = 3;
+
+// Per-wavefront description of the rows it streams.  All members are wave-uniform scalars; the
+// helpers take it BY VALUE and select between plain scalars only, so it never lives in memory.
+struct SegView {
+  int rows;              // weight rows per expert
+  int a0;                // position (in the active list) of the workgroup's first expert
+  int e0, e1, e2;        // expert ids of the (up to 3) segments
+  int cnt0, cnt1, cnt2;  // (expert, token) pairs per segment
+  int my_hi;             // end of this wavefront's rows (concatenated numbering)
+};
+
+struct TileRef {
+  int e;     // expert id
+  int rloc;  // first row inside the expert
+  int cnt;   // pairs of that expert
+  int vb;    // index of its first pair in the staged lists
+};
+
+__device__ __forceinline__ int seg_of(const SegView sv, int r) {
+  return (r >= (sv.a0 + 1) * sv.rows ? 1 : 0) + (r >= (sv.a0 + 2) * sv.rows ? 1 : 0);
+}
+
+// rows of the tile that starts at concatenated row r: at most trows, never across an expert boundary
+__device__ __forceinline__ int tile_rows(const SegView sv, int r, int trows) {
+  if (r >= sv.my_hi) return 0;
+  int lim = (sv.a0 + seg_of(sv, r) + 1) * sv.rows;
+  lim = lim < sv.my_hi ? lim : sv.my_hi;
+  const int n = lim - r;
+  return n < trows ? n : trows;
+}
+
+__device__ __forceinline__ TileRef tile_ref(const SegView sv, int r) {
+  const int s = seg_of(sv, r);
+  TileRef t;
+  t.e = s == 0 ? sv.e0 : (s == 1 ? sv.e1 : sv.e2);
+  t.cnt = s == 0 ? sv.cnt0 : (s == 1 ? sv.cnt1 : sv.cnt2);
+  t.vb = s == 0 ? 0 : (s == 1 ? sv.cnt0 : sv.cnt0 + sv.cnt1);
+  t.rloc = r - (sv.a0 + s) * sv.rows;
+  return t;
+}
+
+// Always issues NM*RG*NCH loads.  nrows >= 1; lanes of missing rows re-read the tile's last row,
+// columns past the end re-read the row's last granule (their products are masked in compute).
+template <typename WT, int NM, int LPR, int NCH, int RG, bool FULL>
+__device__ __forceinline__ void load_tile(uint4 (&w)[NM][RG][NCH], const WT* wa, const WT* wb, int rows, int L,
+                                          int lsub, int lrow, const TileRef t, int nrows) {
+  constexpr int EPL = 16 / int(sizeof(WT));
+  constexpr int R = 64 / LPR;
+  constexpr int CH = LPR * EPL;
+  const size_t ebase = (size_t)t.e * rows * L;
+#pragma unroll
+  for (int rg = 0; rg < RG; ++rg) {
+    int rr = rg * R + lrow;
+    rr = rr < nrows ? rr : nrows - 1;
+    const size_t rbase = ebase + (size_t)(t.rloc + rr) * L;
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+      int col = ch * CH + lsub * EPL;
+      if (!FULL) col = col < L ? col : L - EPL;
+#pragma unroll
+      for (int m = 0; m < NM; ++m)
+        w[m][rg][ch] = *reinterpret_cast<const uint4*>((m == 0 ? wa : wb) + rbase + col);
+    }
+  }
+}
+
+// one (expert, token) pair against the tile held in w: dot products, reduction over the row's lanes, epilogue
+template <typename WT, int STAGE, int NM, int LPR, int NCH, int RG, bool FULL, bool COH = false>
+__device__ __forceinline__ void token_step(const uint4 (&w)[NM][RG][NCH], const int* l_tok, const float* l_gw,
+                                           const uint4* l_vec, WT* h_out, float* out, int rows, int L16, int off0,
+                                           int lsub, int lrow, int rloc, int nrows, int pair) {
+  constexpr int R = 64 / LPR;
+  const int tok = l_tok[pair];
+  const uint4* vq = l_vec + (size_t)(STAGE == 0 ? tok : pair) * L16;
+  uint4 v[NCH];
+#pragma unroll
+  for (int ch = 0; ch < NCH; ++ch) {
+    const int g16 = ch * LPR + lsub;
+    if (FULL) {
+      v[ch] = vq[g16];
+    } else {
+      const uint4 t4 = vq[g16 < L16 ? g16 : L16 - 1];
+      const uint32_t keep = g16 < L16 ? 0xffffffffu : 0u;  // a zero vector element kills the product
+      v[ch] = make_uint4(t4.x & keep, t4.y & keep, t4.z & keep, t4.w & keep);
+    }
+  }
+  float acc[NM][RG];
+#pragma unroll
+  for (int m = 0; m < NM; ++m)
+#pragma unroll
+    for (int rg = 0; rg < RG; ++rg) acc[m][rg] = 0.f;
+#pragma unroll
+  for (int ch = 0; ch < NCH; ++ch)
+#pragma unroll
+    for (int m = 0; m < NM; ++m)
+#pragma unroll
+      for (int rg = 0; rg < RG; ++rg) acc[m][rg] = frag_dot<WT>(w[m][rg][ch], v[ch], acc[m][rg]);
+#pragma unroll
+  for (int rg = 0; rg < RG; ++rg) {
+    const int rr = rg * R + lrow;
+    if (STAGE == 0) {
+      const float gsum = row_sum<LPR>(acc[0][rg]);
+      const float usum = row_sum<LPR>(acc[NM - 1][rg]);
+      if (lsub == 0 && rr < nrows) {
+        const float hval = gsum / (1.f + __expf(-gsum)) * usum;
+        if (COH)
+          store_h_coherent(h_out + (size_t)(off0 + pair) * rows + rloc + rr, hval);
+        else
+          store_h(h_out + (size_t)(off0 + pair) * rows + rloc + rr, hval);
+      }
+    } else {
+      const float y = row_sum<LPR>(acc[0][rg]);
+      if (lsub == 0 && rr < nrows) unsafeAtomicAdd(out + (size_t)tok * rows + rloc + rr, l_gw[pair] * y);
+    }
+  }
+}
+
+// The first kUnrollTok pairs of an expert are handled by straight-line code with forward branches
+// only.  A loop here would make the compiler drain ALL outstanding loads (also the prefetched
+// tile) in the loop pre-header, because the loop stores to memory; the loop form is kept for the
+// rare expert with more pairs than that.
+constexpr int kUnrollTok = 8;
+
+template <typename WT, int STAGE, int NM, int LPR, int NCH, int RG, bool FULL, bool COH = false>
+__device__ __forceinline__ void compute_tile(const uint4 (&w)[NM][RG][NCH], const int* l_tok, const float* l_gw,
+                                             const uint4* l_vec, WT* h_out, float* out, int rows, int L16,
+                                             int off0, int lsub, int lrow, const TileRef t, int nrows) {
+#pragma unroll
+  for (int q = 0; q < kUnrollTok; ++q)
+    if (q < t.cnt)
+      token_step<WT, STAGE, NM, LPR, NCH, RG, FULL, COH>(w, l_tok, l_gw, l_vec, h_out, out, rows, L16, off0, lsub, lrow,
+                                                    t.rloc, nrows, t.vb + q);
+  if (t.cnt > kUnrollTok)
+    for (int q = kUnrollTok; q < t.cnt; ++q)
+      token_step<WT, STAGE, NM, LPR, NCH, RG, FULL, COH>(w, l_tok, l_gw, l_vec, h_out, out, rows, L16, off0, lsub, lrow,
+                                                    t.rloc, nrows, t.vb + q);
+}
+
+}  // namespace
+}  // namespace oea

@@ -1,0 +1,441 @@
+// The whole decode-time MoE layer in ONE persistent kernel (gfx950): one workgroup per CU.
+//
+//   phase R1  router GEMV, spread over all workgroups (fp64 accumulation, one dot product per
+//             wavefront); x of the batch is staged into LDS meanwhile; `out` is cleared
+//   -- grid barrier --
+//   phase R2  OEA routing (Algorithm 1), computed redundantly by EVERY workgroup from the logits
+//             into its own LDS: no second barrier, no routing metadata read back from memory
+//   phase A   gate/up mat-vec stage over the active experts (streaming, double-buffered tiles)
+//             the first down-stage weight tiles are requested BEFORE the barrier, so HBM keeps
+//             streaming while the workgroups synchronise
+//   -- grid barrier --  (the hidden vectors h of all experts must be complete)
+//   phase B   down mat-vec stage, accumulated into `out` with the gate weights (Eq. 1)
+//
+// Compared with three back-to-back kernels this removes two dispatch gaps with their pipeline
+// drain/fill and every dependent metadata load.  All 256 workgroups must be resident at once: the
+// launcher checks that a workgroup fits on every CU and the barrier spins for a bounded time only.
+#include "oea_ffn_dev.h"
+#ifdef OEA_TIMELINE
+namespace oea {
+namespace {
+__device__ uint32_t* g_tl_ctrl;  // set by the kernel; lets the routing code stamp its passes
+}
+}  // namespace oea
+#define OEA_ROUTE_TL(slot_)                                                                        \
+  do {                                                                                             \
+    if (threadIdx.x == 0 && blockIdx.x == 0 && g_tl_ctrl) {                                        \
+      unsigned long long t_ = wall_clock64();                                                      \
+      g_tl_ctrl[128 + 2 * (slot_)] = uint32_t(t_);                                                 \
+      g_tl_ctrl[128 + 2 * (slot_) + 1] = uint32_t(t_ >> 32);                                       \
+    }                                                                                              \
+  } while (0)
+#endif
+#include "oea_route_dev.h"
+
+namespace oea {
+
+namespace {
+
+constexpr size_t kFusedLdsMax = 156 * 1024;
+constexpr int kFusedStage = 8;  // staging loads kept in flight per thread
+
+struct FusedParams {
+  const void* x;
+  const void* w_router;
+  const void* w_gate;
+  const void* w_up;
+  const void* w_down;
+  const float* bias;
+  const uint8_t* token_mask;
+  float* out;
+  float* logits;   // [B,N] workspace
+  void* h;         // [B*k, I] workspace
+  RouteOut ro;     // global copies of the routing result, written by workgroup 0
+  uint32_t* ctrl;  // [3] error flag, [32] barrier arrivals, [64] barrier generation (separate 128-byte lines)
+  int B, d, N, I, k, k0;
+  int cap_vec;     // most (expert, token) pairs one workgroup can meet in one stage
+  uint32_t spin_limit;
+};
+
+// words of LDS in front of the vector area (after the 16-byte dump slot)
+__host__ __device__ inline size_t fused_meta_words(int B, int N, int k) {
+  const size_t P = (size_t)B * k;
+  size_t w = route_lds_words(B, N) + 4 * P + (size_t)B + (size_t)N + 4 + (size_t)N + 4 + (size_t)B * N;
+  return (w + 3) & ~size_t(3);
+}
+
+// Sense-reversing barrier over all workgroups of the grid.  count returns to 0, gen only grows.
+// There is no cache maintenance in it (a device-scope fence writes back / invalidates the whole L2
+// of the XCD, far too slow here): data that crosses workgroups in this kernel is written with
+// device-coherent stores and read with device-coherent loads instead.  The leading __syncthreads
+// makes every wavefront wait for its own outstanding stores, so they have reached memory before
+// thread 0 announces the workgroup (the callers also drain explicitly before they come here).
+// The wait is bounded: after spin_limit polls the workgroup raises the error flag and goes on
+// (its results are then meaningless, but every access stays in bounds and the kernel ends).
+__device__ __forceinline__ void grid_barrier(uint32_t* ctrl, uint32_t spin_limit) {
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t* count = ctrl + 32;
+    uint32_t* gen = ctrl + 64;
+    uint32_t g = __hip_atomic_load(gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // the read of gen must have been performed before the arrival becomes visible (else a release
+    // that follows the arrival at once could be mistaken for the old generation): wait for its value
+    asm volatile("" : "+v"(g) : : "memory");
+    const uint32_t old = __hip_atomic_fetch_add(count, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (old == gridDim.x - 1) {
+      __hip_atomic_store(count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // count is back to 0 before anyone is released
+      __hip_atomic_store(gen, g + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+      uint32_t spins = 0;
+      while (__hip_atomic_load(gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == g) {
+        __builtin_amdgcn_s_sleep(2);
+        if (++spins > spin_limit) {
+          atomicExch(ctrl + 3, 1u);
+          break;
+        }
+      }
+    }
+  }
+  __syncthreads();
+}
+
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// Optional timeline (build with -DOEA_TIMELINE): thread 0 of the first and of the last workgroup
+// store the 100 MHz wall clock at phase boundaries into ctrl[128..] and ctrl[192..].
+#ifdef OEA_TIMELINE
+#define OEA_TL(ctrl_, slot_)                                                                      \
+  do {                                                                                            \
+    if (threadIdx.x == 0 && (blockIdx.x == 0 || blockIdx.x == gridDim.x - 1)) {                   \
+      unsigned long long t_ = wall_clock64();                                                     \
+      uint32_t* d_ = (ctrl_) + (blockIdx.x == 0 ? 128 : 192) + 2 * (slot_);                         \
+      d_[0] = uint32_t(t_);                                                                       \
+      d_[1] = uint32_t(t_ >> 32);                                                                 \
+    }                                                                                             \
+  } while (0)
+#else
+#define OEA_TL(ctrl_, slot_) \
+  do {                       \
+  } while (0)
+#endif
+
+// One mat-vec stage of the fused kernel.  Same tile loop as expert_stream_kernel; the routing
+// metadata comes from LDS, and `mid` runs once the first two weight tiles are in flight (it holds
+// the grid barrier and the staging of h for the down stage).  Every workgroup calls mid.
+template <typename WT, int STAGE, int LPR, int NCH, int RG, typename Mid>
+__device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_out, float* out, int rows, int L,
+                                            int T, int N, int pairs_max, int cap_vec, const int* l_active,
+                                            const int* l_off, const int* l_tok, const float* l_gw,
+                                            const uint4* l_vec, Mid mid) {
+  constexpr int EPL = 16 / int(sizeof(WT));
+  constexpr int R = 64 / LPR;
+  constexpr int NM = STAGE == 0 ? 2 : 1;
+  constexpr int TROWS = RG * R;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = uniform(tid >> 6);
+  const int lsub = lane % LPR, lrow = lane / LPR;
+  const int L16 = L / EPL;
+
+  const int total = T * rows;
+  const int R0 = int((long long)total * blockIdx.x / gridDim.x);
+  const int R1 = int((long long)total * (blockIdx.x + 1) / gridDim.x);
+  bool wg_has = R0 < R1;
+  const int a0 = wg_has ? R0 / rows : 0;
+  const int nseg = wg_has ? (R1 - 1) / rows - a0 + 1 : 0;
+  const int off0 = uniform(l_off[a0]);
+  const int off1 = uniform(l_off[a0 + 1]);
+  const int off2 = nseg > 1 ? uniform(l_off[a0 + 2]) : off1;
+  const int off3 = nseg > 2 ? uniform(l_off[a0 + 3]) : off2;
+  const int e0 = uniform(l_active[a0]);
+  const int e1 = nseg > 1 ? uniform(l_active[a0 + 1]) : 0;
+  const int e2 = nseg > 2 ? uniform(l_active[a0 + 2]) : 0;
+  const int nvec = wg_has ? off3 - off0 : 0;
+  // never true for a routing computed by this kernel; keeps every access in bounds regardless
+  if (nseg > kMaxSeg || off0 < 0 || off1 < off0 || off2 < off1 || off3 < off2 || nvec > cap_vec ||
+      off0 + nvec > pairs_max || (unsigned)e0 >= (unsigned)N || (unsigned)e1 >= (unsigned)N ||
+      (unsigned)e2 >= (unsigned)N)
+    wg_has = false;
+
+  const int n_wg = wg_has ? R1 - R0 : 0;
+  const int my_lo = R0 + int((long long)n_wg * wave / kFfnWaves);
+  const int my_hi = R0 + int((long long)n_wg * (wave + 1) / kFfnWaves);
+  const bool has_work = my_lo < my_hi;
+  const SegView sv{rows, a0, e0, e1, e2, off1 - off0, off2 - off1, off3 - off2, my_hi};
+
+  uint4 wA[NM][RG][NCH], wB[NM][RG][NCH];
+  const int r_first = has_work ? my_lo : R0;
+  const int n_first = has_work ? tile_rows(sv, my_lo, TROWS) : 1;
+  int rA = r_first, nA = has_work ? n_first : 0;
+  int rB = rA + nA, nB = tile_rows(sv, rB, TROWS);
+  if (wg_has) {  // uniform over the workgroup; a wavefront without rows loads the first row and drops it
+    load_tile<WT, NM, LPR, NCH, RG, true>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv, r_first), n_first);
+    load_tile<WT, NM, LPR, NCH, RG, true>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv, nB > 0 ? rB : r_first),
+                                          nB > 0 ? nB : n_first);
+  }
+
+  mid(wg_has ? off0 : 0, wg_has ? nvec : 0);
+
+  if (!has_work) return;
+  const int* const s_tok = l_tok + off0;  // pair lists of this workgroup's experts
+  const float* const s_gw = l_gw + off0;
+  while (true) {
+    compute_tile<WT, STAGE, NM, LPR, NCH, RG, true, true>(wA, s_tok, s_gw, l_vec, h_out, out, rows, L16, off0, lsub, lrow,
+                                                    tile_ref(sv, rA), nA);
+    rA = rB + nB;
+    nA = tile_rows(sv, rA, TROWS);
+    load_tile<WT, NM, LPR, NCH, RG, true>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv, nA > 0 ? rA : r_first),
+                                          nA > 0 ? nA : n_first);
+    if (nB <= 0) break;
+    compute_tile<WT, STAGE, NM, LPR, NCH, RG, true, true>(wB, s_tok, s_gw, l_vec, h_out, out, rows, L16, off0, lsub, lrow,
+                                                    tile_ref(sv, rB), nB);
+    rB = rA + nA;
+    nB = tile_rows(sv, rB, TROWS);
+    load_tile<WT, NM, LPR, NCH, RG, true>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv, nB > 0 ? rB : r_first),
+                                          nB > 0 ? nB : n_first);
+    if (nA <= 0) break;
+  }
+}
+
+// d == LPR0*EPL*NCH0 and I == LPR1*EPL*NCH1 exactly; N <= 64*NV; B <= TPW*8.
+template <typename WT, int LPR0, int NCH0, int LPR1, int NCH1, int NV, int TPW>
+__global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
+  extern __shared__ uint4 lds4[];
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  constexpr int EPL = 16 / int(sizeof(WT));
+  const int B = p.B, d = p.d, N = p.N, I = p.I, k = p.k;
+  const int P = B * k;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = uniform(tid >> 6);
+  const int G = gridDim.x, wg = blockIdx.x;
+  const WT* const x = static_cast<const WT*>(p.x);
+
+  // ---- LDS: [dump 16 B][routing scratch][routing result][vectors: x (phases R,A) then h (phase B)]
+  uint32_t* const l_route = reinterpret_cast<uint32_t*>(lds4 + 1);
+  int* const l_idx = reinterpret_cast<int*>(l_route + route_lds_words(B, N));
+  float* const l_gatew = reinterpret_cast<float*>(l_idx + P);
+  int* const l_nsel = reinterpret_cast<int*>(l_gatew + P);
+  int* const l_active = l_nsel + B;
+  int* const l_nact = l_active + N;
+  int* const l_off = l_nact + 4;
+  int* const l_tok = l_off + N + 4;
+  float* const l_gw = reinterpret_cast<float*>(l_tok + P);
+  float* const l_logits = l_gw + P;  // [B,N]
+  uint4* const l_vec = lds4 + 1 + fused_meta_words(B, N, k) / 4;
+
+#ifdef OEA_TIMELINE
+  if (threadIdx.x == 0 && blockIdx.x == 0) g_tl_ctrl = p.ctrl;
+#endif
+  OEA_TL(p.ctrl, 0);
+  // ---- phase R1.  x of the batch -> LDS: loads first, written after the logits
+  const int d16 = d / EPL;
+  const int n16_x = B * d16;
+  u32x4 stg[kFusedStage];
+  {
+    const u32x4* src = reinterpret_cast<const u32x4*>(x);
+#pragma unroll
+    for (int j = 0; j < kFusedStage; ++j) {
+      const int i = j * kFfnThreads + tid;
+      stg[j] = src[i < n16_x ? i : n16_x - 1];
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+
+  {  // clear this workgroup's slice of out[B,d] (d is a multiple of 8: float4 granules)
+    // written through to memory: phase B adds to these words with device-scope atomics from every XCD
+    const int total = B * d;
+    const int per = (total + G - 1) / G;
+    const int lo = per * wg, hi = lo + per < total ? lo + per : total;
+    for (int i = lo + tid; i < hi; i += kFfnThreads)
+      __hip_atomic_store(p.out + i, 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+
+  // router logits: one (token, expert) dot product per wavefront, fp64 accumulation, one rounding
+  {
+    const WT* const wr = static_cast<const WT*>(p.w_router);
+    for (int idx = wg * kFfnWaves + wave; idx < B * N; idx += G * kFfnWaves) {
+      const int t = idx / N, e = idx - t * N;
+      const WT* xr = x + (size_t)t * d;
+      const WT* wre = wr + (size_t)e * d;
+      double acc = 0.0;
+      for (int c = lane * EPL; c < d; c += 64 * EPL) {
+        uint4 a = *reinterpret_cast<const uint4*>(xr + c);
+        uint4 b = *reinterpret_cast<const uint4*>(wre + c);
+        acc = frag_dot_f64<WT>(a, b, acc);
+      }
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
+      if (lane == 0) {
+        if (p.bias) acc += double(p.bias[e]);
+        __hip_atomic_store(p.logits + idx, float(acc), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+  }
+
+#pragma unroll
+  for (int j = 0; j < kFusedStage; ++j) {
+    const int i16 = j * kFfnThreads + tid;
+    *reinterpret_cast<u32x4*>(i16 < n16_x ? l_vec + i16 : lds4) = stg[j];
+  }
+  for (int base = kFusedStage * kFfnThreads; base < n16_x; base += kFusedStage * kFfnThreads) {  // larger x
+    const u32x4* src = reinterpret_cast<const u32x4*>(x);
+#pragma unroll
+    for (int j = 0; j < kFusedStage; ++j) {
+      const int i16 = base + j * kFfnThreads + tid;
+      stg[j] = src[i16 < n16_x ? i16 : n16_x - 1];
+    }
+#pragma unroll
+    for (int j = 0; j < kFusedStage; ++j) {
+      const int i16 = base + j * kFfnThreads + tid;
+      *reinterpret_cast<u32x4*>(i16 < n16_x ? l_vec + i16 : lds4) = stg[j];
+    }
+  }
+
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // logits and cleared out words have reached memory
+  OEA_TL(p.ctrl, 1);
+  grid_barrier(p.ctrl, p.spin_limit);
+  OEA_TL(p.ctrl, 2);
+
+  // ---- phase R2: routing, replicated per workgroup, result in LDS
+  for (int i = tid; i < B * N; i += kFfnThreads)  // device-coherent loads: written by other workgroups
+    l_logits[i] = __hip_atomic_load(p.logits + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  OEA_TL(p.ctrl, 9);
+  {
+    RouteOut lo{l_idx, l_gatew, l_nsel, l_active, l_nact, l_off, l_tok, l_gw};
+    route_block<NV, kFfnThreads, TPW>(l_logits, p.token_mask, B, N, k, p.k0, lo, l_route);
+  }
+  __syncthreads();
+  if (wg == 0) {  // publish the routing result
+    for (int i = tid; i < P; i += kFfnThreads) {
+      p.ro.expert_idx[i] = l_idx[i];
+      p.ro.gate_w[i] = l_gatew[i];
+    }
+    for (int i = tid; i < B; i += kFfnThreads) p.ro.n_sel[i] = l_nsel[i];
+    for (int i = tid; i < N; i += kFfnThreads) p.ro.active_list[i] = l_active[i];
+    if (tid == 0) *p.ro.n_active = l_nact[0];
+  }
+  int T = uniform(l_nact[0]);
+  T = T < 0 ? 0 : (T > N ? N : T);
+  OEA_TL(p.ctrl, 3);
+
+  // ---- phase A: gate/up
+  fused_stage<WT, 0, LPR0, NCH0, 1>(static_cast<const WT*>(p.w_gate), static_cast<const WT*>(p.w_up),
+                                    static_cast<WT*>(p.h), p.out, I, d, T, N, P, p.cap_vec, l_active, l_off,
+                                    l_tok, l_gw, l_vec, [](int, int) {});
+
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wavefront's h values have reached memory
+  OEA_TL(p.ctrl, 4);
+  // ---- phase B: down.  mid = barrier (h complete everywhere), then this workgroup's h rows -> LDS
+  const WT* const hsrc = static_cast<const WT*>(p.h);
+  const int I16 = I / EPL;
+  uint32_t* const ctrl = p.ctrl;
+  const uint32_t spin_limit = p.spin_limit;
+  fused_stage<WT, 1, LPR1, NCH1, 2>(
+      static_cast<const WT*>(p.w_down), static_cast<const WT*>(nullptr), static_cast<WT*>(nullptr), p.out, d, I, T,
+      N, P, p.cap_vec, l_active, l_off, l_tok, l_gw, l_vec, [=](int off0, int nvec) {
+        OEA_TL(ctrl, 5);
+        grid_barrier(ctrl, spin_limit);
+        OEA_TL(ctrl, 6);
+        // h was written by other workgroups (other XCDs): device-coherent 16-byte loads, which
+        // exist as buffer loads with the sc0 sc1 bits; the descriptor also bounds the access
+        const int n16 = nvec * I16;
+        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<WT*>(hsrc + (size_t)off0 * I), 0, n16 * 16, 0x00020000);
+        for (int base = 0; base < n16; base += kFusedStage * kFfnThreads) {
+          u32x4 t4[kFusedStage];
+#pragma unroll
+          for (int j = 0; j < kFusedStage; ++j) {
+            const int i16 = base + j * kFfnThreads + tid;
+            t4[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (i16 < n16 ? i16 : n16 - 1) * 16, 0, 1 | 16);
+          }
+#pragma unroll
+          for (int j = 0; j < kFusedStage; ++j) {
+            const int i16 = base + j * kFfnThreads + tid;
+            *reinterpret_cast<u32x4*>(i16 < n16 ? l_vec + i16 : lds4) = t4[j];
+          }
+        }
+        __syncthreads();
+        OEA_TL(ctrl, 7);
+      });
+  OEA_TL(p.ctrl, 8);
+}
+
+int g_fused_cus = -1;  // CUs when the residency check passed, 0 when it failed, -1 before the check
+
+template <typename WT, int LPR0, int NCH0, int LPR1, int NCH1, int NV, int TPW>
+hipError_t launch_fused_one(const FusedParams& p, size_t lds_bytes, hipStream_t s) {
+  auto kern = moe_fused_kernel<WT, LPR0, NCH0, LPR1, NCH1, NV, TPW>;
+  static int checked = 0;  // 1 = usable, -1 = not
+  if (checked == 0) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLdsMax);
+    if (e != hipSuccess) return e;
+    int per_cu = 0;
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, kFfnThreads, kFusedLdsMax);
+    if (e != hipSuccess) return e;
+    checked = per_cu >= 1 ? 1 : -1;  // every CU can hold one workgroup: the whole grid is resident
+  }
+  if (checked < 0) return hipErrorNotSupported;
+  hipLaunchKernelGGL(kern, dim3(g_fused_cus), dim3(kFfnThreads), lds_bytes, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// The fused kernel when the shape is one it is built for; hipErrorNotSupported otherwise.
+hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_gate, const void* w_up,
+                            const void* w_down, const float* bias, const uint8_t* token_mask, float* out,
+                            float* logits, void* h, RouteOut ro, uint32_t* ctrl, int B, int d, int N, int I,
+                            int k, int k0, oea_dtype dt, hipStream_t s) {
+  if (dt != OEA_BF16 || N > 128 || B > 32) return hipErrorNotSupported;
+  const bool shape30 = d == 2048 && I == 768, shape235 = d == 4096 && I == 1536;
+  if (!shape30 && !shape235) return hipErrorNotSupported;
+  if (g_fused_cus < 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hipErrorUnknown;
+    g_fused_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 0;
+  }
+  const int grid = g_fused_cus;
+  if (grid < 1) return hipErrorNotSupported;
+  const int nseg_max = (N + grid - 1) / grid + 1;
+  if (nseg_max > kMaxSeg) return hipErrorNotSupported;
+  long long cap_vec = (long long)nseg_max * B;
+  if (cap_vec > (long long)B * k) cap_vec = (long long)B * k;
+  const size_t vec_x = (size_t)B * d * 2, vec_h = (size_t)cap_vec * I * 2;
+  size_t lds_bytes = 16 + fused_meta_words(B, N, k) * 4 + (vec_x > vec_h ? vec_x : vec_h);
+  if (lds_bytes > kFusedLdsMax) return hipErrorNotSupported;
+  const size_t alone = 84 * 1024;  // more than half of a CU's LDS: exactly one workgroup per CU
+  if (lds_bytes < alone) lds_bytes = alone;
+
+  FusedParams p{};
+  p.x = x;
+  p.w_router = w_router;
+  p.w_gate = w_gate;
+  p.w_up = w_up;
+  p.w_down = w_down;
+  p.bias = bias;
+  p.token_mask = token_mask;
+  p.out = out;
+  p.logits = logits;
+  p.h = h;
+  p.ro = ro;
+  p.ctrl = ctrl;
+  p.B = B;
+  p.d = d;
+  p.N = N;
+  p.I = I;
+  p.k = k;
+  p.k0 = k0;
+  p.cap_vec = (int)cap_vec;
+  p.spin_limit = 4u << 20;  // polls of >= 100 ns each: gives up after about a second
+  if (shape30) {
+    if (B <= 16) return launch_fused_one<uint16_t, 32, 8, 16, 6, 2, 2>(p, lds_bytes, s);
+    return launch_fused_one<uint16_t, 32, 8, 16, 6, 2, 4>(p, lds_bytes, s);
+  }
+  if (B <= 16) return launch_fused_one<uint16_t, 64, 8, 32, 6, 2, 2>(p, lds_bytes, s);
+  return launch_fused_one<uint16_t, 64, 8, 32, 6, 2, 4>(p, lds_bytes, s);
+}
+
+}  // namespace oea

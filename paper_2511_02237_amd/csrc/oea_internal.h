@@ -10,7 +10,8 @@ namespace oea {
 
 // Carving of the caller's workspace.  All offsets are multiples of 256 bytes.
 struct WsLayout {
-  size_t ctrl;         // uint32[64]; [0] = arrival counter of the router kernel (zero between calls)
+  size_t ctrl;         // uint32[1024], zero between calls: [0] arrival counter of the router kernel,
+                       // [3] error flag, [32] and [64] grid-barrier words of the fused kernel
   size_t logits;       // float [B,N]
   size_t expert_idx;   // int32 [B,k]
   size_t gate_w;       // float [B,k]
@@ -58,6 +59,12 @@ hipError_t launch_expert_gate_up(const void* x, const void* w_gate, const void* 
                                  int d, int N, int I, int k, oea_dtype dt, Grouping g, hipStream_t s);
 hipError_t launch_expert_down(const void* h, const void* w_down, float* out, int B, int d, int N, int I,
                               int k, oea_dtype dt, Grouping g, hipStream_t s);
+
+// whole layer in one persistent kernel; hipErrorNotSupported if the shape is not one it is built for
+hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_gate, const void* w_up,
+                            const void* w_down, const float* bias, const uint8_t* token_mask, float* out,
+                            float* logits, void* h, RouteOut ro, uint32_t* ctrl, int B, int d, int N, int I,
+                            int k, int k0, oea_dtype dt, hipStream_t s);
 
 size_t route_lds_bytes(int B, int N);
 void set_force_generic(bool on);

@@ -1,0 +1,344 @@
+// Device-side routing code shared by the routing kernels and the fused layer kernel (gfx950).
+//
+// Routing follows Algorithm 1 of the paper in its closed form: every token's Phase-1 set is a
+// subset of the union U, and the k0 best experts overall are also the k0 best inside U, so the
+// final set of a token is "the min(k,|U|) best-ranked members of U".  route_block does
+//   pass 1: per token (one wavefront each) top-k0 by repeated wave arg-max -> OR into a bit mask in LDS
+//   barrier
+//   pass 2: per token the best members of U up to k -> S_i in rank order, gate weights
+//           (softmax scores renormalised over S_i: Eq. 1 / Section 3.2 "Weighting after rerouting")
+//   pass 3: ascending active list, and the expert -> (token, weight) grouping the FFN kernels use.
+// Ranking is on the fp32 logits, ties to the lower expert id, -0.0 equal to +0.0.
+#pragma once
+#include "oea_internal.h"
+
+#ifndef OEA_ROUTE_TL
+#define OEA_ROUTE_TL(slot_) \
+  do {                      \
+  } while (0)
+#endif
+
+namespace oea {
+namespace {
+
+__device__ __forceinline__ uint32_t orderable_bits(float v) {
+  uint32_t u = __float_as_uint(v);
+  if ((u << 1) == 0u) u = 0u;  // -0.0 ranks equal to +0.0
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ float from_orderable(uint32_t o) {
+  uint32_t u = (o & 0x80000000u) ? (o & 0x7fffffffu) : ~o;
+  return __uint_as_float(u);
+}
+
+// Ranking key of a logit: its order-preserving bit pattern; larger = better rank.  0 marks "not a
+// candidate" (only one negative-NaN pattern maps to 0, and routing of NaN logits is unspecified).
+// Equal keys are separated by expert id when the winner is looked up (lowest id first).
+__device__ __forceinline__ uint32_t make_key(float logit) { return orderable_bits(logit); }
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_max_u32(uint32_t v) {
+  const uint32_t o = uint32_t(__builtin_amdgcn_update_dpp(0, int(v), CTRL, 0xF, 0xF, true));
+  return o > v ? o : v;
+}
+
+// max over the 64 lanes as a wave-uniform value: 4 DPP steps inside each row of 16 lanes, then the
+// four row results are read into scalar registers and compared there
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+  v = dpp_max_u32<0xB1>(v);   // quad_perm [1,0,3,2]
+  v = dpp_max_u32<0x4E>(v);   // quad_perm [2,3,0,1]
+  v = dpp_max_u32<0x141>(v);  // row_half_mirror
+  v = dpp_max_u32<0x140>(v);  // row_mirror
+  uint32_t m = 0;
+#pragma unroll
+  for (int row = 0; row < 4; ++row) {
+    const uint32_t r = uint32_t(__builtin_amdgcn_readlane(int(v), row * 16));
+    m = r > m ? r : m;
+  }
+  return m;
+}
+
+__device__ __forceinline__ float wave_sum_f32(float v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// One arg-max round over the wave's candidate keys (lane l, slot j holds expert l + 64 j); removes
+// the winner.  Returns false if no candidate is left; else the winner's key and expert id (uniform).
+template <int NV>
+__device__ __forceinline__ bool pick_best(uint32_t (&key)[NV], int lane, uint32_t& best_key, int& best_id) {
+  uint32_t local = key[0];
+#pragma unroll
+  for (int j = 1; j < NV; ++j) local = key[j] > local ? key[j] : local;
+  const uint32_t m = wave_max_u32(local);
+  if (m == 0) return false;
+  int id = -1;  // equal keys: the lowest expert id wins
+#pragma unroll
+  for (int j = NV - 1; j >= 0; --j) {
+    const uint64_t hit = __ballot(key[j] == m);
+    if (hit != 0) id = 64 * j + int(__builtin_ctzll(hit));
+  }
+#pragma unroll
+  for (int j = 0; j < NV; ++j)
+    if (id == lane + 64 * j) key[j] = 0;
+  best_key = m;
+  best_id = id;
+  return true;
+}
+
+// LDS words used by route_block
+__host__ __device__ inline size_t route_lds_words(int B, int N) {
+  return 64 + (size_t)N * ((B + 31) / 32) + (size_t)N;
+}
+
+// Executed by ONE workgroup of NT threads (NT/64 wavefronts, NT >= N).  lds: route_lds_words(B,N) words.
+// TPW > 0 (requires B <= TPW * NT/64): every wavefront owns at most TPW tokens and keeps their
+// candidate keys in registers across the barrier, so Phase 2 continues where Phase 1 stopped.
+// TPW == 0: any B; Phase 2 starts over from the logits.
+// The RouteOut pointers may point to global memory or to LDS.
+template <int NV, int NT, int TPW>
+__device__ void route_block(const float* __restrict__ logits, const uint8_t* __restrict__ token_mask,
+                            int B, int N, int k, int k0, RouteOut o, uint32_t* lds) {
+  constexpr int NW = NT / 64;
+  constexpr int TP = TPW > 0 ? TPW : 1;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int NWB = (B + 31) >> 5;
+  uint32_t* U = lds;                   // [16] union bit mask over experts
+  uint32_t* scan = lds + 16;           // [48] scratch for block scans
+  uint32_t* colmask = lds + 64;        // [N*NWB] per expert: bit mask of the tokens routed to it
+  uint32_t* eoff = colmask + N * NWB;  // [N] per expert: first pair in the grouped order
+
+  for (int i = tid; i < int(route_lds_words(B, N)); i += NT) lds[i] = 0;
+  __syncthreads();
+  OEA_ROUTE_TL(10);
+
+  uint32_t keep[TP][NV];  // TPW > 0: the wavefront's keys after Phase 1
+  int sel_id[TP];         // lane r holds the expert of rank r
+  float sel_logit[TP];
+  int sel_n[TP];
+
+  // ---- pass 1: Phase 1 of Algorithm 1, S_i^base = k0 best experts; U = union over the batch
+  auto phase1 = [&](int t, uint32_t (&key)[NV], int& n, int& my_id, float& my_logit) __attribute__((always_inline)) {
+    const bool live = !(token_mask && token_mask[t] == 0);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      int e = lane + 64 * j;
+      key[j] = (live && e < N) ? make_key(logits[(size_t)t * N + e]) : 0;
+    }
+    n = 0;
+    my_id = -1;
+    my_logit = 0.f;
+    for (int r = 0; r < k0; ++r) {
+      uint32_t bk;
+      int id;
+      if (!pick_best<NV>(key, lane, bk, id)) break;
+      if (lane == 0) atomicOr(&U[id >> 5], 1u << (id & 31));
+      if (lane == r) {
+        my_id = id;
+        my_logit = from_orderable(bk);
+      }
+      ++n;
+    }
+  };
+  if (TPW > 0) {
+#pragma unroll
+    for (int i = 0; i < TP; ++i) {
+      const int t = wave + i * NW;
+      const bool live = t < B && !(token_mask && token_mask[t] == 0);
+      sel_n[i] = 0;
+      sel_id[i] = -1;
+      sel_logit[i] = 0.f;
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        int e = lane + 64 * j;
+        keep[i][j] = (live && e < N) ? make_key(logits[(size_t)(live ? t : 0) * N + e]) : 0;
+      }
+    }
+    // rounds outside, tokens inside: the wavefront's tokens form independent dependency chains
+    for (int r = 0; r < k0; ++r) {
+#pragma unroll
+      for (int i = 0; i < TP; ++i) {
+        uint32_t bk;
+        int id;
+        if (pick_best<NV>(keep[i], lane, bk, id)) {
+          if (lane == 0) atomicOr(&U[id >> 5], 1u << (id & 31));
+          if (lane == r) {
+            sel_id[i] = id;
+            sel_logit[i] = from_orderable(bk);
+          }
+          ++sel_n[i];
+        }
+      }
+    }
+  } else {
+    for (int t = wave; t < B; t += NW) {
+      uint32_t key[NV];
+      int n, id;
+      float lg;
+      phase1(t, key, n, id, lg);
+    }
+  }
+  __syncthreads();
+  OEA_ROUTE_TL(11);
+
+  // ---- pass 2: Phase 2 in closed form: the token's best members of U up to k in all, then weights.
+  // Every Phase-1 pick is in U and outranks the rest, so with kept keys Phase 2 just continues.
+  auto phase2 = [&](int t, uint32_t (&key)[NV], int n, int my_id, float my_logit) __attribute__((always_inline)) {
+    for (int r = n; r < k; ++r) {
+      uint32_t bk;
+      int id;
+      if (!pick_best<NV>(key, lane, bk, id)) break;
+      if (lane == r) {
+        my_id = id;
+        my_logit = from_orderable(bk);
+      }
+      ++n;
+    }
+    // g_s = exp(l_s - m) / sum_{s'} exp(l_s' - m): the softmax denominator cancels in Eq. 1
+    float m = __shfl(my_logit, 0, 64);
+    float w = lane < n ? expf(my_logit - m) : 0.f;
+    float z = wave_sum_f32(w);
+    if (lane < k) {
+      o.expert_idx[(size_t)t * k + lane] = lane < n ? my_id : -1;
+      o.gate_w[(size_t)t * k + lane] = lane < n ? w / z : 0.f;
+    }
+    if (lane < n) atomicOr(&colmask[my_id * NWB + (t >> 5)], 1u << (t & 31));
+    if (lane == 0) o.n_sel[t] = n;
+  };
+  if (TPW > 0) {
+#pragma unroll
+    for (int i = 0; i < TP; ++i)
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        int e = lane + 64 * j;
+        bool cand = e < N && ((U[e >> 5] >> (e & 31)) & 1u);
+        if (!cand) keep[i][j] = 0;
+      }
+    for (int r = k0; r < k; ++r) {  // every live token holds exactly k0 picks here
+#pragma unroll
+      for (int i = 0; i < TP; ++i) {
+        uint32_t bk;
+        int id;
+        if (pick_best<NV>(keep[i], lane, bk, id)) {
+          if (lane == sel_n[i]) {
+            sel_id[i] = id;
+            sel_logit[i] = from_orderable(bk);
+          }
+          ++sel_n[i];
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < TP; ++i) {
+      const int t = wave + i * NW;
+      if (t < B) {
+        uint32_t none[NV];
+#pragma unroll
+        for (int j = 0; j < NV; ++j) none[j] = 0;
+        phase2(t, none, sel_n[i], sel_id[i], sel_logit[i]);  // no candidate left: only weights and stores
+      }
+    }
+  } else {
+    for (int t = wave; t < B; t += NW) {
+      const bool live = !(token_mask && token_mask[t] == 0);
+      uint32_t key[NV];
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        int e = lane + 64 * j;
+        bool cand = live && e < N && ((U[e >> 5] >> (e & 31)) & 1u);
+        key[j] = cand ? make_key(logits[(size_t)t * N + e]) : 0;
+      }
+      phase2(t, key, 0, -1, 0.f);
+    }
+  }
+  __syncthreads();
+  OEA_ROUTE_TL(12);
+
+  // ---- pass 3a: active list (ascending ids), pairs per expert, CSR offsets
+  const int e = tid;
+  const bool in_u = e < N && ((U[e >> 5] >> (e & 31)) & 1u);
+  uint64_t ballot = __ballot(in_u);
+  if (lane == 0) scan[wave] = uint32_t(__popcll(ballot));
+  int cnt = 0;
+  if (in_u)
+    for (int w = 0; w < NWB; ++w) cnt += __popc(colmask[e * NWB + w]);
+  int incl = cnt;  // inclusive scan of cnt inside the wave
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    int v = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += v;
+  }
+  if (lane == 63) scan[16 + wave] = uint32_t(incl);
+  __syncthreads();
+  int pos_base = 0, cnt_base = 0, T = 0, P = 0;
+  for (int w = 0; w < NW; ++w) {
+    int a = int(scan[w]), c = int(scan[16 + w]);
+    if (w < wave) {
+      pos_base += a;
+      cnt_base += c;
+    }
+    T += a;
+    P += c;
+  }
+  const int pos = pos_base + __popcll(ballot & ((1ull << lane) - 1ull));
+  const int excl = cnt_base + incl - cnt;
+  if (in_u) o.active_list[pos] = e;
+  if (e < N && e >= T) o.active_list[e] = -1;
+  if (tid == 0) *o.n_active = T;
+  if (!o.grp_off) return;
+  if (in_u) {
+    o.grp_off[pos] = excl;
+    eoff[e] = uint32_t(excl);
+  }
+  if (tid == 0) o.grp_off[T] = P;
+  __syncthreads();
+  OEA_ROUTE_TL(13);
+
+  // ---- pass 3b: one thread per (token, slot) pair; inside an expert, pairs are in token order
+  for (int p = tid; p < B * k; p += NT) {
+    const int ex = o.expert_idx[p];
+    if (ex < 0) continue;
+    const int t = p / k;
+    int rank = __popc(colmask[ex * NWB + (t >> 5)] & ((1u << (t & 31)) - 1u));
+    for (int w = 0; w < (t >> 5); ++w) rank += __popc(colmask[ex * NWB + w]);
+    const int dst = int(eoff[ex]) + rank;
+    o.grp_tok[dst] = t;
+    o.grp_gw[dst] = o.gate_w[p];
+  }
+}
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// fp64 dot product of one 16-byte fragment pair
+template <typename WT>
+__device__ __forceinline__ double frag_dot_f64(const uint4& a, const uint4& b, double acc);
+
+template <>
+__device__ __forceinline__ double frag_dot_f64<float>(const uint4& a, const uint4& b, double acc) {
+  acc = fma(double(__uint_as_float(a.x)), double(__uint_as_float(b.x)), acc);
+  acc = fma(double(__uint_as_float(a.y)), double(__uint_as_float(b.y)), acc);
+  acc = fma(double(__uint_as_float(a.z)), double(__uint_as_float(b.z)), acc);
+  acc = fma(double(__uint_as_float(a.w)), double(__uint_as_float(b.w)), acc);
+  return acc;
+}
+
+template <>
+__device__ __forceinline__ double frag_dot_f64<uint16_t>(const uint4& a, const uint4& b, double acc) {
+  const uint32_t av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    // a bf16 x bf16 product is exact in fp32
+    acc += double(bf16_bits_to_f32(av[i] & 0xffffu) * bf16_bits_to_f32(bv[i] & 0xffffu));
+    acc += double(__uint_as_float(av[i] & 0xffff0000u) * __uint_as_float(bv[i] & 0xffff0000u));
+  }
+  return acc;
+}
+
+// grid = N workgroups (one per expert e), kRouteThreads threads.
+//   part A: logits[t,e] = fp32( sum_c x[t,c] W_router[e,c] + bias[e] ), fp64 accumulation;
+//           the workgroups also clear `out` for the atomically accumulating down-projection.
+
+}  // namespace
+}  // namespace oea

@@ -216,18 +216,73 @@ def test_workspace_reuse_and_repeatability(torch, B_, oracle):
     assert np.abs(o1 - o3).max() <= 1e-5 * np.abs(o1).max()
 
 
-@pytest.mark.parametrize("name,seeds", [("qwen3_30b", (0, 1)), ("qwen3_30b_skew", (0,))])
-def test_full_size_30b_shape(torch, B_, oracle, name, seeds):
-    """The configuration the benchmark times (B=16, d=2048, N=128, I=768, k=8), every output element."""
-    for seed in seeds:
-        L = W.make_layer(name, 2000 + seed)
+_BIG = {}
+
+
+def big_layer(B_, name, seed):
+    """Full-size layers are slow to draw and upload: keep the last one per name."""
+    key = (name, seed)
+    if _BIG.get(name, (None,))[0] != key:
+        L = W.make_layer(name, seed)
         dev = {f: B_.to_device(getattr(L, f)) for f in ("x", "w_router", "w_gate", "w_up", "w_down")}
+        _BIG[name] = (key, L, dev)
+    return _BIG[name][1], _BIG[name][2]
+
+
+@pytest.mark.parametrize("name,seeds", [("qwen3_30b", (1, 0)), ("qwen3_30b_skew", (0,))])
+def test_full_size_30b_shape(torch, B_, oracle, name, seeds):
+    """The configuration the benchmark times (B=16, d=2048, N=128, I=768, k=8), every output element.
+    This shape runs as the single fused kernel."""
+    for seed in seeds:
+        L, dev = big_layer(B_, name, 2000 + seed)
         ws = B_.new_workspace(L.B, L.d, L.N, L.I, L.k)
         for k0 in ((1, 3, 5, 8) if name == "qwen3_30b" else L.k0s):
             ctx = "%s seed=%d k0=%d" % (name, seed, k0)
             out, tap = run_layer_dev(torch, B_, L, dev, k0, ws=ws, bias=L.router_bias)
             err, ref = check_layer(oracle, L, k0, out, tap, ctx, bias=L.router_bias)
             say(ctx, "T=%d sum_n_sel=%d err=%.2e" % (ref["n_active"], int(ref["n_sel"].sum()), err))
+
+
+@pytest.mark.parametrize("path", [2, 1])
+def test_full_size_30b_shape_three_kernel_paths(torch, B_, oracle, path):
+    """Same layer through the three-kernel paths (streaming / generic expert kernels)."""
+    L, dev = big_layer(B_, "qwen3_30b", 2000)
+    B_.set_kernel_path(path)
+    try:
+        for k0 in (3, 8):
+            out, tap = run_layer_dev(torch, B_, L, dev, k0)
+            err, ref = check_layer(oracle, L, k0, out, tap, "path %d k0=%d" % (path, k0))
+            say("path", path, "k0", k0, "T=%d err=%.2e" % (ref["n_active"], err))
+    finally:
+        B_.set_kernel_path(0)
+
+
+def test_fused_kernel_repeatable_and_masked(torch, B_, oracle):
+    """Fused path: many calls in a row on one workspace (barrier state returns to rest), a padding
+    mask, an all-padding batch (no active expert: every workgroup still passes both barriers)."""
+    L, dev = big_layer(B_, "qwen3_30b", 2000)
+    ws = B_.new_workspace(L.B, L.d, L.N, L.I, L.k)
+    first = None
+    for it in range(20):
+        out, tap = run_layer_dev(torch, B_, L, dev, 3, ws=ws)
+        if first is None:
+            first = (out, tap)
+            check_layer(oracle, L, 3, out, tap, "fused repeat 0")
+        else:
+            assert np.array_equal(tap["expert_idx"], first[1]["expert_idx"])
+            assert np.abs(out - first[0]).max() <= 1e-5 * np.abs(first[0]).max()
+    mask = np.ones(L.B, np.uint8)
+    mask[[0, 7, 15]] = 0
+    out, tap = run_layer_dev(torch, B_, L, dev, 3, ws=ws, mask=mask)
+    check_layer(oracle, L, 3, out, tap, "fused mask", mask=mask)
+    out, tap = run_layer_dev(torch, B_, L, dev, 3, ws=ws, mask=np.zeros(L.B, np.uint8))
+    assert int(tap["n_active"][0]) == 0 and (out == 0).all()
+    for B in (1, 5, 16, 17, 32):  # both register-resident routing variants, ragged batches
+        Ls = W.Layer(**{**L.__dict__, "B": B, "x": np.ascontiguousarray(np.resize(L.x, (B, L.d)))})
+        devs = dict(dev, x=B_.to_device(Ls.x))
+        for k0 in (2, 8):
+            out, tap = run_layer_dev(torch, B_, Ls, devs, k0)
+            check_layer(oracle, Ls, k0, out, tap, "fused B=%d k0=%d" % (B, k0))
 
 
 def test_full_size_30b_batch_sweep(torch, B_, oracle):
@@ -244,10 +299,16 @@ def test_full_size_30b_batch_sweep(torch, B_, oracle):
 
 
 def test_full_size_235b_shape(torch, B_, oracle):
+    _BIG.clear()
     L = W.make_layer("qwen3_235b", 3000)
     dev = {f: B_.to_device(getattr(L, f)) for f in ("x", "w_router", "w_gate", "w_up", "w_down")}
-    for k0 in (3, 8):
-        ctx = "qwen3_235b k0=%d" % k0
-        out, tap = run_layer_dev(torch, B_, L, dev, k0)
-        err, ref = check_layer(oracle, L, k0, out, tap, ctx)
-        say(ctx, "T=%d err=%.2e" % (ref["n_active"], err))
+    for path in (0, 2):
+        B_.set_kernel_path(path)
+        try:
+            for k0 in (3, 8):
+                ctx = "qwen3_235b path=%d k0=%d" % (path, k0)
+                out, tap = run_layer_dev(torch, B_, L, dev, k0)
+                err, ref = check_layer(oracle, L, k0, out, tap, ctx)
+                say(ctx, "T=%d err=%.2e" % (ref["n_active"], err))
+        finally:
+            B_.set_kernel_path(0)
