@@ -112,7 +112,7 @@ __global__ __launch_bounds__(kFfnThreads) void expert_kernel(FfnParams p) {
 #pragma unroll
             for (int m = 0; m < NM; ++m) {
               const WT* src = (m == 0 ? wae : wbe) + (size_t)row * L + col;
-              w[m][rg][c] = ok ? *reinterpret_cast<const uint4*>(src) : make_uint4(0, 0, 0, 0);
+              w[m][rg][c] = ok ? load_stream16(src) : make_uint4(0, 0, 0, 0);
             }
           }
         }

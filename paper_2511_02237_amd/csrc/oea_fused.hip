@@ -36,6 +36,10 @@ namespace oea {
 
 namespace {
 
+#ifndef OEA_BARRIER2_MODE
+#define OEA_BARRIER2_MODE 2
+#endif
+
 constexpr size_t kFusedLdsMax = 156 * 1024;
 constexpr int kFusedStage = 8;  // staging loads kept in flight per thread
 
@@ -72,12 +76,16 @@ __host__ __device__ inline size_t fused_meta_words(int B, int N, int k) {
 // thread 0 announces the workgroup (the callers also drain explicitly before they come here).
 // The wait is bounded: after spin_limit polls the workgroup raises the error flag and goes on
 // (its results are then meaningless, but every access stays in bounds and the kernel ends).
-__device__ __forceinline__ void grid_barrier(uint32_t* ctrl, uint32_t spin_limit) {
+// first half: every wavefront of the workgroup has drained its stores; thread 0 announces the
+// workgroup.  Returns (to thread 0 only) the generation to wait on, or ~0u if this workgroup was
+// the last one and has released the others.
+__device__ __forceinline__ uint32_t grid_arrive(uint32_t* ctrl) {
   __syncthreads();
+  uint32_t g = ~0u;
   if (threadIdx.x == 0) {
     uint32_t* count = ctrl + 32;
     uint32_t* gen = ctrl + 64;
-    uint32_t g = __hip_atomic_load(gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    g = __hip_atomic_load(gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     // the read of gen must have been performed before the arrival becomes visible (else a release
     // that follows the arrival at once could be mistaken for the old generation): wait for its value
     asm volatile("" : "+v"(g) : : "memory");
@@ -86,18 +94,31 @@ __device__ __forceinline__ void grid_barrier(uint32_t* ctrl, uint32_t spin_limit
       __hip_atomic_store(count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // count is back to 0 before anyone is released
       __hip_atomic_store(gen, g + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    } else {
-      uint32_t spins = 0;
-      while (__hip_atomic_load(gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == g) {
-        __builtin_amdgcn_s_sleep(2);
-        if (++spins > spin_limit) {
-          atomicExch(ctrl + 3, 1u);
-          break;
-        }
+      g = ~0u;
+    }
+  }
+  return g;
+}
+
+// second half: thread 0 polls the generation (bounded), then the workgroup goes on together
+__device__ __forceinline__ void grid_wait(uint32_t* ctrl, uint32_t g, uint32_t spin_limit) {
+  if (threadIdx.x == 0 && g != ~0u) {
+    uint32_t* gen = ctrl + 64;
+    uint32_t spins = 0;
+    while (__hip_atomic_load(gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == g) {
+      __builtin_amdgcn_s_sleep(2);
+      if (++spins > spin_limit) {
+        atomicExch(ctrl + 3, 1u);
+        break;
       }
     }
   }
   __syncthreads();
+}
+
+__device__ __forceinline__ void grid_barrier(uint32_t* ctrl, uint32_t spin_limit) {
+  const uint32_t g = grid_arrive(ctrl);
+  grid_wait(ctrl, g, spin_limit);
 }
 
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
@@ -123,11 +144,11 @@ __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirs
 // One mat-vec stage of the fused kernel.  Same tile loop as expert_stream_kernel; the routing
 // metadata comes from LDS, and `mid` runs once the first two weight tiles are in flight (it holds
 // the grid barrier and the staging of h for the down stage).  Every workgroup calls mid.
-template <typename WT, int STAGE, int LPR, int NCH, int RG, typename Mid>
+template <typename WT, int STAGE, int LPR, int NCH, int RG, typename Pre, typename Mid>
 __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_out, float* out, int rows, int L,
                                             int T, int N, int pairs_max, int cap_vec, const int* l_active,
                                             const int* l_off, const int* l_tok, const float* l_gw,
-                                            const uint4* l_vec, Mid mid) {
+                                            const uint4* l_vec, Pre pre, Mid mid) {
   constexpr int EPL = 16 / int(sizeof(WT));
   constexpr int R = 64 / LPR;
   constexpr int NM = STAGE == 0 ? 2 : 1;
@@ -162,6 +183,8 @@ __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_ou
   const int my_hi = R0 + int((long long)n_wg * (wave + 1) / kFfnWaves);
   const bool has_work = my_lo < my_hi;
   const SegView sv{rows, a0, e0, e1, e2, off1 - off0, off2 - off1, off3 - off2, my_hi};
+
+  pre();
 
   uint4 wA[NM][RG][NCH], wB[NM][RG][NCH];
   const int r_first = has_work ? my_lo : R0;
@@ -322,7 +345,7 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   // ---- phase A: gate/up
   fused_stage<WT, 0, LPR0, NCH0, 1>(static_cast<const WT*>(p.w_gate), static_cast<const WT*>(p.w_up),
                                     static_cast<WT*>(p.h), p.out, I, d, T, N, P, p.cap_vec, l_active, l_off,
-                                    l_tok, l_gw, l_vec, [](int, int) {});
+                                    l_tok, l_gw, l_vec, []() {}, [](int, int) {});
 
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wavefront's h values have reached memory
   OEA_TL(p.ctrl, 4);
@@ -331,11 +354,18 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   const int I16 = I / EPL;
   uint32_t* const ctrl = p.ctrl;
   const uint32_t spin_limit = p.spin_limit;
+  uint32_t bar_gen = ~0u;
   fused_stage<WT, 1, LPR1, NCH1, 2>(
       static_cast<const WT*>(p.w_down), static_cast<const WT*>(nullptr), static_cast<WT*>(nullptr), p.out, d, I, T,
-      N, P, p.cap_vec, l_active, l_off, l_tok, l_gw, l_vec, [=](int off0, int nvec) {
+      N, P, p.cap_vec, l_active, l_off, l_tok, l_gw, l_vec,
+      [&]() {
+        if (OEA_BARRIER2_MODE == 0) grid_barrier(ctrl, spin_limit);      // barrier, then the first tiles
+        if (OEA_BARRIER2_MODE == 2) bar_gen = grid_arrive(ctrl);          // announce, tiles, then wait
+      },
+      [&](int off0, int nvec) {
         OEA_TL(ctrl, 5);
-        grid_barrier(ctrl, spin_limit);
+        if (OEA_BARRIER2_MODE == 1) grid_barrier(ctrl, spin_limit);      // first tiles, then the barrier
+        if (OEA_BARRIER2_MODE == 2) grid_wait(ctrl, bar_gen, spin_limit);
         OEA_TL(ctrl, 6);
         // h was written by other workgroups (other XCDs): device-coherent 16-byte loads, which
         // exist as buffer loads with the sc0 sc1 bits; the descriptor also bounds the access
