@@ -37,6 +37,7 @@ def parse():
     ap.add_argument("--weight-sets", type=int, default=0, help="rotating expert-weight sets (0 = auto)")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="budget of the oracle timing")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--kernel-path", type=int, default=0, help="0 automatic (fused kernel), 1 generic, 2 three kernels")
     ap.add_argument("--verbose", action="store_true")
     return ap.parse_args()
 
@@ -80,6 +81,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     binding.lib()
+    binding.set_kernel_path(args.kernel_path)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     hip = Hip()

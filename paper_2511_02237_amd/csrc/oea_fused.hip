@@ -36,11 +36,8 @@ namespace oea {
 
 namespace {
 
-#ifndef OEA_BARRIER2_MODE
-#define OEA_BARRIER2_MODE 2
-#endif
-
 constexpr size_t kFusedLdsMax = 156 * 1024;
+#define OEA_MAX_FUSED_N 128  // experts the fused kernel handles (completion words in the control area)
 constexpr int kFusedStage = 8;  // staging loads kept in flight per thread
 
 struct FusedParams {
@@ -55,7 +52,8 @@ struct FusedParams {
   float* logits;   // [B,N] workspace
   void* h;         // [B*k, I] workspace
   RouteOut ro;     // global copies of the routing result, written by workgroup 0
-  uint32_t* ctrl;  // [3] error flag, [32] barrier arrivals, [64] barrier generation (separate 128-byte lines)
+  uint32_t* ctrl;  // [3] error flag, [32] barrier arrivals, [64] barrier generation (separate 128-byte
+                   // lines), from [1024] the per-expert completion counters and flags (done_count, done_flag)
   int B, d, N, I, k, k0;
   int cap_vec;     // most (expert, token) pairs one workgroup can meet in one stage
   uint32_t spin_limit;
@@ -64,48 +62,48 @@ struct FusedParams {
 // words of LDS in front of the vector area (after the 16-byte dump slot)
 __host__ __device__ inline size_t fused_meta_words(int B, int N, int k) {
   const size_t P = (size_t)B * k;
-  size_t w = route_lds_words(B, N) + 4 * P + (size_t)B + (size_t)N + 4 + (size_t)N + 4 + (size_t)B * N;
+  size_t w = route_lds_words(B, N) + 4 * P + (size_t)B + (size_t)N + 4 + (size_t)N + 4 + (size_t)B * N + 2 * ((size_t)N + 4);
   return (w + 3) & ~size_t(3);
 }
 
-// Sense-reversing barrier over all workgroups of the grid.  count returns to 0, gen only grows.
-// There is no cache maintenance in it (a device-scope fence writes back / invalidates the whole L2
-// of the XCD, far too slow here): data that crosses workgroups in this kernel is written with
-// device-coherent stores and read with device-coherent loads instead.  The leading __syncthreads
-// makes every wavefront wait for its own outstanding stores, so they have reached memory before
-// thread 0 announces the workgroup (the callers also drain explicitly before they come here).
+// Barrier over all workgroups of the grid: an arrival counter that returns to 0 and a generation
+// word that only grows, on separate 128-byte lines (the pollers read the generation, the arrivals
+// hit the counter).  The generation is read ONCE per call, at the start of the kernel (no barrier of
+// this call can complete before this workgroup has arrived); barrier i of the call is passed when
+// the generation has reached gen0 + i.  The workgroup whose arrival completes the count resets the
+// counter and publishes the next generation.
+//
+// There is no cache maintenance here (a device-scope fence writes back / invalidates the whole L2
+// of the XCD, far too slow): data that crosses workgroups in this kernel is written with
+// device-coherent stores and read with device-coherent loads.  grid_arrive drains the wavefront's
+// stores before the workgroup's __syncthreads, so they have reached memory before thread 0
+// announces the workgroup.
 // The wait is bounded: after spin_limit polls the workgroup raises the error flag and goes on
 // (its results are then meaningless, but every access stays in bounds and the kernel ends).
-// first half: every wavefront of the workgroup has drained its stores; thread 0 announces the
-// workgroup.  Returns (to thread 0 only) the generation to wait on, or ~0u if this workgroup was
-// the last one and has released the others.
-__device__ __forceinline__ uint32_t grid_arrive(uint32_t* ctrl) {
+__device__ __forceinline__ uint32_t grid_generation(uint32_t* ctrl) {
+  return __hip_atomic_load(ctrl + 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// next = the generation that completes this barrier (thread 0's value is the one used)
+__device__ __forceinline__ void grid_arrive(uint32_t* ctrl, uint32_t next) {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wavefront's stores have reached memory
   __syncthreads();
-  uint32_t g = ~0u;
   if (threadIdx.x == 0) {
     uint32_t* count = ctrl + 32;
-    uint32_t* gen = ctrl + 64;
-    g = __hip_atomic_load(gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    // the read of gen must have been performed before the arrival becomes visible (else a release
-    // that follows the arrival at once could be mistaken for the old generation): wait for its value
-    asm volatile("" : "+v"(g) : : "memory");
     const uint32_t old = __hip_atomic_fetch_add(count, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (old == gridDim.x - 1) {
       __hip_atomic_store(count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // count is back to 0 before anyone is released
-      __hip_atomic_store(gen, g + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      g = ~0u;
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the counter is back to 0 before anyone is released
+      __hip_atomic_store(ctrl + 64, next, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
-  return g;
 }
 
-// second half: thread 0 polls the generation (bounded), then the workgroup goes on together
-__device__ __forceinline__ void grid_wait(uint32_t* ctrl, uint32_t g, uint32_t spin_limit) {
-  if (threadIdx.x == 0 && g != ~0u) {
-    uint32_t* gen = ctrl + 64;
+__device__ __forceinline__ void grid_wait(uint32_t* ctrl, uint32_t next, uint32_t spin_limit) {
+  if (threadIdx.x == 0) {
     uint32_t spins = 0;
-    while (__hip_atomic_load(gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == g) {
+    // signed distance: correct across the wrap of the 32-bit generation
+    while (int(__hip_atomic_load(ctrl + 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - next) < 0) {
       __builtin_amdgcn_s_sleep(2);
       if (++spins > spin_limit) {
         atomicExch(ctrl + 3, 1u);
@@ -114,11 +112,6 @@ __device__ __forceinline__ void grid_wait(uint32_t* ctrl, uint32_t g, uint32_t s
     }
   }
   __syncthreads();
-}
-
-__device__ __forceinline__ void grid_barrier(uint32_t* ctrl, uint32_t spin_limit) {
-  const uint32_t g = grid_arrive(ctrl);
-  grid_wait(ctrl, g, spin_limit);
 }
 
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
@@ -141,14 +134,51 @@ __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirs
   } while (0)
 #endif
 
+// ---- cost-weighted split of the work over the workgroups.
+// A weight row of an expert with c pairs costs about (kRowCost + beta*c): streaming its bytes plus c
+// dot products per weight.  Cutting the concatenated rows of the active experts by BYTES left the
+// workgroups that own popular experts (many tokens) still computing long after the others had
+// finished; cutting by COST lets everyone finish together.  pref[a] = cost of all rows of the
+// active experts before position a (pref[T] = total); the boundary of workgroup b is the row at
+// cost total*b/G.
+constexpr int kRowCost = 64;
+constexpr int kBetaGateUp = 5;  // per pair, gate/up stage (measured: about 0.08 of a row's streaming time)
+constexpr int kBetaDown = 6;    // per pair, down stage
+
+__device__ __forceinline__ int row_at_cost(const int* pref, int T, int rows, long long x) {
+  int lo = 0, hi = T;  // largest a in [0,T) with pref[a] <= x
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if ((long long)pref[mid] <= x)
+      lo = mid;
+    else
+      hi = mid;
+  }
+  const int w = (pref[lo + 1] - pref[lo]) / rows;  // cost of one row of that expert
+  int r = int((x - pref[lo]) / w);
+  r = r < rows ? r : rows;
+  return lo * rows + r;
+}
+
+// this workgroup's rows [R0,R1) of the T*rows concatenated weight rows
+__device__ __forceinline__ void wg_rows(const int* pref, int T, int rows, int& R0, int& R1) {
+  R0 = 0;
+  R1 = 0;
+  if (T <= 0) return;
+  const long long total = pref[T];
+  const int b = blockIdx.x, G = gridDim.x;
+  R0 = b == 0 ? 0 : uniform(row_at_cost(pref, T, rows, total * b / G));
+  R1 = b == G - 1 ? T * rows : uniform(row_at_cost(pref, T, rows, total * (b + 1) / G));
+}
+
 // One mat-vec stage of the fused kernel.  Same tile loop as expert_stream_kernel; the routing
 // metadata comes from LDS, and `mid` runs once the first two weight tiles are in flight (it holds
 // the grid barrier and the staging of h for the down stage).  Every workgroup calls mid.
-template <typename WT, int STAGE, int LPR, int NCH, int RG, typename Pre, typename Mid>
+template <typename WT, int STAGE, int LPR, int NCH, int RG, typename Mid>
 __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_out, float* out, int rows, int L,
-                                            int T, int N, int pairs_max, int cap_vec, const int* l_active,
+                                            int R0, int R1, int N, int pairs_max, int cap_vec, const int* l_active,
                                             const int* l_off, const int* l_tok, const float* l_gw,
-                                            const uint4* l_vec, Pre pre, Mid mid) {
+                                            const uint4* l_vec, Mid mid) {
   constexpr int EPL = 16 / int(sizeof(WT));
   constexpr int R = 64 / LPR;
   constexpr int NM = STAGE == 0 ? 2 : 1;
@@ -158,9 +188,6 @@ __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_ou
   const int lsub = lane % LPR, lrow = lane / LPR;
   const int L16 = L / EPL;
 
-  const int total = T * rows;
-  const int R0 = int((long long)total * blockIdx.x / gridDim.x);
-  const int R1 = int((long long)total * (blockIdx.x + 1) / gridDim.x);
   bool wg_has = R0 < R1;
   const int a0 = wg_has ? R0 / rows : 0;
   const int nseg = wg_has ? (R1 - 1) / rows - a0 + 1 : 0;
@@ -184,8 +211,6 @@ __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_ou
   const bool has_work = my_lo < my_hi;
   const SegView sv{rows, a0, e0, e1, e2, off1 - off0, off2 - off1, off3 - off2, my_hi};
 
-  pre();
-
   uint4 wA[NM][RG][NCH], wB[NM][RG][NCH];
   const int r_first = has_work ? my_lo : R0;
   const int n_first = has_work ? tile_rows(sv, my_lo, TROWS) : 1;
@@ -197,7 +222,7 @@ __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_ou
                                           nB > 0 ? nB : n_first);
   }
 
-  mid(wg_has ? off0 : 0, wg_has ? nvec : 0);
+  mid(a0, wg_has ? nseg : 0, wg_has ? off0 : 0, wg_has ? nvec : 0);
 
   if (!has_work) return;
   const int* const s_tok = l_tok + off0;  // pair lists of this workgroup's experts
@@ -218,6 +243,45 @@ __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_ou
                                           nB > 0 ? nB : n_first);
     if (nA <= 0) break;
   }
+}
+
+// Layout of the per-expert completion words in the control area: counter and flag of the expert at
+// position a of the active list each sit on a 128-byte line of their own (same-line atomics and
+// polls from many workgroups serialise badly).
+constexpr int kDoneBase = 1024;  // first word
+constexpr int kDoneStride = 32;  // words between experts
+__device__ __forceinline__ uint32_t* done_count(uint32_t* ctrl, int a) { return ctrl + kDoneBase + a * kDoneStride; }
+__device__ __forceinline__ uint32_t* done_flag(uint32_t* ctrl, int a) {
+  return ctrl + kDoneBase + (OEA_MAX_FUSED_N + a) * kDoneStride;
+}
+
+// After the gate/up stage: tell the down stage which hidden vectors are complete.  Called by the whole
+// workgroup once every wavefront has drained its h stores.  Thread 0 adds the rows this workgroup
+// produced to the counter of each expert it touched; the arrival that completes an expert (all
+// `rows` hidden units) raises that expert's flag.
+__device__ __forceinline__ void signal_hidden_done(uint32_t* ctrl, int R0, int R1, int rows) {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (threadIdx.x != 0) return;
+  if (R0 >= R1) return;
+  const int a0 = R0 / rows, a1 = (R1 - 1) / rows;
+  uint32_t old[kMaxSeg] = {0, 0, 0};
+  int n[kMaxSeg] = {0, 0, 0};
+#pragma unroll
+  for (int sgm = 0; sgm < kMaxSeg; ++sgm) {
+    const int a = a0 + sgm;
+    if (a <= a1) {
+      const int lo = R0 > a * rows ? R0 : a * rows;
+      const int hi = R1 < (a + 1) * rows ? R1 : (a + 1) * rows;
+      n[sgm] = hi - lo;
+      old[sgm] = __hip_atomic_fetch_add(done_count(ctrl, a), uint32_t(n[sgm]), __ATOMIC_RELAXED,
+                                        __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+#pragma unroll
+  for (int sgm = 0; sgm < kMaxSeg; ++sgm)
+    if (n[sgm] > 0 && old[sgm] + uint32_t(n[sgm]) == uint32_t(rows))
+      __hip_atomic_store(done_flag(ctrl, a0 + sgm), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // d == LPR0*EPL*NCH0 and I == LPR1*EPL*NCH1 exactly; N <= 64*NV; B <= TPW*8.
@@ -244,12 +308,22 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   int* const l_tok = l_off + N + 4;
   float* const l_gw = reinterpret_cast<float*>(l_tok + P);
   float* const l_logits = l_gw + P;  // [B,N]
+  int* const l_prefA = reinterpret_cast<int*>(l_logits + B * N);  // [N+4] cost prefix, gate/up stage
+  int* const l_prefB = l_prefA + N + 4;                           // [N+4] cost prefix, down stage
   uint4* const l_vec = lds4 + 1 + fused_meta_words(B, N, k) / 4;
 
 #ifdef OEA_TIMELINE
   if (threadIdx.x == 0 && blockIdx.x == 0) g_tl_ctrl = p.ctrl;
 #endif
+#ifdef OEA_TIMELINE
+  if (threadIdx.x == 0) {
+    unsigned long long* tl = reinterpret_cast<unsigned long long*>(static_cast<char*>(p.h) + (size_t)p.B * p.k * p.I * 2);
+    tl[1024 + blockIdx.x] = wall_clock64();
+  }
+#endif
   OEA_TL(p.ctrl, 0);
+  uint32_t gen0 = 0;  // thread 0: barrier generation at the start of this call
+  if (tid == 0) gen0 = grid_generation(p.ctrl);
   // ---- phase R1.  x of the batch -> LDS: loads first, written after the logits
   const int d16 = d / EPL;
   const int n16_x = B * d16;
@@ -271,6 +345,12 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
     const int lo = per * wg, hi = lo + per < total ? lo + per : total;
     for (int i = lo + tid; i < hi; i += kFfnThreads)
       __hip_atomic_store(p.out + i, 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+
+  // per-expert completion counters of the gate/up stage: cleared here, before the first grid barrier
+  if (wg == 0 && tid < N) {
+    __hip_atomic_store(done_count(p.ctrl, tid), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(done_flag(p.ctrl, tid), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 
   // router logits: one (token, expert) dot product per wavefront, fp64 accumulation, one rounding
@@ -314,9 +394,9 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
     }
   }
 
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // logits and cleared out words have reached memory
   OEA_TL(p.ctrl, 1);
-  grid_barrier(p.ctrl, p.spin_limit);
+  grid_arrive(p.ctrl, gen0 + 1);  // logits and cleared out words are in memory
+  grid_wait(p.ctrl, gen0 + 1, p.spin_limit);
   OEA_TL(p.ctrl, 2);
 
   // ---- phase R2: routing, replicated per workgroup, result in LDS
@@ -340,32 +420,77 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   }
   int T = uniform(l_nact[0]);
   T = T < 0 ? 0 : (T > N ? N : T);
+  if (tid < 64) {  // cost prefixes of both stages: one wavefront scans the (at most 128) active experts
+    int runA = 0, runB = 0;
+    for (int base = 0; base < T; base += 64) {
+      const int a = base + lane;
+      const int c = a < T ? l_off[a + 1] - l_off[a] : 0;
+      int va = a < T ? I * (kRowCost + kBetaGateUp * c) : 0;
+      int vb = a < T ? d * (kRowCost + kBetaDown * c) : 0;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const int ua = __shfl_up(va, off, 64), ub = __shfl_up(vb, off, 64);
+        if (lane >= off) {
+          va += ua;
+          vb += ub;
+        }
+      }
+      if (a < T) {  // inclusive sums -> entry a+1
+        l_prefA[a + 1] = runA + va;
+        l_prefB[a + 1] = runB + vb;
+      }
+      runA += __shfl(va, 63, 64);
+      runB += __shfl(vb, 63, 64);
+    }
+    if (lane == 0) {
+      l_prefA[0] = 0;
+      l_prefB[0] = 0;
+    }
+  }
+  __syncthreads();
+  int RA0, RA1, RB0, RB1;
+  wg_rows(l_prefA, T, I, RA0, RA1);
+  wg_rows(l_prefB, T, d, RB0, RB1);
   OEA_TL(p.ctrl, 3);
 
   // ---- phase A: gate/up
   fused_stage<WT, 0, LPR0, NCH0, 1>(static_cast<const WT*>(p.w_gate), static_cast<const WT*>(p.w_up),
-                                    static_cast<WT*>(p.h), p.out, I, d, T, N, P, p.cap_vec, l_active, l_off,
-                                    l_tok, l_gw, l_vec, []() {}, [](int, int) {});
+                                    static_cast<WT*>(p.h), p.out, I, d, RA0, RA1, N, P, p.cap_vec, l_active, l_off,
+                                    l_tok, l_gw, l_vec, [](int, int, int, int) {});
+  signal_hidden_done(p.ctrl, RA0, RA1, I);
+#ifdef OEA_TIMELINE
+  if (threadIdx.x == 0) {
+    unsigned long long* tl = reinterpret_cast<unsigned long long*>(static_cast<char*>(p.h) + (size_t)P * I * 2);
+    tl[512 + blockIdx.x] = wall_clock64();
+  }
+#endif
 
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wavefront's h values have reached memory
   OEA_TL(p.ctrl, 4);
   // ---- phase B: down.  mid = barrier (h complete everywhere), then this workgroup's h rows -> LDS
   const WT* const hsrc = static_cast<const WT*>(p.h);
   const int I16 = I / EPL;
   uint32_t* const ctrl = p.ctrl;
   const uint32_t spin_limit = p.spin_limit;
-  uint32_t bar_gen = ~0u;
   fused_stage<WT, 1, LPR1, NCH1, 2>(
-      static_cast<const WT*>(p.w_down), static_cast<const WT*>(nullptr), static_cast<WT*>(nullptr), p.out, d, I, T,
-      N, P, p.cap_vec, l_active, l_off, l_tok, l_gw, l_vec,
-      [&]() {
-        if (OEA_BARRIER2_MODE == 0) grid_barrier(ctrl, spin_limit);      // barrier, then the first tiles
-        if (OEA_BARRIER2_MODE == 2) bar_gen = grid_arrive(ctrl);          // announce, tiles, then wait
-      },
-      [&](int off0, int nvec) {
+      static_cast<const WT*>(p.w_down), static_cast<const WT*>(nullptr), static_cast<WT*>(nullptr), p.out, d, I, RB0,
+      RB1, N, P, p.cap_vec, l_active, l_off, l_tok, l_gw, l_vec,
+      [&](int a0, int nseg, int off0, int nvec) {  // runs once the first weight tiles are requested
         OEA_TL(ctrl, 5);
-        if (OEA_BARRIER2_MODE == 1) grid_barrier(ctrl, spin_limit);      // first tiles, then the barrier
-        if (OEA_BARRIER2_MODE == 2) grid_wait(ctrl, bar_gen, spin_limit);
+        // No grid barrier here: this workgroup only needs the hidden vectors of ITS experts, which
+        // its neighbours produce (both stages cut the expert list in the same proportions).  Wait,
+        // bounded, until each of them is flagged complete.
+        if (tid == 0) {
+          uint32_t spins = 0;
+          for (int sgm = 0; sgm < nseg; ++sgm)
+            while (__hip_atomic_load(done_flag(ctrl, a0 + sgm), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+              __builtin_amdgcn_s_sleep(2);
+              if (++spins > spin_limit) {
+                atomicExch(ctrl + 3, 1u);
+                break;
+              }
+            }
+        }
+        __syncthreads();
         OEA_TL(ctrl, 6);
         // h was written by other workgroups (other XCDs): device-coherent 16-byte loads, which
         // exist as buffer loads with the sc0 sc1 bits; the descriptor also bounds the access
@@ -389,6 +514,12 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
         OEA_TL(ctrl, 7);
       });
   OEA_TL(p.ctrl, 8);
+#ifdef OEA_TIMELINE
+  if (threadIdx.x == 0) {  // per-workgroup stamps in the unused upper half of the bf16 h buffer
+    unsigned long long* tl = reinterpret_cast<unsigned long long*>(static_cast<char*>(p.h) + (size_t)P * I * 2);
+    tl[blockIdx.x] = wall_clock64();
+  }
+#endif
 }
 
 int g_fused_cus = -1;  // CUs when the residency check passed, 0 when it failed, -1 before the check
@@ -429,7 +560,11 @@ hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_g
   }
   const int grid = g_fused_cus;
   if (grid < 1) return hipErrorNotSupported;
-  const int nseg_max = (N + grid - 1) / grid + 1;
+  // most experts one workgroup's cost share can touch: share / cheapest expert, plus the two it may cut
+  const int beta_max = kBetaGateUp > kBetaDown ? kBetaGateUp : kBetaDown;
+  const int beta_min = kBetaGateUp < kBetaDown ? kBetaGateUp : kBetaDown;
+  const long long share_num = (long long)kRowCost * N + (long long)beta_max * B * k;
+  const int nseg_max = int(share_num / ((long long)grid * (kRowCost + beta_min))) + 2;
   if (nseg_max > kMaxSeg) return hipErrorNotSupported;
   long long cap_vec = (long long)nseg_max * B;
   if (cap_vec > (long long)B * k) cap_vec = (long long)B * k;
