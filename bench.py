@@ -9,7 +9,8 @@ nothing is served from the 256 MB infinity cache.  All inputs are in HBM before 
 Prints ONE JSON line.  `value` is the layer latency with OEA at k0=3 (the setting the paper's
 headline reduction is quoted at); the same line carries the latency and unique-expert count for
 every k0 (k0=8 is the unmodified top-k router), the roofline of the dominant kernel (gate/up
-mat-vec stage) measured with HIP events, and the CPU oracle timed on the host cores.
+mat-vec stage, or the single fused kernel) measured with HIP events, and the CPU oracle timed on the
+host cores.
 """
 import argparse
 import ctypes
@@ -38,6 +39,8 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="budget of the oracle timing")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--kernel-path", type=int, default=0, help="0 automatic (fused kernel), 1 generic, 2 three kernels")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain device copy of known size (reference for rocprofv3 --pmc byte counters)")
     ap.add_argument("--verbose", action="store_true")
     return ap.parse_args()
 
@@ -161,6 +164,14 @@ def main():
         parity = float(np.abs(o.cpu().numpy() - ref["out"]).max() / np.abs(ref["out"]).max())
         assert parity <= 5e-3, parity
 
+    if args.calib_copy:  # 256 MiB read + 256 MiB written per copy, by a plain elementwise copy kernel
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- timed region: exactly `steps` calls per (trial, k0), synchronised on both sides
     e0, e1 = hip.event(), hip.event()
     lat_wall, lat_ev = {}, {}
@@ -227,20 +238,30 @@ def main():
         fit = dict(us_per_expert=round(float(slope), 4), intercept_us=round(float(icpt), 2), r2=round(r2, 5),
                    marginal_GBps=round(expert_bytes / float(slope) / 1e3, 1))
 
-    # dominant kernel: gate/up stage streams 2/3 of the expert bytes
+    # dominant kernel.  Automatic path: the whole layer is ONE fused kernel (events [0]..[5] bracket
+    # it) and its algorithmic bytes are the layer's.  Three-kernel paths: the gate/up stage, which
+    # streams 2/3 of the expert bytes.
     T0, pairs0 = stats[(0, args.k0)]
-    gu_us = kern[args.k0][1]
-    gu_bytes = T0 * 2 * d * I * 2 + pairs0 * d * 2 + pairs0 * I * 2  # weights + gathered x + hidden written
-    achieved = gu_bytes / gu_us / 1e3
+    fused = args.kernel_path == 0 and kern[args.k0][1] < 0.25 * kern[args.k0][0]
+    if fused:
+        dom_us = kern[args.k0][0]  # events [0],[1] bracket the one kernel
+        dom_bytes = layer_bytes(T0, pairs0)
+        dom_name = "moe_fused_kernel<bf16> (router + routing + gate/up + down)"
+    else:
+        dom_us = kern[args.k0][1]
+        dom_bytes = T0 * 2 * d * I * 2 + pairs0 * d * 2 + pairs0 * I * 2  # weights + gathered x + hidden written
+        dom_name = "expert_stream_kernel<bf16, gate/up>"
+    achieved = dom_bytes / dom_us / 1e3
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "pmc_traffic_%s.txt" % args.workload)
     if os.path.exists(tpath):
+        key = ("fused" if fused else "gate_up") + "_bytes_per_launch_k0_%d" % args.k0
         for line in open(tpath):
-            if line.startswith("gate_up_bytes_per_launch_k0_%d" % args.k0):
+            if line.startswith(key):
                 traffic = float(line.split("=")[1])
-    roofline = dict(bound="hbm", kernel="expert_kernel<bf16, gate/up>", achieved=round(achieved, 1),
+    roofline = dict(bound="hbm", kernel=dom_name, achieved=round(achieved, 1),
                     peak=HBM_PEAK_GBS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4), traffic=traffic,
-                    bytes_per_launch=int(gu_bytes), us_per_launch=round(gu_us, 2),
+                    bytes_per_launch=int(dom_bytes), us_per_launch=round(dom_us, 2),
                     kernels_us={str(k0_): dict(router_route=round(v[0], 2), gate_up=round(v[1], 2), down=round(v[2], 2))
                                 for k0_, v in kern.items()})
 

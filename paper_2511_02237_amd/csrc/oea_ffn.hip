@@ -266,16 +266,14 @@ __global__ __launch_bounds__(kFfnThreads) void expert_stream_kernel(FfnParams p)
 
   // ---- prologue: first two tiles in flight, then the staged data goes to LDS
   uint4 wA[NM][RG][NCH], wB[NM][RG][NCH];
-  // r_first/n_first is also the dummy target of the prefetches past the end; a wavefront without rows
-  // (fewer rows than wavefronts) still issues its loads, on the workgroup's first row, and discards them:
-  // unconditional loads keep the compiler's count of outstanding loads exact.
+  // Requests past the end of the wavefront's rows (and those of a wavefront without rows) are placeholders
+  // on the row r_first: the loads stay unconditional, which keeps the compiler's count of outstanding
+  // loads exact, but they read one granule only.
   const int r_first = has_work ? my_lo : R0;
-  const int n_first = has_work ? tile_rows(sv, my_lo, TROWS) : 1;
-  int rA = r_first, nA = has_work ? n_first : 0;
+  int rA = r_first, nA = has_work ? tile_rows(sv, my_lo, TROWS) : 0;
   int rB = rA + nA, nB = tile_rows(sv, rB, TROWS);
-  load_tile<WT, NM, LPR, NCH, RG, FULL>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv, r_first), n_first);
-  load_tile<WT, NM, LPR, NCH, RG, FULL>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv, nB > 0 ? rB : r_first),
-                                        nB > 0 ? nB : n_first);
+  load_tile<WT, NM, LPR, NCH, RG, FULL>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv, r_first), nA);
+  load_tile<WT, NM, LPR, NCH, RG, FULL>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv, nB > 0 ? rB : r_first), nB);
 
   __builtin_amdgcn_sched_barrier(0);  // weight tiles are requested before the staged data is consumed
   {
@@ -304,15 +302,13 @@ __global__ __launch_bounds__(kFfnThreads) void expert_stream_kernel(FfnParams p)
                                                     tile_ref(sv, rA), nA);
     rA = rB + nB;
     nA = tile_rows(sv, rA, TROWS);
-    load_tile<WT, NM, LPR, NCH, RG, FULL>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv, nA > 0 ? rA : r_first),
-                                          nA > 0 ? nA : n_first);
+    load_tile<WT, NM, LPR, NCH, RG, FULL>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv, nA > 0 ? rA : r_first), nA);
     if (nB <= 0) break;
     compute_tile<WT, STAGE, NM, LPR, NCH, RG, FULL>(wB, l_tok, l_gw, l_vec, h_out, out, rows, L16, off0, lsub, lrow,
                                                     tile_ref(sv, rB), nB);
     rB = rA + nA;
     nB = tile_rows(sv, rB, TROWS);
-    load_tile<WT, NM, LPR, NCH, RG, FULL>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv, nB > 0 ? rB : r_first),
-                                          nB > 0 ? nB : n_first);
+    load_tile<WT, NM, LPR, NCH, RG, FULL>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv, nB > 0 ? rB : r_first), nB);
     if (nA <= 0) break;
   }
 }

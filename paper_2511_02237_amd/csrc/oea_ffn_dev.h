@@ -123,8 +123,11 @@ __device__ __forceinline__ TileRef tile_ref(const SegView sv, int r) {
   return t;
 }
 
-// Always issues NM*RG*NCH loads.  nrows >= 1; lanes of missing rows re-read the tile's last row,
-// columns past the end re-read the row's last granule (their products are masked in compute).
+// Always issues NM*RG*NCH loads.  nrows >= 1 rows of the tile are wanted; lanes of missing rows
+// re-read the tile's last row, columns past the end re-read the row's last granule (their products
+// are masked in compute).  nrows == 0 is a placeholder request past the end of the wavefront's work
+// (it keeps the number of outstanding loads fixed): every lane then reads the same 16 bytes, so it
+// costs one cache line per load instead of a tile.
 template <typename WT, int NM, int LPR, int NCH, int RG, bool FULL>
 __device__ __forceinline__ void load_tile(uint4 (&w)[NM][RG][NCH], const WT* wa, const WT* wb, int rows, int L,
                                           int lsub, int lrow, const TileRef t, int nrows) {
@@ -132,18 +135,20 @@ __device__ __forceinline__ void load_tile(uint4 (&w)[NM][RG][NCH], const WT* wa,
   constexpr int R = 64 / LPR;
   constexpr int CH = LPR * EPL;
   const size_t ebase = (size_t)t.e * rows * L;
+  const bool real = nrows > 0;
 #pragma unroll
   for (int rg = 0; rg < RG; ++rg) {
     int rr = rg * R + lrow;
     rr = rr < nrows ? rr : nrows - 1;
+    rr = real ? rr : 0;
     const size_t rbase = ebase + (size_t)(t.rloc + rr) * L;
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch) {
       int col = ch * CH + lsub * EPL;
       if (!FULL) col = col < L ? col : L - EPL;
+      col = real ? col : 0;
 #pragma unroll
-      for (int m = 0; m < NM; ++m)
-        w[m][rg][ch] = load_stream16((m == 0 ? wa : wb) + rbase + col);
+      for (int m = 0; m < NM; ++m) w[m][rg][ch] = load_stream16((m == 0 ? wa : wb) + rbase + col);
     }
   }
 }

@@ -213,13 +213,11 @@ __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_ou
 
   uint4 wA[NM][RG][NCH], wB[NM][RG][NCH];
   const int r_first = has_work ? my_lo : R0;
-  const int n_first = has_work ? tile_rows(sv, my_lo, TROWS) : 1;
-  int rA = r_first, nA = has_work ? n_first : 0;
+  int rA = r_first, nA = has_work ? tile_rows(sv, my_lo, TROWS) : 0;
   int rB = rA + nA, nB = tile_rows(sv, rB, TROWS);
   if (wg_has) {  // uniform over the workgroup; a wavefront without rows loads the first row and drops it
-    load_tile<WT, NM, LPR, NCH, RG, true>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv, r_first), n_first);
-    load_tile<WT, NM, LPR, NCH, RG, true>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv, nB > 0 ? rB : r_first),
-                                          nB > 0 ? nB : n_first);
+    load_tile<WT, NM, LPR, NCH, RG, true>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv, r_first), nA);
+    load_tile<WT, NM, LPR, NCH, RG, true>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv, nB > 0 ? rB : r_first), nB);
   }
 
   mid(a0, wg_has ? nseg : 0, wg_has ? off0 : 0, wg_has ? nvec : 0);
@@ -232,15 +230,13 @@ __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_ou
                                                     tile_ref(sv, rA), nA);
     rA = rB + nB;
     nA = tile_rows(sv, rA, TROWS);
-    load_tile<WT, NM, LPR, NCH, RG, true>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv, nA > 0 ? rA : r_first),
-                                          nA > 0 ? nA : n_first);
+    load_tile<WT, NM, LPR, NCH, RG, true>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv, nA > 0 ? rA : r_first), nA);
     if (nB <= 0) break;
     compute_tile<WT, STAGE, NM, LPR, NCH, RG, true, true>(wB, s_tok, s_gw, l_vec, h_out, out, rows, L16, off0, lsub, lrow,
                                                     tile_ref(sv, rB), nB);
     rB = rA + nA;
     nB = tile_rows(sv, rB, TROWS);
-    load_tile<WT, NM, LPR, NCH, RG, true>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv, nB > 0 ? rB : r_first),
-                                          nB > 0 ? nB : n_first);
+    load_tile<WT, NM, LPR, NCH, RG, true>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv, nB > 0 ? rB : r_first), nB);
     if (nA <= 0) break;
   }
 }
