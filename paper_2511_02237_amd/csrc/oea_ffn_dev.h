@@ -91,6 +91,7 @@ struct SegView {
   int e0, e1, e2;        // expert ids of the (up to 3) segments
   int cnt0, cnt1, cnt2;  // (expert, token) pairs per segment
   int my_hi;             // end of this wavefront's rows (concatenated numbering)
+  int my_lo;             // their start (only used for the result buffer in LDS)
 };
 
 struct TileRef {
@@ -98,6 +99,8 @@ struct TileRef {
   int rloc;  // first row inside the expert
   int cnt;   // pairs of that expert
   int vb;    // index of its first pair in the staged lists
+  int ebase;    // result buffer in LDS: entry of the tile's first row for the expert's first pair ...
+  int estride;  // ... and the distance between consecutive pairs (= rows of this segment the wavefront owns)
 };
 
 __device__ __forceinline__ int seg_of(const SegView sv, int r) {
@@ -120,6 +123,34 @@ __device__ __forceinline__ TileRef tile_ref(const SegView sv, int r) {
   t.cnt = s == 0 ? sv.cnt0 : (s == 1 ? sv.cnt1 : sv.cnt2);
   t.vb = s == 0 ? 0 : (s == 1 ? sv.cnt0 : sv.cnt0 + sv.cnt1);
   t.rloc = r - (sv.a0 + s) * sv.rows;
+  t.ebase = 0;
+  t.estride = 0;
+  return t;
+}
+
+// Result buffer of a wavefront (LDS, floats): its rows of segment s form a block [pair][row],
+// the blocks of the segments follow each other.
+__device__ __forceinline__ int seg_lo(const SegView sv, int s) {
+  const int start = (sv.a0 + s) * sv.rows;
+  return start > sv.my_lo ? start : sv.my_lo;
+}
+__device__ __forceinline__ int seg_n(const SegView sv, int s) {  // rows of segment s this wavefront owns
+  const int end = (sv.a0 + s + 1) * sv.rows;
+  const int n = (end < sv.my_hi ? end : sv.my_hi) - seg_lo(sv, s);
+  return n > 0 ? n : 0;
+}
+__device__ __forceinline__ int seg_cnt(const SegView sv, int s) { return s == 0 ? sv.cnt0 : (s == 1 ? sv.cnt1 : sv.cnt2); }
+__device__ __forceinline__ int seg_ebase(const SegView sv, int s) {
+  return (s > 0 ? seg_n(sv, 0) * sv.cnt0 : 0) + (s > 1 ? seg_n(sv, 1) * sv.cnt1 : 0);
+}
+__device__ __forceinline__ int result_entries(const SegView sv) {
+  return seg_n(sv, 0) * sv.cnt0 + seg_n(sv, 1) * sv.cnt1 + seg_n(sv, 2) * sv.cnt2;
+}
+__device__ __forceinline__ TileRef tile_ref_buffered(const SegView sv, int r) {
+  TileRef t = tile_ref(sv, r);
+  const int s = seg_of(sv, r);
+  t.ebase = seg_ebase(sv, s) + (r - seg_lo(sv, s));
+  t.estride = seg_n(sv, s);
   return t;
 }
 
@@ -154,10 +185,13 @@ __device__ __forceinline__ void load_tile(uint4 (&w)[NM][RG][NCH], const WT* wa,
 }
 
 // one (expert, token) pair against the tile held in w: dot products, reduction over the row's lanes, epilogue
-template <typename WT, int STAGE, int NM, int LPR, int NCH, int RG, bool FULL, bool COH = false>
+// use_buf: the results go to the wavefront's result buffer in LDS (entry eidx + row of the
+// tile) instead of memory; flush_results writes them out when the wavefront has streamed all its rows.
+template <typename WT, int STAGE, int NM, int LPR, int NCH, int RG, bool FULL, bool COH = false, bool EBUF = false>
 __device__ __forceinline__ void token_step(const uint4 (&w)[NM][RG][NCH], const int* l_tok, const float* l_gw,
                                            const uint4* l_vec, WT* h_out, float* out, int rows, int L16, int off0,
-                                           int lsub, int lrow, int rloc, int nrows, int pair) {
+                                           int lsub, int lrow, int rloc, int nrows, int pair, float* ebuf = nullptr,
+                                           bool use_buf = false, int eidx = 0) {
   constexpr int R = 64 / LPR;
   const int tok = l_tok[pair];
   const uint4* vq = l_vec + (size_t)(STAGE == 0 ? tok : pair) * L16;
@@ -192,14 +226,21 @@ __device__ __forceinline__ void token_step(const uint4 (&w)[NM][RG][NCH], const 
       const float usum = row_sum<LPR>(acc[NM - 1][rg]);
       if (lsub == 0 && rr < nrows) {
         const float hval = gsum / (1.f + __expf(-gsum)) * usum;
-        if (COH)
+        if (EBUF && use_buf)
+          ebuf[eidx + rr] = hval;
+        else if (COH)
           store_h_coherent(h_out + (size_t)(off0 + pair) * rows + rloc + rr, hval);
         else
           store_h(h_out + (size_t)(off0 + pair) * rows + rloc + rr, hval);
       }
     } else {
       const float y = row_sum<LPR>(acc[0][rg]);
-      if (lsub == 0 && rr < nrows) unsafeAtomicAdd(out + (size_t)tok * rows + rloc + rr, l_gw[pair] * y);
+      if (lsub == 0 && rr < nrows) {
+        if (EBUF && use_buf)
+          ebuf[eidx + rr] = y;
+        else
+          unsafeAtomicAdd(out + (size_t)tok * rows + rloc + rr, l_gw[pair] * y);
+      }
     }
   }
 }
@@ -210,19 +251,50 @@ __device__ __forceinline__ void token_step(const uint4 (&w)[NM][RG][NCH], const 
 // rare expert with more pairs than that.
 constexpr int kUnrollTok = 8;
 
-template <typename WT, int STAGE, int NM, int LPR, int NCH, int RG, bool FULL, bool COH = false>
+template <typename WT, int STAGE, int NM, int LPR, int NCH, int RG, bool FULL, bool COH = false, bool EBUF = false>
 __device__ __forceinline__ void compute_tile(const uint4 (&w)[NM][RG][NCH], const int* l_tok, const float* l_gw,
                                              const uint4* l_vec, WT* h_out, float* out, int rows, int L16,
-                                             int off0, int lsub, int lrow, const TileRef t, int nrows) {
+                                             int off0, int lsub, int lrow, const TileRef t, int nrows,
+                                             float* ebuf = nullptr, bool use_buf = false) {
 #pragma unroll
   for (int q = 0; q < kUnrollTok; ++q)
     if (q < t.cnt)
-      token_step<WT, STAGE, NM, LPR, NCH, RG, FULL, COH>(w, l_tok, l_gw, l_vec, h_out, out, rows, L16, off0, lsub, lrow,
-                                                    t.rloc, nrows, t.vb + q);
+      token_step<WT, STAGE, NM, LPR, NCH, RG, FULL, COH, EBUF>(w, l_tok, l_gw, l_vec, h_out, out, rows, L16, off0, lsub,
+                                                               lrow, t.rloc, nrows, t.vb + q, ebuf, use_buf,
+                                                               t.ebase + q * t.estride);
   if (t.cnt > kUnrollTok)
     for (int q = kUnrollTok; q < t.cnt; ++q)
-      token_step<WT, STAGE, NM, LPR, NCH, RG, FULL, COH>(w, l_tok, l_gw, l_vec, h_out, out, rows, L16, off0, lsub, lrow,
-                                                    t.rloc, nrows, t.vb + q);
+      token_step<WT, STAGE, NM, LPR, NCH, RG, FULL, COH, EBUF>(w, l_tok, l_gw, l_vec, h_out, out, rows, L16, off0, lsub,
+                                                               lrow, t.rloc, nrows, t.vb + q, ebuf, use_buf,
+                                                               t.ebase + q * t.estride);
+}
+
+// Write a wavefront's buffered results to memory: for every segment and pair, its rows are
+// consecutive addresses, so each instruction stores (or adds) 64 neighbouring values.
+//   STAGE 0: h[(off0 + pair), row] = value (device-coherent store, rounded to the storage type)
+//   STAGE 1: out[token, row] += gate weight * value
+template <typename WT, int STAGE>
+__device__ __forceinline__ void flush_results(const SegView sv, const float* ebuf, const int* s_tok, const float* s_gw,
+                                              WT* h_out, float* out, int off0, int lane) {
+  int vb = 0;
+#pragma unroll
+  for (int s = 0; s < kMaxSeg; ++s) {
+    const int n = seg_n(sv, s), cnt = seg_cnt(sv, s);
+    const int rloc = seg_lo(sv, s) - (sv.a0 + s) * sv.rows;
+    const int base = seg_ebase(sv, s);
+    if (n > 0)
+      for (int q = 0; q < cnt; ++q) {
+        const int pair = vb + q;
+        for (int r = lane; r < n; r += 64) {
+          const float v = ebuf[base + q * n + r];
+          if (STAGE == 0)
+            store_h_coherent(h_out + (size_t)(off0 + pair) * sv.rows + rloc + r, v);
+          else
+            unsafeAtomicAdd(out + (size_t)s_tok[pair] * sv.rows + rloc + r, s_gw[pair] * v);
+        }
+      }
+    vb += cnt;
+  }
 }
 
 }  // namespace

@@ -52,10 +52,11 @@ struct FusedParams {
   float* logits;   // [B,N] workspace
   void* h;         // [B*k, I] workspace
   RouteOut ro;     // global copies of the routing result, written by workgroup 0
-  uint32_t* ctrl;  // [3] error flag, [32] barrier arrivals, [64] barrier generation (separate 128-byte
-                   // lines), from [1024] the per-expert completion counters and flags (done_count, done_flag)
+  uint32_t* ctrl;  // [3] error flag, [32] and [256 + 32 i] barrier arrivals, [64] barrier generation (separate
+                   // 128-byte lines), from [1024] the per-expert completion counters and flags (done_count, done_flag)
   int B, d, N, I, k, k0;
   int cap_vec;     // most (expert, token) pairs one workgroup can meet in one stage
+  int ecap0, ecap1;  // floats of LDS result buffer per wavefront, gate/up and down stage (0 = none)
   uint32_t spin_limit;
 };
 
@@ -70,8 +71,8 @@ __host__ __device__ inline size_t fused_meta_words(int B, int N, int k) {
 // word that only grows, on separate 128-byte lines (the pollers read the generation, the arrivals
 // hit the counter).  The generation is read ONCE per call, at the start of the kernel (no barrier of
 // this call can complete before this workgroup has arrived); barrier i of the call is passed when
-// the generation has reached gen0 + i.  The workgroup whose arrival completes the count resets the
-// counter and publishes the next generation.
+// the generation has reached gen0 + i.  The workgroup whose arrival completes the count (which
+// wraps back to 0 by itself) publishes the next generation.
 //
 // There is no cache maintenance here (a device-scope fence writes back / invalidates the whole L2
 // of the XCD, far too slow): data that crosses workgroups in this kernel is written with
@@ -84,18 +85,26 @@ __device__ __forceinline__ uint32_t grid_generation(uint32_t* ctrl) {
   return __hip_atomic_load(ctrl + 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Arrivals go through two levels: workgroup b adds to leaf counter b % kBarrierLeaves, the arrival
+// that completes a leaf adds to the root, the one that completes the root publishes the generation.
+// Atomics on one line execute one after the other (about 20 ns each), so 256 arrivals on a single
+// counter cost 4-5 us; with 16 leaves on lines of their own the two levels take 2 x 16 steps.
+constexpr int kBarrierLeaves = 16;
+constexpr int kBarrierLeafBase = 256;  // ctrl word of leaf 0; one 128-byte line per leaf
+
 // next = the generation that completes this barrier (thread 0's value is the one used)
 __device__ __forceinline__ void grid_arrive(uint32_t* ctrl, uint32_t next) {
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wavefront's stores have reached memory
   __syncthreads();
   if (threadIdx.x == 0) {
-    uint32_t* count = ctrl + 32;
-    const uint32_t old = __hip_atomic_fetch_add(count, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (old == gridDim.x - 1) {
-      __hip_atomic_store(count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the counter is back to 0 before anyone is released
-      __hip_atomic_store(ctrl + 64, next, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
+    const uint32_t G = gridDim.x, b = blockIdx.x;
+    const uint32_t leaf = b % kBarrierLeaves;
+    const uint32_t n_leaves = G < kBarrierLeaves ? G : kBarrierLeaves;
+    const uint32_t members = (G - leaf + kBarrierLeaves - 1) / kBarrierLeaves;  // workgroups on this leaf
+    // wrapping increments: the arrival that completes a counter also returns it to 0, in one atomic
+    if (atomicInc(ctrl + kBarrierLeafBase + 32 * leaf, members - 1) == members - 1)
+      if (atomicInc(ctrl + 32, n_leaves - 1) == n_leaves - 1)
+        __hip_atomic_store(ctrl + 64, next, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 }
 
@@ -134,16 +143,18 @@ __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirs
   } while (0)
 #endif
 
-// ---- cost-weighted split of the work over the workgroups.
+// ---- cost-weighted split of the down stage over the workgroups.
 // A weight row of an expert with c pairs costs about (kRowCost + beta*c): streaming its bytes plus c
-// dot products per weight.  Cutting the concatenated rows of the active experts by BYTES left the
-// workgroups that own popular experts (many tokens) still computing long after the others had
-// finished; cutting by COST lets everyone finish together.  pref[a] = cost of all rows of the
-// active experts before position a (pref[T] = total); the boundary of workgroup b is the row at
-// cost total*b/G.
+// dot products per weight.  Cutting the concatenated rows of the active experts by BYTES leaves the
+// workgroups that own popular experts (many tokens) computing after the others have finished;
+// cutting by COST lets everyone finish together.  pref[a] = cost of all rows of the active experts
+// before position a (pref[T] = total); the boundary of workgroup b is the row at cost total*b/G.
+// (The gate/up stage is cut evenly: its first tiles are requested before the pair counts exist.)
 constexpr int kRowCost = 64;
-constexpr int kBetaGateUp = 5;  // per pair, gate/up stage (measured: about 0.08 of a row's streaming time)
-constexpr int kBetaDown = 6;    // per pair, down stage
+#ifndef OEA_BETA_DOWN
+#define OEA_BETA_DOWN 6
+#endif
+constexpr int kBetaDown = OEA_BETA_DOWN;  // per pair
 
 __device__ __forceinline__ int row_at_cost(const int* pref, int T, int rows, long long x) {
   int lo = 0, hi = T;  // largest a in [0,T) with pref[a] <= x
@@ -178,7 +189,7 @@ template <typename WT, int STAGE, int LPR, int NCH, int RG, typename Mid>
 __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_out, float* out, int rows, int L,
                                             int R0, int R1, int N, int pairs_max, int cap_vec, const int* l_active,
                                             const int* l_off, const int* l_tok, const float* l_gw,
-                                            const uint4* l_vec, Mid mid) {
+                                            const uint4* l_vec, float* ebuf, int ecap, Mid mid) {
   constexpr int EPL = 16 / int(sizeof(WT));
   constexpr int R = 64 / LPR;
   constexpr int NM = STAGE == 0 ? 2 : 1;
@@ -191,54 +202,75 @@ __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_ou
   bool wg_has = R0 < R1;
   const int a0 = wg_has ? R0 / rows : 0;
   const int nseg = wg_has ? (R1 - 1) / rows - a0 + 1 : 0;
-  const int off0 = uniform(l_off[a0]);
-  const int off1 = uniform(l_off[a0 + 1]);
-  const int off2 = nseg > 1 ? uniform(l_off[a0 + 2]) : off1;
-  const int off3 = nseg > 2 ? uniform(l_off[a0 + 3]) : off2;
   const int e0 = uniform(l_active[a0]);
   const int e1 = nseg > 1 ? uniform(l_active[a0 + 1]) : 0;
   const int e2 = nseg > 2 ? uniform(l_active[a0 + 2]) : 0;
-  const int nvec = wg_has ? off3 - off0 : 0;
   // never true for a routing computed by this kernel; keeps every access in bounds regardless
-  if (nseg > kMaxSeg || off0 < 0 || off1 < off0 || off2 < off1 || off3 < off2 || nvec > cap_vec ||
-      off0 + nvec > pairs_max || (unsigned)e0 >= (unsigned)N || (unsigned)e1 >= (unsigned)N ||
-      (unsigned)e2 >= (unsigned)N)
+  if (nseg > kMaxSeg || (unsigned)e0 >= (unsigned)N || (unsigned)e1 >= (unsigned)N || (unsigned)e2 >= (unsigned)N)
     wg_has = false;
 
   const int n_wg = wg_has ? R1 - R0 : 0;
   const int my_lo = R0 + int((long long)n_wg * wave / kFfnWaves);
   const int my_hi = R0 + int((long long)n_wg * (wave + 1) / kFfnWaves);
-  const bool has_work = my_lo < my_hi;
-  const SegView sv{rows, a0, e0, e1, e2, off1 - off0, off2 - off1, off3 - off2, my_hi};
+  bool has_work = my_lo < my_hi;
+  const SegView sv0{rows, a0, e0, e1, e2, 0, 0, 0, my_hi, my_lo};  // the pair counts are not needed to address weights
 
   uint4 wA[NM][RG][NCH], wB[NM][RG][NCH];
   const int r_first = has_work ? my_lo : R0;
-  int rA = r_first, nA = has_work ? tile_rows(sv, my_lo, TROWS) : 0;
-  int rB = rA + nA, nB = tile_rows(sv, rB, TROWS);
+  int rA = r_first, nA = has_work ? tile_rows(sv0, my_lo, TROWS) : 0;
+  int rB = rA + nA, nB = tile_rows(sv0, rB, TROWS);
+#ifndef OEA_EARLY_TILES
+#define OEA_EARLY_TILES 2
+#endif
+  constexpr int kEarly = STAGE == 0 ? OEA_EARLY_TILES : 2;
   if (wg_has) {  // uniform over the workgroup; a wavefront without rows loads the first row and drops it
-    load_tile<WT, NM, LPR, NCH, RG, true>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv, r_first), nA);
-    load_tile<WT, NM, LPR, NCH, RG, true>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv, nB > 0 ? rB : r_first), nB);
+    if (kEarly >= 1) load_tile<WT, NM, LPR, NCH, RG, true>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv0, r_first), nA);
+    if (kEarly >= 2) load_tile<WT, NM, LPR, NCH, RG, true>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv0, nB > 0 ? rB : r_first), nB);
+  }
+  __builtin_amdgcn_sched_barrier(0);  // the requests above are issued before anything in mid
+
+  mid(a0, wg_has ? nseg : 0);
+
+  __builtin_amdgcn_sched_barrier(0);
+  if (wg_has) {
+    if (kEarly < 1) load_tile<WT, NM, LPR, NCH, RG, true>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv0, r_first), nA);
+    if (kEarly < 2) load_tile<WT, NM, LPR, NCH, RG, true>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv0, nB > 0 ? rB : r_first), nB);
   }
 
-  mid(a0, wg_has ? nseg : 0, wg_has ? off0 : 0, wg_has ? nvec : 0);
+  // pair lists of this workgroup's experts (for the gate/up stage mid has just produced them)
+  const int off0 = uniform(l_off[a0]);
+  const int off1 = uniform(l_off[a0 + 1]);
+  const int off2 = nseg > 1 ? uniform(l_off[a0 + 2]) : off1;
+  const int off3 = nseg > 2 ? uniform(l_off[a0 + 3]) : off2;
+  const int nvec = off3 - off0;
+  if (off0 < 0 || off1 < off0 || off2 < off1 || off3 < off2 || nvec > cap_vec || off0 + nvec > pairs_max)
+    has_work = false;  // never true, as above
+  const SegView sv{rows, a0, e0, e1, e2, off1 - off0, off2 - off1, off3 - off2, my_hi, my_lo};
 
   if (!has_work) return;
   const int* const s_tok = l_tok + off0;  // pair lists of this workgroup's experts
   const float* const s_gw = l_gw + off0;
+  // Results are collected in the wavefront's LDS buffer and written out after its last tile: a store
+  // or atomic issued between the weight loads would have to complete (the memory counter retires in
+  // order) before the NEXT tile's data counts as arrived.  A wavefront whose results do not fit
+  // (many rows of a very popular expert) writes them directly instead.
+  float* const eb = ebuf + (size_t)wave * ecap;
+  const bool use_buf = result_entries(sv) <= ecap;
   while (true) {
-    compute_tile<WT, STAGE, NM, LPR, NCH, RG, true, true>(wA, s_tok, s_gw, l_vec, h_out, out, rows, L16, off0, lsub, lrow,
-                                                    tile_ref(sv, rA), nA);
+    compute_tile<WT, STAGE, NM, LPR, NCH, RG, true, true, true>(wA, s_tok, s_gw, l_vec, h_out, out, rows, L16, off0, lsub,
+                                                                lrow, tile_ref_buffered(sv, rA), nA, eb, use_buf);
     rA = rB + nB;
     nA = tile_rows(sv, rA, TROWS);
     load_tile<WT, NM, LPR, NCH, RG, true>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv, nA > 0 ? rA : r_first), nA);
     if (nB <= 0) break;
-    compute_tile<WT, STAGE, NM, LPR, NCH, RG, true, true>(wB, s_tok, s_gw, l_vec, h_out, out, rows, L16, off0, lsub, lrow,
-                                                    tile_ref(sv, rB), nB);
+    compute_tile<WT, STAGE, NM, LPR, NCH, RG, true, true, true>(wB, s_tok, s_gw, l_vec, h_out, out, rows, L16, off0, lsub,
+                                                                lrow, tile_ref_buffered(sv, rB), nB, eb, use_buf);
     rB = rA + nA;
     nB = tile_rows(sv, rB, TROWS);
     load_tile<WT, NM, LPR, NCH, RG, true>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv, nB > 0 ? rB : r_first), nB);
     if (nA <= 0) break;
   }
+  if (use_buf) flush_results<WT, STAGE>(sv, eb, s_tok, s_gw, h_out, out, off0, lane);
 }
 
 // Layout of the per-expert completion words in the control area: counter and flag of the expert at
@@ -304,8 +336,7 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   int* const l_tok = l_off + N + 4;
   float* const l_gw = reinterpret_cast<float*>(l_tok + P);
   float* const l_logits = l_gw + P;  // [B,N]
-  int* const l_prefA = reinterpret_cast<int*>(l_logits + B * N);  // [N+4] cost prefix, gate/up stage
-  int* const l_prefB = l_prefA + N + 4;                           // [N+4] cost prefix, down stage
+  int* const l_prefB = reinterpret_cast<int*>(l_logits + B * N);  // [N+4] cost prefix, down stage
   uint4* const l_vec = lds4 + 1 + fused_meta_words(B, N, k) / 4;
 
 #ifdef OEA_TIMELINE
@@ -400,59 +431,67 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
     l_logits[i] = __hip_atomic_load(p.logits + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   __syncthreads();
   OEA_TL(p.ctrl, 9);
-  {
-    RouteOut lo{l_idx, l_gatew, l_nsel, l_active, l_nact, l_off, l_tok, l_gw};
-    route_block<NV, kFfnThreads, TPW>(l_logits, p.token_mask, B, N, k, p.k0, lo, l_route);
-  }
+  // First half: Phase 1 and the union.  That fixes WHICH weights the layer reads, so the gate/up
+  // stage can request its first tiles before the rest of the routing (Phase 2, weights, grouping)
+  // runs underneath those requests.
+  const RouteOut lo{l_idx, l_gatew, l_nsel, l_active, l_nact, l_off, l_tok, l_gw};
+  const RouteOut gro = p.ro;
+  uint32_t* const ctrl = p.ctrl;
+  const uint8_t* const token_mask = p.token_mask;
+  const int k0 = p.k0;
+  RouteCarry<NV, TPW> carry;
+#ifdef OEA_TL_WARM  // experiment: a first, untimed pass through the routing code (instruction cache warm for the second)
+  route_union<NV, kFfnThreads, TPW>(l_logits, token_mask, B, N, k0, lo, l_route, carry);
   __syncthreads();
-  if (wg == 0) {  // publish the routing result
-    for (int i = tid; i < P; i += kFfnThreads) {
-      p.ro.expert_idx[i] = l_idx[i];
-      p.ro.gate_w[i] = l_gatew[i];
-    }
-    for (int i = tid; i < B; i += kFfnThreads) p.ro.n_sel[i] = l_nsel[i];
-    for (int i = tid; i < N; i += kFfnThreads) p.ro.active_list[i] = l_active[i];
-    if (tid == 0) *p.ro.n_active = l_nact[0];
-  }
+  route_fill<NV, kFfnThreads, TPW>(l_logits, token_mask, B, N, k, k0, lo, l_route, carry);
+  __syncthreads();
+  OEA_TL(p.ctrl, 15);
+#endif
+  route_union<NV, kFfnThreads, TPW>(l_logits, token_mask, B, N, k0, lo, l_route, carry);
+  __syncthreads();
   int T = uniform(l_nact[0]);
   T = T < 0 ? 0 : (T > N ? N : T);
-  if (tid < 64) {  // cost prefixes of both stages: one wavefront scans the (at most 128) active experts
-    int runA = 0, runB = 0;
-    for (int base = 0; base < T; base += 64) {
-      const int a = base + lane;
-      const int c = a < T ? l_off[a + 1] - l_off[a] : 0;
-      int va = a < T ? I * (kRowCost + kBetaGateUp * c) : 0;
-      int vb = a < T ? d * (kRowCost + kBetaDown * c) : 0;
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const int ua = __shfl_up(va, off, 64), ub = __shfl_up(vb, off, 64);
-        if (lane >= off) {
-          va += ua;
-          vb += ub;
-        }
-      }
-      if (a < T) {  // inclusive sums -> entry a+1
-        l_prefA[a + 1] = runA + va;
-        l_prefB[a + 1] = runB + vb;
-      }
-      runA += __shfl(va, 63, 64);
-      runB += __shfl(vb, 63, 64);
-    }
-    if (lane == 0) {
-      l_prefA[0] = 0;
-      l_prefB[0] = 0;
-    }
-  }
-  __syncthreads();
-  int RA0, RA1, RB0, RB1;
-  wg_rows(l_prefA, T, I, RA0, RA1);
-  wg_rows(l_prefB, T, d, RB0, RB1);
+  // gate/up stage: the T*I row pairs are cut evenly (the pair counts are not known yet)
+  const int RA0 = int((long long)T * I * wg / G), RA1 = int((long long)T * I * (wg + 1) / G);
+  int RB0 = 0, RB1 = 0;
   OEA_TL(p.ctrl, 3);
 
   // ---- phase A: gate/up
-  fused_stage<WT, 0, LPR0, NCH0, 1>(static_cast<const WT*>(p.w_gate), static_cast<const WT*>(p.w_up),
-                                    static_cast<WT*>(p.h), p.out, I, d, RA0, RA1, N, P, p.cap_vec, l_active, l_off,
-                                    l_tok, l_gw, l_vec, [](int, int, int, int) {});
+  fused_stage<WT, 0, LPR0, NCH0, 1>(
+      static_cast<const WT*>(p.w_gate), static_cast<const WT*>(p.w_up), static_cast<WT*>(p.h), p.out, I, d, RA0, RA1,
+      N, P, p.cap_vec, l_active, l_off, l_tok, l_gw, l_vec, reinterpret_cast<float*>(l_vec + (size_t)B * d16), p.ecap0,
+      [&](int, int) {  // runs once the first weight tiles are requested
+        route_fill<NV, kFfnThreads, TPW>(l_logits, token_mask, B, N, k, k0, lo, l_route, carry);
+        __syncthreads();
+        if (wg == 0) {  // publish the routing result
+          for (int i = tid; i < P; i += kFfnThreads) {
+            gro.expert_idx[i] = l_idx[i];
+            gro.gate_w[i] = l_gatew[i];
+          }
+          for (int i = tid; i < B; i += kFfnThreads) gro.n_sel[i] = l_nsel[i];
+          for (int i = tid; i < N; i += kFfnThreads) gro.active_list[i] = l_active[i];
+          if (tid == 0) *gro.n_active = l_nact[0];
+        }
+        if (tid < 64) {  // cost prefix of the down stage: one wavefront scans the (at most 128) active experts
+          int run = 0;
+          for (int base = 0; base < T; base += 64) {
+            const int a = base + lane;
+            const int c = a < T ? l_off[a + 1] - l_off[a] : 0;
+            int v = a < T ? d * (kRowCost + kBetaDown * c) : 0;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+              const int u = __shfl_up(v, off, 64);
+              if (lane >= off) v += u;
+            }
+            if (a < T) l_prefB[a + 1] = run + v;  // inclusive sums -> entry a+1
+            run += __shfl(v, 63, 64);
+          }
+          if (lane == 0) l_prefB[0] = 0;
+        }
+        __syncthreads();
+        wg_rows(l_prefB, T, d, RB0, RB1);
+        OEA_TL(ctrl, 14);
+      });
   signal_hidden_done(p.ctrl, RA0, RA1, I);
 #ifdef OEA_TIMELINE
   if (threadIdx.x == 0) {
@@ -465,16 +504,17 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   // ---- phase B: down.  mid = barrier (h complete everywhere), then this workgroup's h rows -> LDS
   const WT* const hsrc = static_cast<const WT*>(p.h);
   const int I16 = I / EPL;
-  uint32_t* const ctrl = p.ctrl;
   const uint32_t spin_limit = p.spin_limit;
+  const int cap_vec = p.cap_vec;
   fused_stage<WT, 1, LPR1, NCH1, 2>(
       static_cast<const WT*>(p.w_down), static_cast<const WT*>(nullptr), static_cast<WT*>(nullptr), p.out, d, I, RB0,
       RB1, N, P, p.cap_vec, l_active, l_off, l_tok, l_gw, l_vec,
-      [&](int a0, int nseg, int off0, int nvec) {  // runs once the first weight tiles are requested
+      reinterpret_cast<float*>(l_vec + (size_t)cap_vec * I16), p.ecap1,
+      [&](int a0, int nseg) {  // runs once the first weight tiles are requested
         OEA_TL(ctrl, 5);
         // No grid barrier here: this workgroup only needs the hidden vectors of ITS experts, which
-        // its neighbours produce (both stages cut the expert list in the same proportions).  Wait,
-        // bounded, until each of them is flagged complete.
+        // its neighbours produce (both stages cut the expert list in about the same proportions).
+        // Wait, bounded, until each of them is flagged complete.
         if (tid == 0) {
           uint32_t spins = 0;
           for (int sgm = 0; sgm < nseg; ++sgm)
@@ -488,6 +528,9 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
         }
         __syncthreads();
         OEA_TL(ctrl, 6);
+        const int off0 = uniform(l_off[a0]);
+        int nvec = uniform(l_off[a0 + nseg]) - off0;
+        if (off0 < 0 || nvec < 0 || nvec > cap_vec || off0 + nvec > P) nvec = 0;  // never true; bounds the copy
         // h was written by other workgroups (other XCDs): device-coherent 16-byte loads, which
         // exist as buffer loads with the sc0 sc1 bits; the descriptor also bounds the access
         const int n16 = nvec * I16;
@@ -556,17 +599,28 @@ hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_g
   }
   const int grid = g_fused_cus;
   if (grid < 1) return hipErrorNotSupported;
-  // most experts one workgroup's cost share can touch: share / cheapest expert, plus the two it may cut
-  const int beta_max = kBetaGateUp > kBetaDown ? kBetaGateUp : kBetaDown;
-  const int beta_min = kBetaGateUp < kBetaDown ? kBetaGateUp : kBetaDown;
-  const long long share_num = (long long)kRowCost * N + (long long)beta_max * B * k;
-  const int nseg_max = int(share_num / ((long long)grid * (kRowCost + beta_min))) + 2;
+  // most experts one workgroup's share can touch.  Down stage (cut by cost): share / cheapest expert,
+  // plus the two it may cut; gate/up stage (cut evenly): rows of at most ceil(N/grid) experts plus one.
+  const long long share_num = (long long)kRowCost * N + (long long)kBetaDown * B * k;
+  const int nseg_down = int(share_num / ((long long)grid * (kRowCost + kBetaDown))) + 2;
+  const int nseg_up = (N + grid - 1) / grid + 1;
+  const int nseg_max = nseg_down > nseg_up ? nseg_down : nseg_up;
   if (nseg_max > kMaxSeg) return hipErrorNotSupported;
   long long cap_vec = (long long)nseg_max * B;
   if (cap_vec > (long long)B * k) cap_vec = (long long)B * k;
   const size_t vec_x = (size_t)B * d * 2, vec_h = (size_t)cap_vec * I * 2;
-  size_t lds_bytes = 16 + fused_meta_words(B, N, k) * 4 + (vec_x > vec_h ? vec_x : vec_h);
-  if (lds_bytes > kFusedLdsMax) return hipErrorNotSupported;
+  const size_t fixed = 16 + fused_meta_words(B, N, k) * 4;
+  if (fixed + (vec_x > vec_h ? vec_x : vec_h) > kFusedLdsMax) return hipErrorNotSupported;
+  // what is left of the LDS holds the wavefronts' result buffers (at most 2048 floats each)
+  auto result_cap = [&](size_t vec) {
+    size_t per_wave = (kFusedLdsMax - fixed - vec) / (kFfnWaves * sizeof(float));
+    per_wave = per_wave > 2048 ? 2048 : per_wave & ~size_t(3);
+    return per_wave >= 64 ? (int)per_wave : 0;
+  };
+  const int ecap0 = result_cap(vec_x), ecap1 = result_cap(vec_h);
+  const size_t need0 = vec_x + (size_t)ecap0 * kFfnWaves * sizeof(float);
+  const size_t need1 = vec_h + (size_t)ecap1 * kFfnWaves * sizeof(float);
+  size_t lds_bytes = fixed + (need0 > need1 ? need0 : need1);
   const size_t alone = 84 * 1024;  // more than half of a CU's LDS: exactly one workgroup per CU
   if (lds_bytes < alone) lds_bytes = alone;
 
@@ -590,6 +644,8 @@ hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_g
   p.k = k;
   p.k0 = k0;
   p.cap_vec = (int)cap_vec;
+  p.ecap0 = ecap0;
+  p.ecap1 = ecap1;
   p.spin_limit = 4u << 20;  // polls of >= 100 ns each: gives up after about a second
   if (shape30) {
     if (B <= 16) return launch_fused_one<uint16_t, 32, 8, 16, 6, 2, 2>(p, lds_bytes, s);

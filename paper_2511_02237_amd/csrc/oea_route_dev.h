@@ -93,67 +93,52 @@ __host__ __device__ inline size_t route_lds_words(int B, int N) {
   return 64 + (size_t)N * ((B + 31) / 32) + (size_t)N;
 }
 
+// Routing state that a wavefront carries from the first half of route_block to the second.
+template <int NV, int TPW>
+struct RouteCarry {
+  static constexpr int TP = TPW > 0 ? TPW : 1;
+  uint32_t keep[TP][NV];  // TPW > 0: the wavefront's candidate keys after Phase 1
+  int sel_id[TP];         // lane r holds the expert of rank r
+  float sel_logit[TP];
+  int sel_n[TP];
+};
+
 // Executed by ONE workgroup of NT threads (NT/64 wavefronts, NT >= N).  lds: route_lds_words(B,N) words.
 // TPW > 0 (requires B <= TPW * NT/64): every wavefront owns at most TPW tokens and keeps their
 // candidate keys in registers across the barrier, so Phase 2 continues where Phase 1 stopped.
 // TPW == 0: any B; Phase 2 starts over from the logits.
 // The RouteOut pointers may point to global memory or to LDS.
+//
+// First half: Phase 1 of Algorithm 1 and the union.  On return (after the caller's next
+// __syncthreads) o.active_list and *o.n_active are complete: everything the expert stages need to
+// know WHICH weights will be read.
 template <int NV, int NT, int TPW>
-__device__ void route_block(const float* __restrict__ logits, const uint8_t* __restrict__ token_mask,
-                            int B, int N, int k, int k0, RouteOut o, uint32_t* lds) {
+__device__ __forceinline__ void route_union(const float* __restrict__ logits, const uint8_t* __restrict__ token_mask,
+                                            int B, int N, int k0, RouteOut o, uint32_t* lds,
+                                            RouteCarry<NV, TPW>& c) {
   constexpr int NW = NT / 64;
-  constexpr int TP = TPW > 0 ? TPW : 1;
+  constexpr int TP = RouteCarry<NV, TPW>::TP;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int NWB = (B + 31) >> 5;
-  uint32_t* U = lds;                   // [16] union bit mask over experts
-  uint32_t* scan = lds + 16;           // [48] scratch for block scans
-  uint32_t* colmask = lds + 64;        // [N*NWB] per expert: bit mask of the tokens routed to it
-  uint32_t* eoff = colmask + N * NWB;  // [N] per expert: first pair in the grouped order
+  uint32_t* U = lds;          // [16] union bit mask over experts
+  uint32_t* scan = lds + 16;  // [48] scratch for block scans
 
   for (int i = tid; i < int(route_lds_words(B, N)); i += NT) lds[i] = 0;
   __syncthreads();
   OEA_ROUTE_TL(10);
 
-  uint32_t keep[TP][NV];  // TPW > 0: the wavefront's keys after Phase 1
-  int sel_id[TP];         // lane r holds the expert of rank r
-  float sel_logit[TP];
-  int sel_n[TP];
-
   // ---- pass 1: Phase 1 of Algorithm 1, S_i^base = k0 best experts; U = union over the batch
-  auto phase1 = [&](int t, uint32_t (&key)[NV], int& n, int& my_id, float& my_logit) __attribute__((always_inline)) {
-    const bool live = !(token_mask && token_mask[t] == 0);
-#pragma unroll
-    for (int j = 0; j < NV; ++j) {
-      int e = lane + 64 * j;
-      key[j] = (live && e < N) ? make_key(logits[(size_t)t * N + e]) : 0;
-    }
-    n = 0;
-    my_id = -1;
-    my_logit = 0.f;
-    for (int r = 0; r < k0; ++r) {
-      uint32_t bk;
-      int id;
-      if (!pick_best<NV>(key, lane, bk, id)) break;
-      if (lane == 0) atomicOr(&U[id >> 5], 1u << (id & 31));
-      if (lane == r) {
-        my_id = id;
-        my_logit = from_orderable(bk);
-      }
-      ++n;
-    }
-  };
   if (TPW > 0) {
 #pragma unroll
     for (int i = 0; i < TP; ++i) {
       const int t = wave + i * NW;
       const bool live = t < B && !(token_mask && token_mask[t] == 0);
-      sel_n[i] = 0;
-      sel_id[i] = -1;
-      sel_logit[i] = 0.f;
+      c.sel_n[i] = 0;
+      c.sel_id[i] = -1;
+      c.sel_logit[i] = 0.f;
 #pragma unroll
       for (int j = 0; j < NV; ++j) {
         int e = lane + 64 * j;
-        keep[i][j] = (live && e < N) ? make_key(logits[(size_t)(live ? t : 0) * N + e]) : 0;
+        c.keep[i][j] = (live && e < N) ? make_key(logits[(size_t)(live ? t : 0) * N + e]) : 0;
       }
     }
     // rounds outside, tokens inside: the wavefront's tokens form independent dependency chains
@@ -162,40 +147,72 @@ __device__ void route_block(const float* __restrict__ logits, const uint8_t* __r
       for (int i = 0; i < TP; ++i) {
         uint32_t bk;
         int id;
-        if (pick_best<NV>(keep[i], lane, bk, id)) {
+        if (pick_best<NV>(c.keep[i], lane, bk, id)) {
           if (lane == 0) atomicOr(&U[id >> 5], 1u << (id & 31));
           if (lane == r) {
-            sel_id[i] = id;
-            sel_logit[i] = from_orderable(bk);
+            c.sel_id[i] = id;
+            c.sel_logit[i] = from_orderable(bk);
           }
-          ++sel_n[i];
+          ++c.sel_n[i];
         }
       }
     }
   } else {
     for (int t = wave; t < B; t += NW) {
+      const bool live = !(token_mask && token_mask[t] == 0);
       uint32_t key[NV];
-      int n, id;
-      float lg;
-      phase1(t, key, n, id, lg);
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        int e = lane + 64 * j;
+        key[j] = (live && e < N) ? make_key(logits[(size_t)t * N + e]) : 0;
+      }
+      for (int r = 0; r < k0; ++r) {
+        uint32_t bk;
+        int id;
+        if (!pick_best<NV>(key, lane, bk, id)) break;
+        if (lane == 0) atomicOr(&U[id >> 5], 1u << (id & 31));
+      }
     }
   }
   __syncthreads();
   OEA_ROUTE_TL(11);
 
-  // ---- pass 2: Phase 2 in closed form: the token's best members of U up to k in all, then weights.
+  // ---- active list: members of U in ascending order
+  const int e = tid;
+  const bool in_u = e < N && ((U[e >> 5] >> (e & 31)) & 1u);
+  const uint64_t ballot = __ballot(in_u);
+  if (lane == 0) scan[wave] = uint32_t(__popcll(ballot));
+  __syncthreads();
+  int pos_base = 0, T = 0;
+  for (int w = 0; w < NW; ++w) {
+    const int a = int(scan[w]);
+    if (w < wave) pos_base += a;
+    T += a;
+  }
+  const int pos = pos_base + __popcll(ballot & ((1ull << lane) - 1ull));
+  if (in_u) o.active_list[pos] = e;
+  if (e < N && e >= T) o.active_list[e] = -1;
+  if (tid == 0) *o.n_active = T;
+}
+
+// Second half: Phase 2 in closed form (the token's best members of U up to k in all), the weights of
+// Eq. 1, and the expert -> (token, weight) grouping.  Needs a __syncthreads between route_union and
+// this call only if o.active_list / o.n_active are read in between; its own barriers order the rest.
+template <int NV, int NT, int TPW>
+__device__ __forceinline__ void route_fill(const float* __restrict__ logits, const uint8_t* __restrict__ token_mask,
+                                           int B, int N, int k, int k0, RouteOut o, uint32_t* lds,
+                                           RouteCarry<NV, TPW>& c) {
+  constexpr int NW = NT / 64;
+  constexpr int TP = RouteCarry<NV, TPW>::TP;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int NWB = (B + 31) >> 5;
+  uint32_t* U = lds;
+  uint32_t* scan = lds + 16;
+  uint32_t* colmask = lds + 64;        // [N*NWB] per expert: bit mask of the tokens routed to it
+  uint32_t* eoff = colmask + N * NWB;  // [N] per expert: first pair in the grouped order
+
   // Every Phase-1 pick is in U and outranks the rest, so with kept keys Phase 2 just continues.
-  auto phase2 = [&](int t, uint32_t (&key)[NV], int n, int my_id, float my_logit) __attribute__((always_inline)) {
-    for (int r = n; r < k; ++r) {
-      uint32_t bk;
-      int id;
-      if (!pick_best<NV>(key, lane, bk, id)) break;
-      if (lane == r) {
-        my_id = id;
-        my_logit = from_orderable(bk);
-      }
-      ++n;
-    }
+  auto finish = [&](int t, int n, int my_id, float my_logit) __attribute__((always_inline)) {
     // g_s = exp(l_s - m) / sum_{s'} exp(l_s' - m): the softmax denominator cancels in Eq. 1
     float m = __shfl(my_logit, 0, 64);
     float w = lane < n ? expf(my_logit - m) : 0.f;
@@ -214,31 +231,26 @@ __device__ void route_block(const float* __restrict__ logits, const uint8_t* __r
       for (int j = 0; j < NV; ++j) {
         int e = lane + 64 * j;
         bool cand = e < N && ((U[e >> 5] >> (e & 31)) & 1u);
-        if (!cand) keep[i][j] = 0;
+        if (!cand) c.keep[i][j] = 0;
       }
     for (int r = k0; r < k; ++r) {  // every live token holds exactly k0 picks here
 #pragma unroll
       for (int i = 0; i < TP; ++i) {
         uint32_t bk;
         int id;
-        if (pick_best<NV>(keep[i], lane, bk, id)) {
-          if (lane == sel_n[i]) {
-            sel_id[i] = id;
-            sel_logit[i] = from_orderable(bk);
+        if (pick_best<NV>(c.keep[i], lane, bk, id)) {
+          if (lane == c.sel_n[i]) {
+            c.sel_id[i] = id;
+            c.sel_logit[i] = from_orderable(bk);
           }
-          ++sel_n[i];
+          ++c.sel_n[i];
         }
       }
     }
 #pragma unroll
     for (int i = 0; i < TP; ++i) {
       const int t = wave + i * NW;
-      if (t < B) {
-        uint32_t none[NV];
-#pragma unroll
-        for (int j = 0; j < NV; ++j) none[j] = 0;
-        phase2(t, none, sel_n[i], sel_id[i], sel_logit[i]);  // no candidate left: only weights and stores
-      }
+      if (t < B) finish(t, c.sel_n[i], c.sel_id[i], c.sel_logit[i]);
     }
   } else {
     for (int t = wave; t < B; t += NW) {
@@ -250,17 +262,29 @@ __device__ void route_block(const float* __restrict__ logits, const uint8_t* __r
         bool cand = live && e < N && ((U[e >> 5] >> (e & 31)) & 1u);
         key[j] = cand ? make_key(logits[(size_t)t * N + e]) : 0;
       }
-      phase2(t, key, 0, -1, 0.f);
+      int n = 0, my_id = -1;
+      float my_logit = 0.f;
+      for (int r = 0; r < k; ++r) {
+        uint32_t bk;
+        int id;
+        if (!pick_best<NV>(key, lane, bk, id)) break;
+        if (lane == r) {
+          my_id = id;
+          my_logit = from_orderable(bk);
+        }
+        ++n;
+      }
+      finish(t, n, my_id, my_logit);
     }
   }
   __syncthreads();
   OEA_ROUTE_TL(12);
+  if (!o.grp_off) return;
 
-  // ---- pass 3a: active list (ascending ids), pairs per expert, CSR offsets
+  // ---- pairs per expert, CSR offsets by position in the active list
   const int e = tid;
   const bool in_u = e < N && ((U[e >> 5] >> (e & 31)) & 1u);
-  uint64_t ballot = __ballot(in_u);
-  if (lane == 0) scan[wave] = uint32_t(__popcll(ballot));
+  const uint64_t ballot = __ballot(in_u);
   int cnt = 0;
   if (in_u)
     for (int w = 0; w < NWB; ++w) cnt += __popc(colmask[e * NWB + w]);
@@ -271,23 +295,20 @@ __device__ void route_block(const float* __restrict__ logits, const uint8_t* __r
     if (lane >= off) incl += v;
   }
   if (lane == 63) scan[16 + wave] = uint32_t(incl);
+  if (lane == 0) scan[32 + wave] = uint32_t(__popcll(ballot));
   __syncthreads();
   int pos_base = 0, cnt_base = 0, T = 0, P = 0;
   for (int w = 0; w < NW; ++w) {
-    int a = int(scan[w]), c = int(scan[16 + w]);
+    const int a = int(scan[32 + w]), cw = int(scan[16 + w]);
     if (w < wave) {
       pos_base += a;
-      cnt_base += c;
+      cnt_base += cw;
     }
     T += a;
-    P += c;
+    P += cw;
   }
   const int pos = pos_base + __popcll(ballot & ((1ull << lane) - 1ull));
   const int excl = cnt_base + incl - cnt;
-  if (in_u) o.active_list[pos] = e;
-  if (e < N && e >= T) o.active_list[e] = -1;
-  if (tid == 0) *o.n_active = T;
-  if (!o.grp_off) return;
   if (in_u) {
     o.grp_off[pos] = excl;
     eoff[e] = uint32_t(excl);
@@ -296,7 +317,7 @@ __device__ void route_block(const float* __restrict__ logits, const uint8_t* __r
   __syncthreads();
   OEA_ROUTE_TL(13);
 
-  // ---- pass 3b: one thread per (token, slot) pair; inside an expert, pairs are in token order
+  // ---- one thread per (token, slot) pair; inside an expert, pairs are in token order
   for (int p = tid; p < B * k; p += NT) {
     const int ex = o.expert_idx[p];
     if (ex < 0) continue;
@@ -307,6 +328,14 @@ __device__ void route_block(const float* __restrict__ logits, const uint8_t* __r
     o.grp_tok[dst] = t;
     o.grp_gw[dst] = o.gate_w[p];
   }
+}
+
+template <int NV, int NT, int TPW>
+__device__ void route_block(const float* __restrict__ logits, const uint8_t* __restrict__ token_mask,
+                            int B, int N, int k, int k0, RouteOut o, uint32_t* lds) {
+  RouteCarry<NV, TPW> c;
+  route_union<NV, NT, TPW>(logits, token_mask, B, N, k0, o, lds, c);
+  route_fill<NV, NT, TPW>(logits, token_mask, B, N, k, k0, o, lds, c);
 }
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
