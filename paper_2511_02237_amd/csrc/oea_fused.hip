@@ -63,7 +63,7 @@ struct FusedParams {
 // words of LDS in front of the vector area (after the 16-byte dump slot)
 __host__ __device__ inline size_t fused_meta_words(int B, int N, int k) {
   const size_t P = (size_t)B * k;
-  size_t w = route_lds_words(B, N) + 4 * P + (size_t)B + (size_t)N + 4 + (size_t)N + 4 + (size_t)B * N + 2 * ((size_t)N + 4);
+  size_t w = route_lds_words(B, N) + 4 * P + (size_t)B + (size_t)N + 4 + (size_t)N + 4 + (size_t)B * N;
   return (w + 3) & ~size_t(3);
 }
 
@@ -143,43 +143,42 @@ __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirs
   } while (0)
 #endif
 
-// ---- cost-weighted split of the down stage over the workgroups.
+// ---- cost-weighted split of a stage over the workgroups.
 // A weight row of an expert with c pairs costs about (kRowCost + beta*c): streaming its bytes plus c
 // dot products per weight.  Cutting the concatenated rows of the active experts by BYTES leaves the
-// workgroups that own popular experts (many tokens) computing after the others have finished;
-// cutting by COST lets everyone finish together.  pref[a] = cost of all rows of the active experts
-// before position a (pref[T] = total); the boundary of workgroup b is the row at cost total*b/G.
-// (The gate/up stage is cut evenly: its first tiles are requested before the pair counts exist.)
+// workgroups that own popular experts (many tokens) computing after the others have finished (in
+// the gate/up stage about 1.6 us per extra token at B=16, and the down stage of an expert cannot
+// start before its slowest gate/up part); cutting by COST lets everyone finish together.
+// With off[] the CSR offsets of the pairs, the cost of all rows of the active experts before
+// position a is rows * (kRowCost*a + beta*off[a]); workgroup b starts at the row at cost total*b/G.
 constexpr int kRowCost = 64;
-#ifndef OEA_BETA_DOWN
-#define OEA_BETA_DOWN 6
+#ifndef OEA_BETA_UP
+#define OEA_BETA_UP 3
 #endif
-constexpr int kBetaDown = OEA_BETA_DOWN;  // per pair
+#ifndef OEA_BETA_DOWN
+#define OEA_BETA_DOWN 12
+#endif
+constexpr int kBetaUp = OEA_BETA_UP;      // per pair, gate/up stage
+constexpr int kBetaDown = OEA_BETA_DOWN;  // per pair, down stage (also makes up for what is left of the gate/up skew)
 
-__device__ __forceinline__ int row_at_cost(const int* pref, int T, int rows, long long x) {
-  int lo = 0, hi = T;  // largest a in [0,T) with pref[a] <= x
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if ((long long)pref[mid] <= x)
-      lo = mid;
-    else
-      hi = mid;
-  }
-  const int w = (pref[lo + 1] - pref[lo]) / rows;  // cost of one row of that expert
-  int r = int((x - pref[lo]) / w);
-  r = r < rows ? r : rows;
-  return lo * rows + r;
-}
-
-// this workgroup's rows [R0,R1) of the T*rows concatenated weight rows
-__device__ __forceinline__ void wg_rows(const int* pref, int T, int rows, int& R0, int& R1) {
-  R0 = 0;
-  R1 = 0;
-  if (T <= 0) return;
-  const long long total = pref[T];
-  const int b = blockIdx.x, G = gridDim.x;
-  R0 = b == 0 ? 0 : uniform(row_at_cost(pref, T, rows, total * b / G));
-  R1 = b == G - 1 ? T * rows : uniform(row_at_cost(pref, T, rows, total * (b + 1) / G));
+// First row of workgroup b (b in [0,G]) in the concatenated numbering.  Called by whole wavefronts
+// (every lane tests two positions of the active list, T <= 128); the result is wave-uniform and the
+// same in every workgroup.
+__device__ __forceinline__ int wg_first_row(const int* l_off, int T, int rows, int beta, int b, int G, int lane) {
+  if (b <= 0 || T <= 0) return 0;
+  if (b >= G) return T * rows;
+  const long long total = (long long)kRowCost * T + (long long)beta * l_off[T];  // in units of one row
+  const long long x = total * rows * b / G;
+  const int a0 = lane, a1 = lane + 64;
+  const long long p0 = (long long)rows * ((long long)kRowCost * a0 + (long long)beta * l_off[a0 < T ? a0 : T]);
+  const long long p1 = (long long)rows * ((long long)kRowCost * a1 + (long long)beta * l_off[a1 < T ? a1 : T]);
+  const int below = __popcll(__ballot(a0 < T && p0 <= x)) + __popcll(__ballot(a1 < T && p1 <= x));
+  const int lo = below > 0 ? below - 1 : 0;  // largest position whose prefix cost is <= x
+  const int off_lo = l_off[lo];
+  const long long w = kRowCost + (long long)beta * (l_off[lo + 1] - off_lo);
+  long long r = (x - (long long)rows * ((long long)kRowCost * lo + (long long)beta * off_lo)) / w;
+  r = r < 0 ? 0 : (r > rows ? rows : r);
+  return uniform(lo * rows + int(r));
 }
 
 // One mat-vec stage of the fused kernel.  Same tile loop as expert_stream_kernel; the routing
@@ -312,8 +311,8 @@ __device__ __forceinline__ void signal_hidden_done(uint32_t* ctrl, int R0, int R
       __hip_atomic_store(done_flag(ctrl, a0 + sgm), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// d == LPR0*EPL*NCH0 and I == LPR1*EPL*NCH1 exactly; N <= 64*NV; B <= TPW*8.
-template <typename WT, int LPR0, int NCH0, int LPR1, int NCH1, int NV, int TPW>
+// d == LPR0*EPL*NCH0 and I == LPR1*EPL*NCH1 exactly; N <= 64*NV; B <= 32; k <= 16.
+template <typename WT, int LPR0, int NCH0, int LPR1, int NCH1, int NV>
 __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   extern __shared__ uint4 lds4[];
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -336,8 +335,7 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   int* const l_tok = l_off + N + 4;
   float* const l_gw = reinterpret_cast<float*>(l_tok + P);
   float* const l_logits = l_gw + P;  // [B,N]
-  int* const l_prefB = reinterpret_cast<int*>(l_logits + B * N);  // [N+4] cost prefix, down stage
-  uint4* const l_vec = lds4 + 1 + fused_meta_words(B, N, k) / 4;
+  uint4* const l_vec = lds4 + 1 + fused_meta_words(B, N, k) / 4;  // after l_logits
 
 #ifdef OEA_TIMELINE
   if (threadIdx.x == 0 && blockIdx.x == 0) g_tl_ctrl = p.ctrl;
@@ -431,67 +429,34 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
     l_logits[i] = __hip_atomic_load(p.logits + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   __syncthreads();
   OEA_TL(p.ctrl, 9);
-  // First half: Phase 1 and the union.  That fixes WHICH weights the layer reads, so the gate/up
-  // stage can request its first tiles before the rest of the routing (Phase 2, weights, grouping)
-  // runs underneath those requests.
   const RouteOut lo{l_idx, l_gatew, l_nsel, l_active, l_nact, l_off, l_tok, l_gw};
-  const RouteOut gro = p.ro;
   uint32_t* const ctrl = p.ctrl;
-  const uint8_t* const token_mask = p.token_mask;
-  const int k0 = p.k0;
-  RouteCarry<NV, TPW> carry;
-#ifdef OEA_TL_WARM  // experiment: a first, untimed pass through the routing code (instruction cache warm for the second)
-  route_union<NV, kFfnThreads, TPW>(l_logits, token_mask, B, N, k0, lo, l_route, carry);
+  {
+    RowCarry<4 * NV> carry;  // one DPP row of 16 lanes per token, 4 * NV keys per lane
+    route_union_rows<4 * NV, kFfnThreads>(l_logits, p.token_mask, B, N, p.k0, lo, l_route, carry);
+    route_fill_rows<4 * NV, kFfnThreads>(B, N, k, p.k0, lo, l_route, carry);
+  }
   __syncthreads();
-  route_fill<NV, kFfnThreads, TPW>(l_logits, token_mask, B, N, k, k0, lo, l_route, carry);
-  __syncthreads();
-  OEA_TL(p.ctrl, 15);
-#endif
-  route_union<NV, kFfnThreads, TPW>(l_logits, token_mask, B, N, k0, lo, l_route, carry);
-  __syncthreads();
+  if (wg == 0) {  // publish the routing result
+    for (int i = tid; i < P; i += kFfnThreads) {
+      p.ro.expert_idx[i] = l_idx[i];
+      p.ro.gate_w[i] = l_gatew[i];
+    }
+    for (int i = tid; i < B; i += kFfnThreads) p.ro.n_sel[i] = l_nsel[i];
+    for (int i = tid; i < N; i += kFfnThreads) p.ro.active_list[i] = l_active[i];
+    if (tid == 0) *p.ro.n_active = l_nact[0];
+  }
   int T = uniform(l_nact[0]);
   T = T < 0 ? 0 : (T > N ? N : T);
-  // gate/up stage: the T*I row pairs are cut evenly (the pair counts are not known yet)
-  const int RA0 = int((long long)T * I * wg / G), RA1 = int((long long)T * I * (wg + 1) / G);
-  int RB0 = 0, RB1 = 0;
+  const int RA0 = wg_first_row(l_off, T, I, kBetaUp, wg, G, lane), RA1 = wg_first_row(l_off, T, I, kBetaUp, wg + 1, G, lane);
+  const int RB0 = wg_first_row(l_off, T, d, kBetaDown, wg, G, lane), RB1 = wg_first_row(l_off, T, d, kBetaDown, wg + 1, G, lane);
   OEA_TL(p.ctrl, 3);
 
   // ---- phase A: gate/up
-  fused_stage<WT, 0, LPR0, NCH0, 1>(
-      static_cast<const WT*>(p.w_gate), static_cast<const WT*>(p.w_up), static_cast<WT*>(p.h), p.out, I, d, RA0, RA1,
-      N, P, p.cap_vec, l_active, l_off, l_tok, l_gw, l_vec, reinterpret_cast<float*>(l_vec + (size_t)B * d16), p.ecap0,
-      [&](int, int) {  // runs once the first weight tiles are requested
-        route_fill<NV, kFfnThreads, TPW>(l_logits, token_mask, B, N, k, k0, lo, l_route, carry);
-        __syncthreads();
-        if (wg == 0) {  // publish the routing result
-          for (int i = tid; i < P; i += kFfnThreads) {
-            gro.expert_idx[i] = l_idx[i];
-            gro.gate_w[i] = l_gatew[i];
-          }
-          for (int i = tid; i < B; i += kFfnThreads) gro.n_sel[i] = l_nsel[i];
-          for (int i = tid; i < N; i += kFfnThreads) gro.active_list[i] = l_active[i];
-          if (tid == 0) *gro.n_active = l_nact[0];
-        }
-        if (tid < 64) {  // cost prefix of the down stage: one wavefront scans the (at most 128) active experts
-          int run = 0;
-          for (int base = 0; base < T; base += 64) {
-            const int a = base + lane;
-            const int c = a < T ? l_off[a + 1] - l_off[a] : 0;
-            int v = a < T ? d * (kRowCost + kBetaDown * c) : 0;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-              const int u = __shfl_up(v, off, 64);
-              if (lane >= off) v += u;
-            }
-            if (a < T) l_prefB[a + 1] = run + v;  // inclusive sums -> entry a+1
-            run += __shfl(v, 63, 64);
-          }
-          if (lane == 0) l_prefB[0] = 0;
-        }
-        __syncthreads();
-        wg_rows(l_prefB, T, d, RB0, RB1);
-        OEA_TL(ctrl, 14);
-      });
+  fused_stage<WT, 0, LPR0, NCH0, 1>(static_cast<const WT*>(p.w_gate), static_cast<const WT*>(p.w_up),
+                                    static_cast<WT*>(p.h), p.out, I, d, RA0, RA1, N, P, p.cap_vec, l_active, l_off,
+                                    l_tok, l_gw, l_vec, reinterpret_cast<float*>(l_vec + (size_t)B * d16), p.ecap0,
+                                    [](int, int) {});
   signal_hidden_done(p.ctrl, RA0, RA1, I);
 #ifdef OEA_TIMELINE
   if (threadIdx.x == 0) {
@@ -563,9 +528,9 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
 
 int g_fused_cus = -1;  // CUs when the residency check passed, 0 when it failed, -1 before the check
 
-template <typename WT, int LPR0, int NCH0, int LPR1, int NCH1, int NV, int TPW>
+template <typename WT, int LPR0, int NCH0, int LPR1, int NCH1, int NV>
 hipError_t launch_fused_one(const FusedParams& p, size_t lds_bytes, hipStream_t s) {
-  auto kern = moe_fused_kernel<WT, LPR0, NCH0, LPR1, NCH1, NV, TPW>;
+  auto kern = moe_fused_kernel<WT, LPR0, NCH0, LPR1, NCH1, NV>;
   static int checked = 0;  // 1 = usable, -1 = not
   if (checked == 0) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -588,7 +553,7 @@ hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_g
                             const void* w_down, const float* bias, const uint8_t* token_mask, float* out,
                             float* logits, void* h, RouteOut ro, uint32_t* ctrl, int B, int d, int N, int I,
                             int k, int k0, oea_dtype dt, hipStream_t s) {
-  if (dt != OEA_BF16 || N > 128 || B > 32) return hipErrorNotSupported;
+  if (dt != OEA_BF16 || N > 128 || B > 32 || k > 16) return hipErrorNotSupported;
   const bool shape30 = d == 2048 && I == 768, shape235 = d == 4096 && I == 1536;
   if (!shape30 && !shape235) return hipErrorNotSupported;
   if (g_fused_cus < 0) {
@@ -599,12 +564,10 @@ hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_g
   }
   const int grid = g_fused_cus;
   if (grid < 1) return hipErrorNotSupported;
-  // most experts one workgroup's share can touch.  Down stage (cut by cost): share / cheapest expert,
-  // plus the two it may cut; gate/up stage (cut evenly): rows of at most ceil(N/grid) experts plus one.
-  const long long share_num = (long long)kRowCost * N + (long long)kBetaDown * B * k;
-  const int nseg_down = int(share_num / ((long long)grid * (kRowCost + kBetaDown))) + 2;
-  const int nseg_up = (N + grid - 1) / grid + 1;
-  const int nseg_max = nseg_down > nseg_up ? nseg_down : nseg_up;
+  // most experts one workgroup's cost share can touch: share / cheapest expert, plus the two it may cut
+  const int beta_hi = kBetaUp > kBetaDown ? kBetaUp : kBetaDown, beta_lo = kBetaUp < kBetaDown ? kBetaUp : kBetaDown;
+  const long long share_num = (long long)kRowCost * N + (long long)beta_hi * B * k;
+  const int nseg_max = int(share_num / ((long long)grid * (kRowCost + beta_lo))) + 2;
   if (nseg_max > kMaxSeg) return hipErrorNotSupported;
   long long cap_vec = (long long)nseg_max * B;
   if (cap_vec > (long long)B * k) cap_vec = (long long)B * k;
@@ -647,12 +610,8 @@ hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_g
   p.ecap0 = ecap0;
   p.ecap1 = ecap1;
   p.spin_limit = 4u << 20;  // polls of >= 100 ns each: gives up after about a second
-  if (shape30) {
-    if (B <= 16) return launch_fused_one<uint16_t, 32, 8, 16, 6, 2, 2>(p, lds_bytes, s);
-    return launch_fused_one<uint16_t, 32, 8, 16, 6, 2, 4>(p, lds_bytes, s);
-  }
-  if (B <= 16) return launch_fused_one<uint16_t, 64, 8, 32, 6, 2, 2>(p, lds_bytes, s);
-  return launch_fused_one<uint16_t, 64, 8, 32, 6, 2, 4>(p, lds_bytes, s);
+  if (shape30) return launch_fused_one<uint16_t, 32, 8, 16, 6, 2>(p, lds_bytes, s);
+  return launch_fused_one<uint16_t, 64, 8, 32, 6, 2>(p, lds_bytes, s);
 }
 
 }  // namespace oea

@@ -93,6 +93,96 @@ __host__ __device__ inline size_t route_lds_words(int B, int N) {
   return 64 + (size_t)N * ((B + 31) / 32) + (size_t)N;
 }
 
+// Tail of the first half: the members of the union bit mask U (lds[0..15]) in ascending order ->
+// o.active_list, their number -> *o.n_active.  Called by all NT threads after a barrier that
+// completes U; the results are complete after the caller's next barrier.
+template <int NT>
+__device__ __forceinline__ void route_active(int N, RouteOut o, uint32_t* lds) {
+  constexpr int NW = NT / 64;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  uint32_t* U = lds;
+  uint32_t* scan = lds + 16;
+  const int e = tid;
+  const bool in_u = e < N && ((U[e >> 5] >> (e & 31)) & 1u);
+  const uint64_t ballot = __ballot(in_u);
+  if (lane == 0) scan[wave] = uint32_t(__popcll(ballot));
+  __syncthreads();
+  int pos_base = 0, T = 0;
+  for (int w = 0; w < NW; ++w) {
+    const int a = int(scan[w]);
+    if (w < wave) pos_base += a;
+    T += a;
+  }
+  const int pos = pos_base + __popcll(ballot & ((1ull << lane) - 1ull));
+  if (in_u) o.active_list[pos] = e;
+  if (e < N && e >= T) o.active_list[e] = -1;
+  if (tid == 0) *o.n_active = T;
+}
+
+
+// Tail of the second half: pairs per expert (from the token bit masks colmask), CSR offsets by
+// position in the active list, and the grouped (token, weight) lists.  Called by all NT threads
+// after a barrier that completes colmask, o.expert_idx and o.gate_w.
+template <int NT>
+__device__ __forceinline__ void route_group(int B, int N, int k, RouteOut o, uint32_t* lds) {
+  constexpr int NW = NT / 64;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int NWB = (B + 31) >> 5;
+  uint32_t* U = lds;
+  uint32_t* scan = lds + 16;
+  uint32_t* colmask = lds + 64;
+  uint32_t* eoff = colmask + N * NWB;
+  if (!o.grp_off) return;
+  // ---- pairs per expert, CSR offsets by position in the active list
+  const int e = tid;
+  const bool in_u = e < N && ((U[e >> 5] >> (e & 31)) & 1u);
+  const uint64_t ballot = __ballot(in_u);
+  int cnt = 0;
+  if (in_u)
+    for (int w = 0; w < NWB; ++w) cnt += __popc(colmask[e * NWB + w]);
+  int incl = cnt;  // inclusive scan of cnt inside the wave
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    int v = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += v;
+  }
+  if (lane == 63) scan[16 + wave] = uint32_t(incl);
+  if (lane == 0) scan[32 + wave] = uint32_t(__popcll(ballot));
+  __syncthreads();
+  int pos_base = 0, cnt_base = 0, T = 0, P = 0;
+  for (int w = 0; w < NW; ++w) {
+    const int a = int(scan[32 + w]), cw = int(scan[16 + w]);
+    if (w < wave) {
+      pos_base += a;
+      cnt_base += cw;
+    }
+    T += a;
+    P += cw;
+  }
+  const int pos = pos_base + __popcll(ballot & ((1ull << lane) - 1ull));
+  const int excl = cnt_base + incl - cnt;
+  if (in_u) {
+    o.grp_off[pos] = excl;
+    eoff[e] = uint32_t(excl);
+  }
+  if (tid == 0) o.grp_off[T] = P;
+  __syncthreads();
+  OEA_ROUTE_TL(13);
+
+  // ---- one thread per (token, slot) pair; inside an expert, pairs are in token order
+  for (int p = tid; p < B * k; p += NT) {
+    const int ex = o.expert_idx[p];
+    if (ex < 0) continue;
+    const int t = p / k;
+    int rank = __popc(colmask[ex * NWB + (t >> 5)] & ((1u << (t & 31)) - 1u));
+    for (int w = 0; w < (t >> 5); ++w) rank += __popc(colmask[ex * NWB + w]);
+    const int dst = int(eoff[ex]) + rank;
+    o.grp_tok[dst] = t;
+    o.grp_gw[dst] = o.gate_w[p];
+  }
+}
+
+
 // Routing state that a wavefront carries from the first half of route_block to the second.
 template <int NV, int TPW>
 struct RouteCarry {
@@ -119,8 +209,7 @@ __device__ __forceinline__ void route_union(const float* __restrict__ logits, co
   constexpr int NW = NT / 64;
   constexpr int TP = RouteCarry<NV, TPW>::TP;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  uint32_t* U = lds;          // [16] union bit mask over experts
-  uint32_t* scan = lds + 16;  // [48] scratch for block scans
+  uint32_t* U = lds;  // [16] union bit mask over experts ([16..63]: scratch for block scans)
 
   for (int i = tid; i < int(route_lds_words(B, N)); i += NT) lds[i] = 0;
   __syncthreads();
@@ -177,22 +266,7 @@ __device__ __forceinline__ void route_union(const float* __restrict__ logits, co
   __syncthreads();
   OEA_ROUTE_TL(11);
 
-  // ---- active list: members of U in ascending order
-  const int e = tid;
-  const bool in_u = e < N && ((U[e >> 5] >> (e & 31)) & 1u);
-  const uint64_t ballot = __ballot(in_u);
-  if (lane == 0) scan[wave] = uint32_t(__popcll(ballot));
-  __syncthreads();
-  int pos_base = 0, T = 0;
-  for (int w = 0; w < NW; ++w) {
-    const int a = int(scan[w]);
-    if (w < wave) pos_base += a;
-    T += a;
-  }
-  const int pos = pos_base + __popcll(ballot & ((1ull << lane) - 1ull));
-  if (in_u) o.active_list[pos] = e;
-  if (e < N && e >= T) o.active_list[e] = -1;
-  if (tid == 0) *o.n_active = T;
+  route_active<NT>(N, o, lds);
 }
 
 // Second half: Phase 2 in closed form (the token's best members of U up to k in all), the weights of
@@ -207,9 +281,7 @@ __device__ __forceinline__ void route_fill(const float* __restrict__ logits, con
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int NWB = (B + 31) >> 5;
   uint32_t* U = lds;
-  uint32_t* scan = lds + 16;
-  uint32_t* colmask = lds + 64;        // [N*NWB] per expert: bit mask of the tokens routed to it
-  uint32_t* eoff = colmask + N * NWB;  // [N] per expert: first pair in the grouped order
+  uint32_t* colmask = lds + 64;  // [N*NWB] per expert: bit mask of the tokens routed to it ([N] more: CSR scratch)
 
   // Every Phase-1 pick is in U and outranks the rest, so with kept keys Phase 2 just continues.
   auto finish = [&](int t, int n, int my_id, float my_logit) __attribute__((always_inline)) {
@@ -279,55 +351,140 @@ __device__ __forceinline__ void route_fill(const float* __restrict__ logits, con
   }
   __syncthreads();
   OEA_ROUTE_TL(12);
-  if (!o.grp_off) return;
+  route_group<NT>(B, N, k, o, lds);
+}
 
-  // ---- pairs per expert, CSR offsets by position in the active list
-  const int e = tid;
-  const bool in_u = e < N && ((U[e >> 5] >> (e & 31)) & 1u);
-  const uint64_t ballot = __ballot(in_u);
-  int cnt = 0;
-  if (in_u)
-    for (int w = 0; w < NWB; ++w) cnt += __popc(colmask[e * NWB + w]);
-  int incl = cnt;  // inclusive scan of cnt inside the wave
+// ---------------------------------------------------------------------------------------------
+// Row-per-token variant for small expert counts (N <= 16*NK, k <= 16, B <= 4*NT/64): a token is
+// handled by one DPP row of 16 lanes (lane li of the row holds the keys of experts li + 16 j), so a
+// wavefront ranks four tokens with the same instructions, and a round of the arg-max is pure vector
+// code: row-wide max of the keys, then row-wide min of the expert ids that hold that key (ties go to
+// the lower id), no scalar round trip and no branch.  Token t sits in wavefront t / RPW, row t % RPW.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_min_u32(uint32_t v) {
+  const uint32_t o = uint32_t(__builtin_amdgcn_update_dpp(0, int(v), CTRL, 0xF, 0xF, true));
+  return o < v ? o : v;
+}
+__device__ __forceinline__ uint32_t row_max_u32(uint32_t v) {  // all 16 lanes of a row get the row's max
+  v = dpp_max_u32<0xB1>(v);
+  v = dpp_max_u32<0x4E>(v);
+  v = dpp_max_u32<0x141>(v);
+  v = dpp_max_u32<0x140>(v);
+  return v;
+}
+__device__ __forceinline__ uint32_t row_min_u32(uint32_t v) {
+  v = dpp_min_u32<0xB1>(v);
+  v = dpp_min_u32<0x4E>(v);
+  v = dpp_min_u32<0x141>(v);
+  v = dpp_min_u32<0x140>(v);
+  return v;
+}
+__device__ __forceinline__ float row_sum_f32(float v) {
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));
+  return v;
+}
+
+template <int NK>
+struct RowCarry {
+  uint32_t key[NK];  // candidate keys of the row's token (0 = taken / not a candidate)
+  uint32_t sel_id;   // lane r of the row: expert of rank r
+  uint32_t sel_key;  // and its key
+  uint32_t top_key;  // key of rank 0 (every lane of the row)
+  int n;             // picks so far (every lane of the row)
+  int t;             // the row's token, -1 if none
+};
+
+// one round for all rows: pick the best remaining candidate of every row's token, store it at rank
+// `rank` (wave-uniform)
+template <int NK>
+__device__ __forceinline__ void row_pick(RowCarry<NK>& c, int li, int rank) {
+  uint32_t lm = c.key[0];
 #pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    int v = __shfl_up(incl, off, 64);
-    if (lane >= off) incl += v;
+  for (int j = 1; j < NK; ++j) lm = c.key[j] > lm ? c.key[j] : lm;
+  const uint32_t m = row_max_u32(lm);
+  uint32_t cand = 0xffffu;  // lowest expert id among this lane's keys equal to m
+#pragma unroll
+  for (int j = NK - 1; j >= 0; --j) cand = c.key[j] == m ? uint32_t(li + 16 * j) : cand;
+  const uint32_t win = row_min_u32(cand);
+  const bool valid = m != 0;
+#pragma unroll
+  for (int j = 0; j < NK; ++j) c.key[j] = uint32_t(li + 16 * j) == win ? 0u : c.key[j];
+  if (valid && li == rank) {
+    c.sel_id = win;
+    c.sel_key = m;
   }
-  if (lane == 63) scan[16 + wave] = uint32_t(incl);
-  if (lane == 0) scan[32 + wave] = uint32_t(__popcll(ballot));
-  __syncthreads();
-  int pos_base = 0, cnt_base = 0, T = 0, P = 0;
-  for (int w = 0; w < NW; ++w) {
-    const int a = int(scan[32 + w]), cw = int(scan[16 + w]);
-    if (w < wave) {
-      pos_base += a;
-      cnt_base += cw;
-    }
-    T += a;
-    P += cw;
-  }
-  const int pos = pos_base + __popcll(ballot & ((1ull << lane) - 1ull));
-  const int excl = cnt_base + incl - cnt;
-  if (in_u) {
-    o.grp_off[pos] = excl;
-    eoff[e] = uint32_t(excl);
-  }
-  if (tid == 0) o.grp_off[T] = P;
-  __syncthreads();
-  OEA_ROUTE_TL(13);
+  if (rank == 0) c.top_key = m;
+  c.n += valid ? 1 : 0;
+}
 
-  // ---- one thread per (token, slot) pair; inside an expert, pairs are in token order
-  for (int p = tid; p < B * k; p += NT) {
-    const int ex = o.expert_idx[p];
-    if (ex < 0) continue;
-    const int t = p / k;
-    int rank = __popc(colmask[ex * NWB + (t >> 5)] & ((1u << (t & 31)) - 1u));
-    for (int w = 0; w < (t >> 5); ++w) rank += __popc(colmask[ex * NWB + w]);
-    const int dst = int(eoff[ex]) + rank;
-    o.grp_tok[dst] = t;
-    o.grp_gw[dst] = o.gate_w[p];
+template <int NK, int NT>
+__device__ __forceinline__ void route_union_rows(const float* __restrict__ logits,
+                                                 const uint8_t* __restrict__ token_mask, int B, int N, int k0,
+                                                 RouteOut o, uint32_t* lds, RowCarry<NK>& c) {
+  constexpr int NW = NT / 64;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 15, row = lane >> 4;
+  const int RPW = B <= NW ? 1 : (B <= 2 * NW ? 2 : 4);  // rows in use per wavefront
+  uint32_t* U = lds;
+
+  for (int i = tid; i < int(route_lds_words(B, N)); i += NT) lds[i] = 0;
+  const int t = wave * RPW + row;
+  const bool have = row < RPW && t < B;
+  const bool live = have && !(token_mask && token_mask[t] == 0);
+  c.t = have ? t : -1;
+  c.n = 0;
+  c.sel_id = 0;
+  c.sel_key = 0;
+  c.top_key = 0;
+#pragma unroll
+  for (int j = 0; j < NK; ++j) {
+    const int e = li + 16 * j;
+    c.key[j] = (live && e < N) ? make_key(logits[(size_t)(live ? t : 0) * N + e]) : 0;
   }
+  __syncthreads();  // U is cleared
+  OEA_ROUTE_TL(10);
+  // ---- Phase 1 of Algorithm 1: S_i^base = the k0 best experts
+  for (int r = 0; r < k0; ++r) row_pick<NK>(c, li, r);
+  if (li < c.n) atomicOr(&U[c.sel_id >> 5], 1u << (c.sel_id & 31));
+  __syncthreads();
+  OEA_ROUTE_TL(11);
+  route_active<NT>(N, o, lds);
+}
+
+template <int NK, int NT>
+__device__ __forceinline__ void route_fill_rows(int B, int N, int k, int k0, RouteOut o, uint32_t* lds,
+                                                RowCarry<NK>& c) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int li = lane & 15;
+  const int NWB = (B + 31) >> 5;
+  uint32_t* U = lds;
+  uint32_t* colmask = lds + 64;
+  // ---- Phase 2 in closed form: continue on the candidates that are in U, up to k picks.
+  // A live token holds exactly k0 picks here (k0 <= N), so the next rank is the round number.
+#pragma unroll
+  for (int j = 0; j < NK; ++j) {
+    const int e = li + 16 * j;  // e < 16*NK <= 512: inside U's 16 words
+    if (!((U[e >> 5] >> (e & 31)) & 1u)) c.key[j] = 0;
+  }
+  for (int r = k0; r < k; ++r) row_pick<NK>(c, li, r);
+  // weights: g_s = exp(l_s - l_top) / sum_s' exp(l_s' - l_top) (Eq. 1; the softmax denominator cancels)
+  const float w = li < c.n ? expf(from_orderable(c.sel_key) - from_orderable(c.top_key)) : 0.f;
+  const float z = row_sum_f32(w);
+  if (c.t >= 0) {
+    const int t = c.t;
+    if (li < k) {
+      o.expert_idx[(size_t)t * k + li] = li < c.n ? int(c.sel_id) : -1;
+      o.gate_w[(size_t)t * k + li] = li < c.n ? w / z : 0.f;
+    }
+    if (li < c.n) atomicOr(&colmask[c.sel_id * NWB + (t >> 5)], 1u << (t & 31));
+    if (li == 0) o.n_sel[t] = c.n;
+  }
+  __syncthreads();
+  OEA_ROUTE_TL(12);
+  route_group<NT>(B, N, k, o, lds);
 }
 
 template <int NV, int NT, int TPW>
