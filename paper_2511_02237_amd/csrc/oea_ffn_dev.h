@@ -128,13 +128,13 @@ __device__ __forceinline__ TileRef tile_ref(const SegView sv, int r) {
   return t;
 }
 
-// Result buffer of a wavefront (LDS, floats): its rows of segment s form a block [pair][row],
+// Result buffer (LDS, floats) for the rows [my_lo, my_hi): the rows of segment s form a block [pair][row],
 // the blocks of the segments follow each other.
 __device__ __forceinline__ int seg_lo(const SegView sv, int s) {
   const int start = (sv.a0 + s) * sv.rows;
   return start > sv.my_lo ? start : sv.my_lo;
 }
-__device__ __forceinline__ int seg_n(const SegView sv, int s) {  // rows of segment s this wavefront owns
+__device__ __forceinline__ int seg_n(const SegView sv, int s) {  // rows of segment s inside [my_lo, my_hi)
   const int end = (sv.a0 + s + 1) * sv.rows;
   const int n = (end < sv.my_hi ? end : sv.my_hi) - seg_lo(sv, s);
   return n > 0 ? n : 0;
@@ -269,13 +269,13 @@ __device__ __forceinline__ void compute_tile(const uint4 (&w)[NM][RG][NCH], cons
                                                                t.ebase + q * t.estride);
 }
 
-// Write a wavefront's buffered results to memory: for every segment and pair, its rows are
-// consecutive addresses, so each instruction stores (or adds) 64 neighbouring values.
+// Write the workgroup's buffered results to memory (all kFfnThreads threads): for every segment
+// and pair its rows are consecutive addresses, so neighbouring threads store (or add) neighbours.
 //   STAGE 0: h[(off0 + pair), row] = value (device-coherent store, rounded to the storage type)
 //   STAGE 1: out[token, row] += gate weight * value
 template <typename WT, int STAGE>
 __device__ __forceinline__ void flush_results(const SegView sv, const float* ebuf, const int* s_tok, const float* s_gw,
-                                              WT* h_out, float* out, int off0, int lane) {
+                                              WT* h_out, float* out, int off0, int tid) {
   int vb = 0;
 #pragma unroll
   for (int s = 0; s < kMaxSeg; ++s) {
@@ -285,7 +285,7 @@ __device__ __forceinline__ void flush_results(const SegView sv, const float* ebu
     if (n > 0)
       for (int q = 0; q < cnt; ++q) {
         const int pair = vb + q;
-        for (int r = lane; r < n; r += 64) {
+        for (int r = tid; r < n; r += kFfnThreads) {
           const float v = ebuf[base + q * n + r];
           if (STAGE == 0)
             store_h_coherent(h_out + (size_t)(off0 + pair) * sv.rows + rloc + r, v);

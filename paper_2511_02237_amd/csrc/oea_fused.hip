@@ -183,18 +183,27 @@ __device__ __forceinline__ int wg_first_row(const int* l_off, int T, int rows, i
 
 // One mat-vec stage of the fused kernel.  Same tile loop as expert_stream_kernel; the routing
 // metadata comes from LDS, and `mid` runs once the first two weight tiles are in flight (it holds
-// the grid barrier and the staging of h for the down stage).  Every workgroup calls mid.
+// the wait for the hidden vectors and their staging for the down stage).  Every workgroup calls mid.
+//
+// The workgroup's rows [R0,R1) are cut into tiles that the wavefronts TAKE one at a time from a
+// counter in LDS (l_next, zero on entry) instead of owning fixed shares: measured with fixed shares,
+// the four wavefronts that start second on their SIMDs stream about 15 % slower than the first four,
+// and the workgroup waited for them.
+// Results are collected in an LDS buffer and written out after the last tile: a store or atomic
+// issued between the weight loads would have to complete (the memory counter retires in order)
+// before the NEXT tile's data counts as arrived.  If they do not fit (many rows of a very popular
+// expert) they are written directly instead.
 template <typename WT, int STAGE, int LPR, int NCH, int RG, typename Mid>
 __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_out, float* out, int rows, int L,
                                             int R0, int R1, int N, int pairs_max, int cap_vec, const int* l_active,
                                             const int* l_off, const int* l_tok, const float* l_gw,
-                                            const uint4* l_vec, float* ebuf, int ecap, Mid mid) {
+                                            const uint4* l_vec, float* ebuf, int ecap, uint32_t* l_next, Mid mid,
+                                            unsigned long long* tl_wave = nullptr) {
   constexpr int EPL = 16 / int(sizeof(WT));
   constexpr int R = 64 / LPR;
   constexpr int NM = STAGE == 0 ? 2 : 1;
   constexpr int TROWS = RG * R;
   const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = uniform(tid >> 6);
   const int lsub = lane % LPR, lrow = lane / LPR;
   const int L16 = L / EPL;
 
@@ -207,69 +216,68 @@ __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_ou
   // never true for a routing computed by this kernel; keeps every access in bounds regardless
   if (nseg > kMaxSeg || (unsigned)e0 >= (unsigned)N || (unsigned)e1 >= (unsigned)N || (unsigned)e2 >= (unsigned)N)
     wg_has = false;
+  const int lo = R0, hi = wg_has ? R1 : R0;
+  const SegView sv0{rows, a0, e0, e1, e2, 0, 0, 0, hi, lo};  // the pair counts are not needed to address weights
 
-  const int n_wg = wg_has ? R1 - R0 : 0;
-  const int my_lo = R0 + int((long long)n_wg * wave / kFfnWaves);
-  const int my_hi = R0 + int((long long)n_wg * (wave + 1) / kFfnWaves);
-  bool has_work = my_lo < my_hi;
-  const SegView sv0{rows, a0, e0, e1, e2, 0, 0, 0, my_hi, my_lo};  // the pair counts are not needed to address weights
+  // tile i of the workgroup: the tiles of segment 0, then of segment 1, ...; none crosses an expert boundary
+  const int nt0 = (seg_n(sv0, 0) + TROWS - 1) / TROWS, nt1 = (seg_n(sv0, 1) + TROWS - 1) / TROWS;
+  const int nt2 = (seg_n(sv0, 2) + TROWS - 1) / TROWS;
+  auto take_tile = [&](int& r, int& n) __attribute__((always_inline)) {
+    int i = 0;
+    if (lane == 0) i = int(atomicAdd(l_next, 1u));
+    i = uniform(i);
+    const int s = i < nt0 ? 0 : (i < nt0 + nt1 ? 1 : 2);
+    const int j = i - (s > 0 ? nt0 : 0) - (s > 1 ? nt1 : 0);
+    r = seg_lo(sv0, s) + j * TROWS;
+    n = i < nt0 + nt1 + nt2 ? tile_rows(sv0, r, TROWS) : 0;
+    if (n <= 0) r = lo;
+  };
 
   uint4 wA[NM][RG][NCH], wB[NM][RG][NCH];
-  const int r_first = has_work ? my_lo : R0;
-  int rA = r_first, nA = has_work ? tile_rows(sv0, my_lo, TROWS) : 0;
-  int rB = rA + nA, nB = tile_rows(sv0, rB, TROWS);
-#ifndef OEA_EARLY_TILES
-#define OEA_EARLY_TILES 2
-#endif
-  constexpr int kEarly = STAGE == 0 ? OEA_EARLY_TILES : 2;
-  if (wg_has) {  // uniform over the workgroup; a wavefront without rows loads the first row and drops it
-    if (kEarly >= 1) load_tile<WT, NM, LPR, NCH, RG, true>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv0, r_first), nA);
-    if (kEarly >= 2) load_tile<WT, NM, LPR, NCH, RG, true>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv0, nB > 0 ? rB : r_first), nB);
+  int rA = lo, nA = 0, rB = lo, nB = 0;
+  if (wg_has) {  // uniform over the workgroup; a wavefront that finds no tile requests a placeholder
+    take_tile(rA, nA);
+    take_tile(rB, nB);
+    load_tile<WT, NM, LPR, NCH, RG, true>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv0, rA), nA);
+    load_tile<WT, NM, LPR, NCH, RG, true>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv0, rB), nB);
   }
   __builtin_amdgcn_sched_barrier(0);  // the requests above are issued before anything in mid
 
   mid(a0, wg_has ? nseg : 0);
 
-  __builtin_amdgcn_sched_barrier(0);
-  if (wg_has) {
-    if (kEarly < 1) load_tile<WT, NM, LPR, NCH, RG, true>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv0, r_first), nA);
-    if (kEarly < 2) load_tile<WT, NM, LPR, NCH, RG, true>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv0, nB > 0 ? rB : r_first), nB);
-  }
-
-  // pair lists of this workgroup's experts (for the gate/up stage mid has just produced them)
+  // pair lists of this workgroup's experts
   const int off0 = uniform(l_off[a0]);
   const int off1 = uniform(l_off[a0 + 1]);
   const int off2 = nseg > 1 ? uniform(l_off[a0 + 2]) : off1;
   const int off3 = nseg > 2 ? uniform(l_off[a0 + 3]) : off2;
   const int nvec = off3 - off0;
   if (off0 < 0 || off1 < off0 || off2 < off1 || off3 < off2 || nvec > cap_vec || off0 + nvec > pairs_max)
-    has_work = false;  // never true, as above
-  const SegView sv{rows, a0, e0, e1, e2, off1 - off0, off2 - off1, off3 - off2, my_hi, my_lo};
+    wg_has = false;  // never true, as above
+  const SegView sv{rows, a0, e0, e1, e2, off1 - off0, off2 - off1, off3 - off2, hi, lo};
+  const int* const s_tok = l_tok + (wg_has ? off0 : 0);
+  const float* const s_gw = l_gw + (wg_has ? off0 : 0);
+  const int n_res = result_entries(sv);
+  const bool use_buf = n_res <= ecap * kFfnWaves;
 
-  if (!has_work) return;
-  const int* const s_tok = l_tok + off0;  // pair lists of this workgroup's experts
-  const float* const s_gw = l_gw + off0;
-  // Results are collected in the wavefront's LDS buffer and written out after its last tile: a store
-  // or atomic issued between the weight loads would have to complete (the memory counter retires in
-  // order) before the NEXT tile's data counts as arrived.  A wavefront whose results do not fit
-  // (many rows of a very popular expert) writes them directly instead.
-  float* const eb = ebuf + (size_t)wave * ecap;
-  const bool use_buf = result_entries(sv) <= ecap;
-  while (true) {
-    compute_tile<WT, STAGE, NM, LPR, NCH, RG, true, true, true>(wA, s_tok, s_gw, l_vec, h_out, out, rows, L16, off0, lsub,
-                                                                lrow, tile_ref_buffered(sv, rA), nA, eb, use_buf);
-    rA = rB + nB;
-    nA = tile_rows(sv, rA, TROWS);
-    load_tile<WT, NM, LPR, NCH, RG, true>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv, nA > 0 ? rA : r_first), nA);
-    if (nB <= 0) break;
-    compute_tile<WT, STAGE, NM, LPR, NCH, RG, true, true, true>(wB, s_tok, s_gw, l_vec, h_out, out, rows, L16, off0, lsub,
-                                                                lrow, tile_ref_buffered(sv, rB), nB, eb, use_buf);
-    rB = rA + nA;
-    nB = tile_rows(sv, rB, TROWS);
-    load_tile<WT, NM, LPR, NCH, RG, true>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv, nB > 0 ? rB : r_first), nB);
-    if (nA <= 0) break;
+  if (wg_has && nA > 0) {
+    while (true) {
+      compute_tile<WT, STAGE, NM, LPR, NCH, RG, true, true, true>(wA, s_tok, s_gw, l_vec, h_out, out, rows, L16, off0,
+                                                                  lsub, lrow, tile_ref_buffered(sv, rA), nA, ebuf, use_buf);
+      take_tile(rA, nA);
+      load_tile<WT, NM, LPR, NCH, RG, true>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv, rA), nA);
+      if (nB <= 0) break;
+      compute_tile<WT, STAGE, NM, LPR, NCH, RG, true, true, true>(wB, s_tok, s_gw, l_vec, h_out, out, rows, L16, off0,
+                                                                  lsub, lrow, tile_ref_buffered(sv, rB), nB, ebuf, use_buf);
+      take_tile(rB, nB);
+      load_tile<WT, NM, LPR, NCH, RG, true>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv, rB), nB);
+      if (nA <= 0) break;
+    }
   }
-  if (use_buf) flush_results<WT, STAGE>(sv, eb, s_tok, s_gw, h_out, out, off0, lane);
+#ifdef OEA_TIMELINE
+  if (tl_wave && lane == 0) tl_wave[blockIdx.x * kFfnWaves + (tid >> 6)] = wall_clock64();
+#endif
+  __syncthreads();  // every wavefront's results are in the buffer
+  if (wg_has && use_buf) flush_results<WT, STAGE>(sv, ebuf, s_tok, s_gw, h_out, out, off0, tid);
 }
 
 // Layout of the per-expert completion words in the control area: counter and flag of the expert at
@@ -427,6 +435,7 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   // ---- phase R2: routing, replicated per workgroup, result in LDS
   for (int i = tid; i < B * N; i += kFfnThreads)  // device-coherent loads: written by other workgroups
     l_logits[i] = __hip_atomic_load(p.logits + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (tid == 0) l_nact[1] = l_nact[2] = 0;  // tile counters of the two stages
   __syncthreads();
   OEA_TL(p.ctrl, 9);
   const RouteOut lo{l_idx, l_gatew, l_nsel, l_active, l_nact, l_off, l_tok, l_gw};
@@ -456,7 +465,11 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   fused_stage<WT, 0, LPR0, NCH0, 1>(static_cast<const WT*>(p.w_gate), static_cast<const WT*>(p.w_up),
                                     static_cast<WT*>(p.h), p.out, I, d, RA0, RA1, N, P, p.cap_vec, l_active, l_off,
                                     l_tok, l_gw, l_vec, reinterpret_cast<float*>(l_vec + (size_t)B * d16), p.ecap0,
-                                    [](int, int) {});
+                                    reinterpret_cast<uint32_t*>(l_nact + 1), [](int, int) {}
+#ifdef OEA_TIMELINE
+                                    , reinterpret_cast<unsigned long long*>(static_cast<char*>(p.h) + (size_t)P * I * 2) + 2048
+#endif
+                                    );
   signal_hidden_done(p.ctrl, RA0, RA1, I);
 #ifdef OEA_TIMELINE
   if (threadIdx.x == 0) {
@@ -474,7 +487,7 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   fused_stage<WT, 1, LPR1, NCH1, 2>(
       static_cast<const WT*>(p.w_down), static_cast<const WT*>(nullptr), static_cast<WT*>(nullptr), p.out, d, I, RB0,
       RB1, N, P, p.cap_vec, l_active, l_off, l_tok, l_gw, l_vec,
-      reinterpret_cast<float*>(l_vec + (size_t)cap_vec * I16), p.ecap1,
+      reinterpret_cast<float*>(l_vec + (size_t)cap_vec * I16), p.ecap1, reinterpret_cast<uint32_t*>(l_nact + 2),
       [&](int a0, int nseg) {  // runs once the first weight tiles are requested
         OEA_TL(ctrl, 5);
         // No grid barrier here: this workgroup only needs the hidden vectors of ITS experts, which
@@ -516,7 +529,11 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
         }
         __syncthreads();
         OEA_TL(ctrl, 7);
-      });
+      }
+#ifdef OEA_TIMELINE
+      , reinterpret_cast<unsigned long long*>(static_cast<char*>(p.h) + (size_t)P * I * 2) + 4096
+#endif
+      );
   OEA_TL(p.ctrl, 8);
 #ifdef OEA_TIMELINE
   if (threadIdx.x == 0) {  // per-workgroup stamps in the unused upper half of the bf16 h buffer
