@@ -167,16 +167,19 @@ constexpr int kBetaDown = OEA_BETA_DOWN;  // per pair, down stage (also makes up
 __device__ __forceinline__ int wg_first_row(const int* l_off, int T, int rows, int beta, int b, int G, int lane) {
   if (b <= 0 || T <= 0) return 0;
   if (b >= G) return T * rows;
-  const long long total = (long long)kRowCost * T + (long long)beta * l_off[T];  // in units of one row
-  const long long x = total * rows * b / G;
+  // All quantities are integers below 2^40, exact in double; the divisions go through double because
+  // 64-bit integer division is a long instruction sequence on this GPU.  Every workgroup evaluates
+  // the same expression for boundary b, so neighbours agree on it.
+  const double total = double(kRowCost) * T + double(beta) * l_off[T];  // in units of one row
+  const double x = floor(total * rows * b / G);
   const int a0 = lane, a1 = lane + 64;
-  const long long p0 = (long long)rows * ((long long)kRowCost * a0 + (long long)beta * l_off[a0 < T ? a0 : T]);
-  const long long p1 = (long long)rows * ((long long)kRowCost * a1 + (long long)beta * l_off[a1 < T ? a1 : T]);
+  const double p0 = double(rows) * (double(kRowCost) * a0 + double(beta) * l_off[a0 < T ? a0 : T]);
+  const double p1 = double(rows) * (double(kRowCost) * a1 + double(beta) * l_off[a1 < T ? a1 : T]);
   const int below = __popcll(__ballot(a0 < T && p0 <= x)) + __popcll(__ballot(a1 < T && p1 <= x));
   const int lo = below > 0 ? below - 1 : 0;  // largest position whose prefix cost is <= x
   const int off_lo = l_off[lo];
-  const long long w = kRowCost + (long long)beta * (l_off[lo + 1] - off_lo);
-  long long r = (x - (long long)rows * ((long long)kRowCost * lo + (long long)beta * off_lo)) / w;
+  const double w = kRowCost + double(beta) * (l_off[lo + 1] - off_lo);
+  double r = floor((x - double(rows) * (double(kRowCost) * lo + double(beta) * off_lo)) / w);
   r = r < 0 ? 0 : (r > rows ? rows : r);
   return uniform(lo * rows + int(r));
 }
@@ -291,9 +294,12 @@ __device__ __forceinline__ uint32_t* done_flag(uint32_t* ctrl, int a) {
 }
 
 // After the gate/up stage: tell the down stage which hidden vectors are complete.  Called by the whole
-// workgroup once every wavefront has drained its h stores.  Thread 0 adds the rows this workgroup
+// workgroup; every wavefront first drains its h stores.  Thread 0 adds the rows this workgroup
 // produced to the counter of each expert it touched; the arrival that completes an expert (all
 // `rows` hidden units) raises that expert's flag.
+// (Signalling only after the down stage's first tiles are requested, with the h stores completing
+// underneath, was measured slower: early finishers then compete with the gate/up stragglers that
+// everyone waits for.)
 __device__ __forceinline__ void signal_hidden_done(uint32_t* ctrl, int R0, int R1, int rows) {
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
@@ -477,7 +483,6 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
     tl[512 + blockIdx.x] = wall_clock64();
   }
 #endif
-
   OEA_TL(p.ctrl, 4);
   // ---- phase B: down.  mid = barrier (h complete everywhere), then this workgroup's h rows -> LDS
   const WT* const hsrc = static_cast<const WT*>(p.h);
