@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--kernel-path", type=int, default=0, help="0 automatic (fused kernel), 1 generic, 2 three kernels")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain device copy of known size (reference for rocprofv3 --pmc byte counters)")
+    ap.add_argument("--launch", default="stream", choices=["stream", "graph"],
+                    help="timed steps launched one by one, or captured into one HIP graph and replayed (measured: same latency)")
     ap.add_argument("--verbose", action="store_true")
     return ap.parse_args()
 
@@ -54,6 +56,29 @@ class Hip:
         self.rt.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
         self.rt.hipEventSynchronize.argtypes = [ctypes.c_void_p]
         self.rt.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.rt.hipStreamBeginCapture.argtypes = [ctypes.c_void_p, ctypes.c_int]
+        self.rt.hipStreamEndCapture.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p)]
+        self.rt.hipGraphInstantiate.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p, ctypes.c_void_p,
+                                                ctypes.c_void_p, ctypes.c_size_t]
+        self.rt.hipGraphLaunch.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        self.rt.hipGraphExecDestroy.argtypes = [ctypes.c_void_p]
+        self.rt.hipGraphDestroy.argtypes = [ctypes.c_void_p]
+
+    def capture(self, stream, enqueue):
+        """Record what enqueue() puts on `stream` into a graph; returns the executable graph."""
+        assert self.rt.hipStreamBeginCapture(stream, 1) == 0  # thread-local capture mode
+        enqueue()
+        graph, ex = ctypes.c_void_p(), ctypes.c_void_p()
+        assert self.rt.hipStreamEndCapture(stream, ctypes.byref(graph)) == 0
+        assert self.rt.hipGraphInstantiate(ctypes.byref(ex), graph, None, None, 0) == 0
+        assert self.rt.hipGraphDestroy(graph) == 0
+        return ex
+
+    def launch_graph(self, ex, stream):
+        assert self.rt.hipGraphLaunch(ex, stream) == 0
+
+    def destroy_graph(self, ex):
+        assert self.rt.hipGraphExecDestroy(ex) == 0
 
     def event(self):
         e = ctypes.c_void_p()
@@ -88,7 +113,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     hip = Hip()
-    stream = torch.cuda.current_stream()
+    stream = torch.cuda.Stream()  # a stream of its own (default priority): graph capture needs a non-null stream
+    torch.cuda.set_stream(stream)
     sptr = ctypes.c_void_p(stream.cuda_stream)
 
     cfg = workloads.CONFIGS[args.workload]
@@ -184,14 +210,31 @@ def main():
                 step += 1
                 assert rc == 0, rc
             torch.cuda.synchronize()
-            t_a = time.perf_counter()
-            hip.record(e0, sptr)
-            for _ in range(args.steps):
-                calls[step % R]()
-                step += 1
-            hip.record(e1, sptr)
-            torch.cuda.synchronize()
-            t_b = time.perf_counter()
+            if args.launch == "graph":
+                first = step
+
+                def enqueue():
+                    for j in range(args.steps):
+                        assert calls[(first + j) % R]() == 0
+                gexec = hip.capture(sptr, enqueue)
+                step += args.steps
+                torch.cuda.synchronize()
+                t_a = time.perf_counter()
+                hip.record(e0, sptr)
+                hip.launch_graph(gexec, sptr)
+                hip.record(e1, sptr)
+                torch.cuda.synchronize()
+                t_b = time.perf_counter()
+                hip.destroy_graph(gexec)
+            else:
+                t_a = time.perf_counter()
+                hip.record(e0, sptr)
+                for _ in range(args.steps):
+                    calls[step % R]()
+                    step += 1
+                hip.record(e1, sptr)
+                torch.cuda.synchronize()
+                t_b = time.perf_counter()
             lat_wall[(ti, k0)] = (t_b - t_a) / args.steps * 1e6
             lat_ev[(ti, k0)] = hip.elapsed_ms(e0, e1) / args.steps * 1e3
 
@@ -262,7 +305,8 @@ def main():
     roofline = dict(bound="hbm", kernel=dom_name, achieved=round(achieved, 1),
                     peak=HBM_PEAK_GBS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4), traffic=traffic,
                     bytes_per_launch=int(dom_bytes), us_per_launch=round(dom_us, 2),
-                    kernels_us={str(k0_): dict(router_route=round(v[0], 2), gate_up=round(v[1], 2), down=round(v[2], 2))
+                    kernels_us={str(k0_): (dict(fused=round(v[0], 2)) if fused else
+                                           dict(router_route=round(v[0], 2), gate_up=round(v[1], 2), down=round(v[2], 2)))
                                 for k0_, v in kern.items()})
 
     cpu = None
@@ -285,7 +329,7 @@ def main():
                 higher_is_better=False, scaling="weak", vs_baseline=None, dtype="bf16", data="synthetic",
                 config=dict(workload="%s B=%d d=%d N=%d I=%d k=%d, OEA k0=%d (k0=%d is plain top-k)"
                                      % (args.workload, B, d, N, I, k, args.k0, k),
-                            trials=len(xs), weight_sets=R, k0=args.k0),
+                            trials=len(xs), weight_sets=R, k0=args.k0, launch=args.launch),
                 topk_latency_us=table[str(k)]["latency_us"],
                 latency_ratio_vs_topk=round(value / table[str(k)]["latency_us"], 4),
                 unique_expert_ratio_vs_topk=round(table[str(args.k0)]["unique_experts"] / table[str(k)]["unique_experts"], 4),
