@@ -75,6 +75,28 @@ int oea_route(const float *router_logits, int B, int N, int k, int k0, int32_t *
               void *stream);
 
 /*
+ * General OEA routing (Algorithm 2 of the paper, Section 3.2 "General OEA"): as oea_route, with
+ *   - a top-p cut of the baseline: n_i = min(k0, t_i), where t_i is the smallest t such that the t
+ *     best experts of token i hold softmax mass >= p (sorted cumulative sum; p = 1 switches the
+ *     cut off, which is how the paper's experiments run it),
+ *   - k_max, the number of experts a token may hold after piggybacking (a baseline that is already
+ *     larger is kept as it is), and
+ *   - max_p: only experts among the token's max_p best-ranked ones are piggybacked.
+ * p = 1, k_max = k, max_p = N gives exactly oea_route(k, k0).
+ *
+ *   token_mask  [B] uint8 or NULL   0 = padding token (selects nothing, adds nothing to the union)
+ *   expert_idx  [B,kw] int32, gate_w [B,kw] fp32 with kw = max(k0, k_max); layout as in oea_route
+ *   n_base      [B] int32 or NULL   n_i, the size of each token's baseline
+ * The top-p comparison is made on fp64 sums of fp64 softmax values.
+ * Errors: OEA_ERR_K unless 1 <= k0 <= N, 1 <= k_max <= N, max(k0,k_max) <= OEA_MAX_K,
+ * 1 <= max_p <= N and 0 < p <= 1.
+ */
+int oea_route_general(const float *router_logits, const uint8_t *token_mask, int B, int N, int k0,
+                      double p, int k_max, int max_p, int32_t *expert_idx, float *gate_w,
+                      int32_t *n_sel, int32_t *n_base, int32_t *active_list, int32_t *n_active,
+                      void *stream);
+
+/*
  * One decode-time MoE layer (Section 2, Eq. 1) with OEA routing (Algorithm 1):
  *   logits = x W_router^T -> routing as in oea_route -> out[i] = sum_{e in S_i} g_{i,e} E_e(x_i),
  *   E_e(x) = W_down[e] ( silu(W_gate[e] x) * (W_up[e] x) )      (Section 4: SwiGLU expert)
@@ -126,6 +148,10 @@ typedef struct {
   void **h_kernel_events;     /* HOST array of 6 hipEvent_t (created by the caller): recorded on the
                                  stream before/after the router+routing kernel [0],[1], the gate/up
                                  kernel [2],[3] and the down kernel [4],[5].  Measurement aid. */
+  double top_p;               /* general OEA (Algorithm 2): top-p cut of the baseline; 0 or >= 1 = off */
+  int32_t max_p;              /* general OEA: piggyback only among the max_p best ranks; 0 or >= N = off.
+                                 With either set, k plays the role of k_max and the layer runs as three
+                                 kernels. */
 } oea_decode_ex;
 
 /* moe_decode with the extras above (ex == NULL behaves as moe_decode). */

@@ -16,8 +16,8 @@ OEA_F32, OEA_BF16 = 0, 1
 OEA_OK = 0
 STATUS = {"OEA_ERR_NULL": -1, "OEA_ERR_SHAPE": -2, "OEA_ERR_K": -3, "OEA_ERR_ALIGN": -4,
           "OEA_ERR_WORKSPACE": -5, "OEA_ERR_DTYPE": -6, "OEA_ERR_HIP": -7}
-EXPORTS = ("oea_status_string", "oea_workspace_bytes", "oea_workspace_init", "oea_route", "moe_decode",
-           "moe_decode_ex", "oea_set_kernel_path")
+EXPORTS = ("oea_status_string", "oea_workspace_bytes", "oea_workspace_init", "oea_route", "oea_route_general",
+           "moe_decode", "moe_decode_ex", "oea_set_kernel_path")
 
 
 class OeaError(RuntimeError):
@@ -31,7 +31,8 @@ class DecodeEx(ctypes.Structure):
                 ("logits_out", ctypes.c_void_p), ("expert_idx_out", ctypes.c_void_p),
                 ("gate_w_out", ctypes.c_void_p), ("n_sel_out", ctypes.c_void_p),
                 ("active_list_out", ctypes.c_void_p), ("n_active_out", ctypes.c_void_p),
-                ("h_kernel_events", ctypes.POINTER(ctypes.c_void_p))]
+                ("h_kernel_events", ctypes.POINTER(ctypes.c_void_p)),
+                ("top_p", ctypes.c_double), ("max_p", ctypes.c_int32)]
 
 
 _lib = None
@@ -55,6 +56,8 @@ def lib():
         L.oea_set_kernel_path.argtypes = [ci]
         L.oea_route.restype = ci
         L.oea_route.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
+        L.oea_route_general.restype = ci
+        L.oea_route_general.argtypes = [vp, vp, ci, ci, ci, ctypes.c_double, ci, ci, vp, vp, vp, vp, vp, vp, vp]
         L.moe_decode.restype = ci
         L.moe_decode.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp]
         L.moe_decode_ex.restype = ci
@@ -125,8 +128,30 @@ def oea_route(router_logits, k, k0, stream=None, out=None):
     return out
 
 
+def oea_route_general(router_logits, k0, p, k_max, max_p, token_mask=None, stream=None):
+    """General OEA routing (Algorithm 2).  Returns dict(expert_idx [B,kw], gate_w, n_sel, n_base,
+    active_list, n_active) on device, kw = max(k0, k_max)."""
+    assert router_logits.is_cuda and router_logits.dtype == torch.float32 and router_logits.is_contiguous()
+    B, N = router_logits.shape
+    dev = router_logits.device
+    kw = max(int(k0), int(k_max))
+    if token_mask is not None:
+        assert token_mask.is_cuda and token_mask.dtype == torch.uint8 and token_mask.numel() == B
+    out = dict(expert_idx=torch.empty((B, kw), dtype=torch.int32, device=dev),
+               gate_w=torch.empty((B, kw), dtype=torch.float32, device=dev),
+               n_sel=torch.empty((B,), dtype=torch.int32, device=dev),
+               n_base=torch.empty((B,), dtype=torch.int32, device=dev),
+               active_list=torch.empty((N,), dtype=torch.int32, device=dev),
+               n_active=torch.empty((1,), dtype=torch.int32, device=dev))
+    _check(lib().oea_route_general(_ptr(router_logits), _ptr(token_mask), B, N, int(k0), float(p), int(k_max),
+                                   int(max_p), _ptr(out["expert_idx"]), _ptr(out["gate_w"]), _ptr(out["n_sel"]),
+                                   _ptr(out["n_base"]), _ptr(out["active_list"]), _ptr(out["n_active"]),
+                                   _stream(stream)))
+    return out
+
+
 def moe_decode(x, w_router, w_gate, w_up, w_down, k, k0, workspace, out=None, stream=None,
-               router_bias=None, token_mask=None, taps=False, kernel_events=None):
+               router_bias=None, token_mask=None, taps=False, kernel_events=None, top_p=None, max_p=None):
     """One decode-time MoE layer with OEA routing.  Returns out [B,d] float32 (and a dict of routing
     taps when taps=True)."""
     for t in (x, w_router, w_gate, w_up, w_down):
@@ -143,11 +168,16 @@ def moe_decode(x, w_router, w_gate, w_up, w_down, k, k0, workspace, out=None, st
         out = torch.empty((B, d), dtype=torch.float32, device=dev)
     args = [_ptr(x), _ptr(w_router), _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(out), B, d, N, I, int(k),
             int(k0), dt, _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)]
-    if not taps and router_bias is None and token_mask is None and kernel_events is None:
+    if not taps and router_bias is None and token_mask is None and kernel_events is None and top_p is None \
+            and max_p is None:
         _check(lib().moe_decode(*args))
         return out
     ex = DecodeEx()
     tap = None
+    if top_p is not None:
+        ex.top_p = float(top_p)
+    if max_p is not None:
+        ex.max_p = int(max_p)
     if kernel_events is not None:  # ctypes array of 6 hipEvent_t handles
         ex.h_kernel_events = ctypes.cast(kernel_events, ctypes.POINTER(ctypes.c_void_p))
     if router_bias is not None:

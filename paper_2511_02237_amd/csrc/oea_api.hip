@@ -110,6 +110,23 @@ extern "C" int oea_route(const float* router_logits, int B, int N, int k, int k0
   return e == hipSuccess ? OEA_OK : OEA_ERR_HIP;
 }
 
+extern "C" int oea_route_general(const float* router_logits, const uint8_t* token_mask, int B, int N, int k0,
+                                 double p, int k_max, int max_p, int32_t* expert_idx, float* gate_w,
+                                 int32_t* n_sel, int32_t* n_base, int32_t* active_list, int32_t* n_active,
+                                 void* stream) {
+  if (!router_logits || !expert_idx || !gate_w || !n_sel || !active_list || !n_active) return OEA_ERR_NULL;
+  if (B < 1 || B > OEA_MAX_B || N < 1 || N > OEA_MAX_N) return OEA_ERR_SHAPE;
+  const int kw = k0 > k_max ? k0 : k_max;
+  if (k0 < 1 || k0 > N || k_max < 1 || k_max > N || kw > OEA_MAX_K || max_p < 1 || max_p > N || !(p > 0.0) ||
+      p > 1.0)
+    return OEA_ERR_K;
+  RouteOut o{expert_idx, gate_w, n_sel, active_list, n_active, nullptr, nullptr, nullptr};
+  const oea::RouteGeneralArgs ga{p, k_max, max_p};
+  hipError_t e = launch_route_general(router_logits, token_mask, B, N, k0, ga, n_base, o,
+                                      static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? OEA_OK : OEA_ERR_HIP;
+}
+
 extern "C" int moe_decode_ex(const void* x, const void* W_router, const void* W_gate, const void* W_up,
                              const void* W_down, float* out, int B, int d, int N, int I, int k, int k0,
                              oea_dtype dt, void* workspace, size_t workspace_bytes, void* stream,
@@ -136,9 +153,15 @@ extern "C" int moe_decode_ex(const void* x, const void* W_router, const void* W_
   hipEvent_t* ev = ex && ex->h_kernel_events ? reinterpret_cast<hipEvent_t*>(ex->h_kernel_events) : nullptr;
   auto mark = [&](int i) { return !ev || hipEventRecord(ev[i], s) == hipSuccess; };
 
+  // general OEA (Algorithm 2) only if the extras ask for it; k is then k_max
+  oea::RouteGeneralArgs ga{1.0, k, N};
+  if (ex && ex->top_p > 0.0 && ex->top_p < 1.0) ga.p = ex->top_p;
+  if (ex && ex->max_p > 0 && ex->max_p < N) ga.max_p = ex->max_p;
+  const bool general = ga.p < 1.0 || ga.max_p < N;
+
   if (!mark(0)) return OEA_ERR_HIP;
   hipError_t e = hipErrorNotSupported;
-  if (g_kernel_path == 0)
+  if (g_kernel_path == 0 && !general)
     e = try_launch_fused(x, W_router, W_gate, W_up, W_down, ex ? ex->router_bias : nullptr,
                          ex ? ex->token_mask : nullptr, out, logits, h, ro,
                          reinterpret_cast<uint32_t*>(ws + w.ctrl), B, d, N, I, k, k0, dt, s);
@@ -149,7 +172,8 @@ extern "C" int moe_decode_ex(const void* x, const void* W_router, const void* W_
     return OEA_ERR_HIP;
   } else {
     e = launch_router_and_route(x, W_router, ex ? ex->router_bias : nullptr, ex ? ex->token_mask : nullptr, B, d,
-                                N, k, k0, dt, logits, out, reinterpret_cast<uint32_t*>(ws + w.ctrl), ro, s);
+                                N, k, k0, dt, logits, out, reinterpret_cast<uint32_t*>(ws + w.ctrl), ro,
+                                general ? &ga : nullptr, s);
     if (e != hipSuccess || !mark(1) || !mark(2)) return OEA_ERR_HIP;
     e = launch_expert_gate_up(x, W_gate, W_up, h, B, d, N, I, k, dt, g, s);
     if (e != hipSuccess || !mark(3) || !mark(4)) return OEA_ERR_HIP;

@@ -48,6 +48,13 @@ struct RouteOut {
   float* grp_gw;     // may be nullptr
 };
 
+// parameters of the general OEA routing (Algorithm 2) beyond k0: top-p threshold, cap, rank window
+struct RouteGeneralArgs {
+  double p;
+  int k_max;
+  int max_p;
+};
+
 // launchers (each returns the hipError_t of the launch)
 hipError_t launch_fill_zero(uint32_t* p, size_t n_words, hipStream_t s);
 hipError_t launch_route(const float* logits, const uint8_t* token_mask, int B, int N, int k, int k0,
@@ -55,7 +62,9 @@ hipError_t launch_route(const float* logits, const uint8_t* token_mask, int B, i
 hipError_t launch_router_and_route(const void* x, const void* w_router, const float* bias,
                                    const uint8_t* token_mask, int B, int d, int N, int k, int k0,
                                    oea_dtype dt, float* logits, float* out_to_zero, uint32_t* counter,
-                                   RouteOut o, hipStream_t s);
+                                   RouteOut o, const RouteGeneralArgs* general, hipStream_t s);
+hipError_t launch_route_general(const float* logits, const uint8_t* token_mask, int B, int N, int k0,
+                                const RouteGeneralArgs& ga, int32_t* n_base, RouteOut o, hipStream_t s);
 hipError_t launch_expert_gate_up(const void* x, const void* w_gate, const void* w_up, void* h, int B,
                                  int d, int N, int I, int k, oea_dtype dt, Grouping g, hipStream_t s);
 hipError_t launch_expert_down(const void* h, const void* w_down, float* out, int B, int d, int N, int I,

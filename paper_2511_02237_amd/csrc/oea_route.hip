@@ -18,12 +18,19 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const float* logit
     route_block<NV, kRouteThreads, 0>(logits, token_mask, B, N, k, k0, o, lds);
 }
 
+template <int NV>
+__global__ __launch_bounds__(kRouteThreads) void route_general_kernel(const float* logits, const uint8_t* token_mask,
+                                                                      int B, int N, int k0, RouteGeneral g, RouteOut o) {
+  extern __shared__ uint32_t lds[];
+  route_block_general<NV, kRouteThreads>(logits, token_mask, B, N, k0, g, o, lds);
+}
+
 //   part B: the workgroup that arrives last at the counter routes the whole batch.
 template <typename WT, int NV>
 __global__ __launch_bounds__(kRouteThreads) void router_route_kernel(
     const WT* __restrict__ x, const WT* __restrict__ w_router, const float* __restrict__ bias,
     const uint8_t* token_mask, int B, int d, int N, int k, int k0, float* logits, float* out_to_zero,
-    uint32_t* counter, RouteOut o) {
+    uint32_t* counter, RouteOut o, RouteGeneral g, int general) {
   extern __shared__ uint32_t lds[];
   constexpr int EPL = 16 / int(sizeof(WT));
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -71,7 +78,9 @@ __global__ __launch_bounds__(kRouteThreads) void router_route_kernel(
   const bool last = lds[0] != 0u;
   __syncthreads();
   if (!last) return;
-  if (B <= kRouteThreads / 64)
+  if (general)
+    route_block_general<NV, kRouteThreads>(logits, token_mask, B, N, k0, g, o, lds);
+  else if (B <= kRouteThreads / 64)
     route_block<NV, kRouteThreads, 1>(logits, token_mask, B, N, k, k0, o, lds);
   else
     route_block<NV, kRouteThreads, 0>(logits, token_mask, B, N, k, k0, o, lds);
@@ -89,7 +98,7 @@ int nv_for(int N) {
 
 }  // namespace
 
-size_t route_lds_bytes(int B, int N) { return sizeof(uint32_t) * route_lds_words(B, N); }
+size_t route_lds_bytes(int B, int N) { return sizeof(uint32_t) * (route_lds_words(B, N) + (size_t)B); }
 
 hipError_t launch_fill_zero(uint32_t* p, size_t n_words, hipStream_t s) {
   if (n_words == 0) return hipSuccess;
@@ -123,7 +132,10 @@ hipError_t launch_route(const float* logits, const uint8_t* token_mask, int B, i
 template <typename WT>
 static hipError_t launch_rr(const void* x, const void* w_router, const float* bias, const uint8_t* token_mask,
                             int B, int d, int N, int k, int k0, float* logits, float* out_to_zero,
-                            uint32_t* counter, RouteOut o, hipStream_t s) {
+                            uint32_t* counter, RouteOut o, const RouteGeneralArgs* ga, hipStream_t s) {
+  RouteGeneral g{1.0, k, N, nullptr};
+  const int general = ga && (ga->p < 1.0 || ga->max_p < N) ? 1 : 0;
+  if (general) g = RouteGeneral{ga->p, k, ga->max_p, nullptr};
   const size_t lds = route_lds_bytes(B, N);
   switch (nv_for(N)) {
 #define OEA_CASE(NV)                                                                                       \
@@ -135,7 +147,7 @@ static hipError_t launch_rr(const void* x, const void* w_router, const float* bi
     }                                                                                                      \
     hipLaunchKernelGGL((router_route_kernel<WT, NV>), dim3(N), dim3(kRouteThreads), lds, s,                \
                        static_cast<const WT*>(x), static_cast<const WT*>(w_router), bias, token_mask, B, d, \
-                       N, k, k0, logits, out_to_zero, counter, o);                                         \
+                       N, k, k0, logits, out_to_zero, counter, o, g, general);                             \
   } break;
     OEA_CASE(1)
     OEA_CASE(2)
@@ -149,10 +161,34 @@ static hipError_t launch_rr(const void* x, const void* w_router, const float* bi
 hipError_t launch_router_and_route(const void* x, const void* w_router, const float* bias,
                                    const uint8_t* token_mask, int B, int d, int N, int k, int k0,
                                    oea_dtype dt, float* logits, float* out_to_zero, uint32_t* counter,
-                                   RouteOut o, hipStream_t s) {
+                                   RouteOut o, const RouteGeneralArgs* ga, hipStream_t s) {
   if (dt == OEA_F32)
-    return launch_rr<float>(x, w_router, bias, token_mask, B, d, N, k, k0, logits, out_to_zero, counter, o, s);
-  return launch_rr<uint16_t>(x, w_router, bias, token_mask, B, d, N, k, k0, logits, out_to_zero, counter, o, s);
+    return launch_rr<float>(x, w_router, bias, token_mask, B, d, N, k, k0, logits, out_to_zero, counter, o, ga, s);
+  return launch_rr<uint16_t>(x, w_router, bias, token_mask, B, d, N, k, k0, logits, out_to_zero, counter, o, ga, s);
+}
+
+hipError_t launch_route_general(const float* logits, const uint8_t* token_mask, int B, int N, int k0,
+                                const RouteGeneralArgs& ga, int32_t* n_base, RouteOut o, hipStream_t s) {
+  const size_t lds = route_lds_bytes(B, N);
+  const RouteGeneral g{ga.p, ga.k_max, ga.max_p, n_base};
+  switch (nv_for(N)) {
+#define OEA_CASE(NV)                                                                                        \
+  case NV: {                                                                                                \
+    if (lds > 48 * 1024) {                                                                                  \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&route_general_kernel<NV>),          \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);             \
+      if (e != hipSuccess) return e;                                                                        \
+    }                                                                                                       \
+    hipLaunchKernelGGL(route_general_kernel<NV>, dim3(1), dim3(kRouteThreads), lds, s, logits, token_mask, B, \
+                       N, k0, g, o);                                                                        \
+  } break;
+    OEA_CASE(1)
+    OEA_CASE(2)
+    OEA_CASE(4)
+    OEA_CASE(8)
+#undef OEA_CASE
+  }
+  return hipGetLastError();
 }
 
 }  // namespace oea

@@ -495,6 +495,157 @@ __device__ void route_block(const float* __restrict__ logits, const uint8_t* __r
   route_fill<NV, NT, TPW>(logits, token_mask, B, N, k, k0, o, lds, c);
 }
 
+// ---------------------------------------------------------------------------------------------
+// General OEA (Algorithm 2 of the paper): the baseline of a token is cut by a top-p rule as well
+// (n_i = min(k0, t_i), t_i = least t whose t best experts hold softmax mass >= p), piggybacking
+// stops at k_max experts and only looks at ranks up to max_p.  p >= 1 switches the top-p cut off,
+// max_p >= N the window; with both off and k_max = k this is Algorithm 1.
+struct RouteGeneral {
+  double p;         // top-p threshold, (0,1]
+  int k_max;        // cap on |S_i| for piggybacking (a baseline larger than k_max is kept)
+  int max_p;        // piggyback only from ranks <= max_p (1-based), i.e. rank indices < max_p
+  int32_t* n_base;  // [B] out: n_i (may be nullptr)
+};
+
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// One workgroup of NT threads, one wavefront per token at a time, any B.  Output rows have
+// kw = max(k0, k_max) slots.  lds: route_lds_words(B,N) + B words.
+// The top-p decision compares fp64 sums of fp64 softmax values (the softmax of Section 2 taken in
+// double, like the weights it decides about are defined), so it can differ from an evaluation in
+// another summation order only when the mass is within rounding of p.
+template <int NV, int NT>
+__device__ void route_block_general(const float* __restrict__ logits, const uint8_t* __restrict__ token_mask,
+                                    int B, int N, int k0, RouteGeneral g, RouteOut o, uint32_t* lds) {
+  constexpr int NW = NT / 64;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int NWB = (B + 31) >> 5;
+  const int kw = k0 > g.k_max ? k0 : g.k_max;
+  uint32_t* U = lds;
+  uint32_t* colmask = lds + 64;
+  int* nb = reinterpret_cast<int*>(lds + route_lds_words(B, N));  // [B] baseline sizes
+
+  for (int i = tid; i < int(route_lds_words(B, N)) + B; i += NT) lds[i] = 0;
+  __syncthreads();
+  const bool capped = g.p < 1.0;
+
+  // ---- Phase 1: baseline S_i^base = the n_i best experts; U = union over the batch
+  for (int t = wave; t < B; t += NW) {
+    const bool live = !(token_mask && token_mask[t] == 0);
+    uint32_t key[NV];
+    float lg[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int e = lane + 64 * j;
+      lg[j] = (live && e < N) ? logits[(size_t)t * N + e] : 0.f;
+      key[j] = (live && e < N) ? make_key(lg[j]) : 0;
+    }
+    double m = 0.0, z = 1.0;
+    if (capped && live) {  // softmax denominator over all N experts
+      uint32_t lm = key[0];
+#pragma unroll
+      for (int j = 1; j < NV; ++j) lm = key[j] > lm ? key[j] : lm;
+      m = double(from_orderable(wave_max_u32(lm)));
+      double zl = 0.0;
+#pragma unroll
+      for (int j = 0; j < NV; ++j)
+        if (key[j] != 0) zl += exp(double(lg[j]) - m);
+      z = wave_sum_f64(zl);
+    }
+    int n = 0;
+    double cum = 0.0;
+    for (int r = 0; r < k0; ++r) {
+      uint32_t bk;
+      int id;
+      if (!pick_best<NV>(key, lane, bk, id)) break;
+      if (lane == 0) atomicOr(&U[id >> 5], 1u << (id & 31));
+      ++n;
+      if (capped) {
+        cum += exp(double(from_orderable(bk)) - m) / z;
+        if (cum >= g.p) break;
+      }
+    }
+    if (lane == 0) {
+      nb[t] = n;
+      if (g.n_base) g.n_base[t] = n;
+    }
+  }
+  __syncthreads();
+  route_active<NT>(N, o, lds);
+  __syncthreads();
+
+  // ---- Phase 2: piggyback on U in rank order, ranks below max_p, until k_max experts are held
+  for (int t = wave; t < B; t += NW) {
+    const bool live = !(token_mask && token_mask[t] == 0);
+    const int nbase = nb[t];
+    uint32_t key[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int e = lane + 64 * j;
+      key[j] = (live && e < N) ? make_key(logits[(size_t)t * N + e]) : 0;
+    }
+    int cnt = 0, my_id = -1;
+    float my_logit = 0.f;
+    auto take = [&](int id, uint32_t bk) __attribute__((always_inline)) {
+      if (lane == cnt) {
+        my_id = id;
+        my_logit = from_orderable(bk);
+      }
+      ++cnt;
+    };
+    if (g.max_p >= N) {
+      // no window: the piggybacked experts are simply the best remaining members of U
+      for (int r = 0; r < nbase; ++r) {
+        uint32_t bk;
+        int id;
+        if (!pick_best<NV>(key, lane, bk, id)) break;
+        take(id, bk);
+      }
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        const int e = lane + 64 * j;
+        if (!(e < N && ((U[e >> 5] >> (e & 31)) & 1u))) key[j] = 0;
+      }
+      while (cnt < g.k_max) {
+        uint32_t bk;
+        int id;
+        if (!pick_best<NV>(key, lane, bk, id)) break;
+        take(id, bk);
+      }
+    } else {
+      // walk the ranks in order; an expert outside U uses up its rank without being taken
+      const int last = nbase > g.max_p ? nbase : g.max_p;
+      for (int r = 0; r < last; ++r) {
+        uint32_t bk;
+        int id;
+        if (!pick_best<NV>(key, lane, bk, id)) break;
+        if (r < nbase) {
+          take(id, bk);
+        } else {
+          if (cnt >= g.k_max) break;
+          if ((U[id >> 5] >> (id & 31)) & 1u) take(id, bk);
+        }
+      }
+    }
+    // weights: original scores renormalised over S_i (Eq. 1; the softmax denominator cancels)
+    const float mtop = __shfl(my_logit, 0, 64);
+    const float w = lane < cnt ? expf(my_logit - mtop) : 0.f;
+    const float zz = wave_sum_f32(w);
+    if (lane < kw) {
+      o.expert_idx[(size_t)t * kw + lane] = lane < cnt ? my_id : -1;
+      o.gate_w[(size_t)t * kw + lane] = lane < cnt ? w / zz : 0.f;
+    }
+    if (lane < cnt) atomicOr(&colmask[my_id * NWB + (t >> 5)], 1u << (t & 31));
+    if (lane == 0) o.n_sel[t] = cnt;
+  }
+  __syncthreads();
+  route_group<NT>(B, N, kw, o, lds);
+}
+
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
 // fp64 dot product of one 16-byte fragment pair

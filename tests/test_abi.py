@@ -23,6 +23,7 @@ def L():
     lib.oea_workspace_bytes.argtypes = [ci] * 5
     lib.oea_workspace_init.argtypes = [vp, sz, vp]
     lib.oea_route.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
+    lib.oea_route_general.argtypes = [vp, vp, ci, ci, ci, ctypes.c_double, ci, ci, vp, vp, vp, vp, vp, vp, vp]
     lib.moe_decode.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp]
     lib.moe_decode_ex.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp, vp]
     return lib
@@ -36,7 +37,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(L):
     names = declared_functions()
-    assert {"oea_route", "moe_decode", "moe_decode_ex", "oea_workspace_bytes", "oea_workspace_init",
+    assert {"oea_route", "oea_route_general", "moe_decode", "moe_decode_ex", "oea_workspace_bytes", "oea_workspace_init",
             "oea_status_string"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
@@ -78,6 +79,21 @@ def test_route_argument_checks(L):
     assert call(a0=None) == -1 and call(a5=None) == -1 and call(a9=None) == -1
     assert call(a1=0) == -2 and call(a1=1025) == -2 and call(a2=0) == -2 and call(a2=513) == -2
     assert call(a4=0) == -3 and call(a4=9) == -3 and call(a3=129) == -3 and call(a3=33, a4=33) == -3
+
+
+def test_route_general_argument_checks(L):
+    # logits, mask, B, N, k0, p, k_max, max_p, expert_idx, gate_w, n_sel, n_base, active_list, n_active, stream
+    ok = [P, None, 16, 128, 3, 0.9, 8, 128, P, P, P, None, P, P, None]
+    def call(**kw):
+        a = list(ok)
+        for i, v in kw.items():
+            a[int(i[1:])] = v
+        return L.oea_route_general(*a)
+    assert call(a0=None) == -1 and call(a8=None) == -1 and call(a13=None) == -1
+    assert call(a2=0) == -2 and call(a2=1025) == -2 and call(a3=0) == -2 and call(a3=513) == -2
+    assert call(a4=0) == -3 and call(a4=129) == -3 and call(a6=0) == -3 and call(a6=33) == -3
+    assert call(a7=0) == -3 and call(a7=129) == -3
+    assert call(a5=0.0) == -3 and call(a5=1.5) == -3 and call(a5=float("nan")) == -3
 
 
 def test_decode_argument_checks(L):

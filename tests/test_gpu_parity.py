@@ -312,3 +312,91 @@ def test_full_size_235b_shape(torch, B_, oracle):
                 say(ctx, "T=%d err=%.2e" % (ref["n_active"], err))
         finally:
             B_.set_kernel_path(0)
+
+
+# ---- general OEA (Algorithm 2): top-p cut of the baseline, k_max, rank window max_p
+
+def route_general_gpu(torch, B_, lg, k0, p, k_max, max_p, mask=None):
+    res = B_.oea_route_general(torch.from_numpy(lg).cuda(), k0, p, k_max, max_p,
+                               token_mask=None if mask is None else torch.from_numpy(mask).cuda())
+    torch.cuda.synchronize()
+    return {n: v.cpu().numpy() for n, v in res.items()}
+
+
+def top_p_is_clear(lg, k0, p, margin=1e-9):
+    """True if no token's sorted cumulative softmax mass comes within `margin` of p inside its k0
+    best experts: then the top-p decision cannot depend on the summation order."""
+    if p >= 1.0:
+        return True
+    l = lg.astype(np.float64)
+    r = np.exp(l - l.max(axis=1, keepdims=True))
+    r /= r.sum(axis=1, keepdims=True)
+    cum = np.cumsum(-np.sort(-r, axis=1), axis=1)[:, :k0]
+    return bool((np.abs(cum - p) > margin).all())
+
+
+GENERAL_CASES = [(B, N, k0, p, k_max, max_p, kind, seed)
+                 for (B, N) in [(16, 128), (4, 16), (33, 64), (7, 200), (130, 100), (1, 128)]
+                 for (k0, k_max) in [(1, 4), (3, 8), (8, 8), (6, 4), (2, 12)]
+                 for p in (1.0, 0.9, 0.5, 0.2)
+                 for max_p in ("N", 32, 5)
+                 for kind in ("gaussian", "skew", "ties", "wide")
+                 for seed in (0,)]
+
+
+def test_route_general_bit_exact(torch, B_, oracle):
+    n = skipped = 0
+    for (B, N, k0, p, k_max, max_p, kind, seed) in GENERAL_CASES:
+        if k0 > N or k_max > N:
+            continue
+        mp = N if max_p == "N" else min(max_p, N)
+        lg = W.make_logits(B, N, 700 + seed, kind)
+        if not top_p_is_clear(lg, k0, p):
+            skipped += 1
+            continue
+        mask = None
+        if B >= 4 and seed == 0 and kind == "skew":
+            mask = np.ones(B, np.uint8)
+            mask[1::3] = 0
+        ctx = "general B=%d N=%d k0=%d p=%g k_max=%d max_p=%d kind=%s" % (B, N, k0, p, k_max, mp, kind)
+        got = route_general_gpu(torch, B_, lg, k0, p, k_max, mp, mask)
+        ref = oracle.route_general(lg, k0, p, k_max, mp, token_mask=mask)
+        assert np.array_equal(got["n_base"], ref["n_base"]), ctx
+        assert_routing_equal(got, ref, ctx)
+        n += 1
+    say("general routing cases checked: %d, skipped as ambiguous: %d" % (n, skipped))
+    assert n > 1000 and skipped < n // 20
+
+
+def test_route_general_reduces_to_algorithm_1(torch, B_):
+    for (B, N, k, k0) in [(16, 128, 8, 3), (33, 64, 6, 6), (5, 512, 32, 7), (200, 130, 8, 1)]:
+        lg = W.make_logits(B, N, 42, "gaussian")
+        a = route_gpu(torch, B_, lg, k, k0)
+        g = route_general_gpu(torch, B_, lg, k0, 1.0, k, N)
+        for f in ("expert_idx", "n_sel", "active_list", "n_active"):
+            assert np.array_equal(a[f], g[f]), (B, N, k, k0, f)
+        assert np.array_equal(a["gate_w"], g["gate_w"]) or np.abs(a["gate_w"] - g["gate_w"]).max() <= 1e-6
+        assert (g["n_base"] == k0).all()
+
+
+def test_layer_general_oea(torch, B_, oracle):
+    """The whole layer under Algorithm 2 (top-p cut and rank window), three-kernel path."""
+    for name, k0, p, max_p in (("mid_bf16", 3, 0.2, None), ("mid_bf16", 4, None, 6), ("qwen3_30b", 3, 0.1, 24)):
+        L = W.make_layer(name, 11)
+        dev = {f: B_.to_device(getattr(L, f)) for f in ("x", "w_router", "w_gate", "w_up", "w_down")}
+        ws = B_.new_workspace(L.B, L.d, L.N, L.I, L.k)
+        out, tap = B_.moe_decode(dev["x"], dev["w_router"], dev["w_gate"], dev["w_up"], dev["w_down"], L.k, k0, ws,
+                                 taps=True, top_p=p, max_p=max_p)
+        torch.cuda.synchronize()
+        tap = {n: v.cpu().numpy() for n, v in tap.items()}
+        pp, mp = (1.0 if p is None else p), (L.N if max_p is None else max_p)
+        ctx = "layer general %s k0=%d p=%s max_p=%s" % (name, k0, p, max_p)
+        assert top_p_is_clear(tap["logits"], k0, pp), ctx
+        ref = oracle.route_general(tap["logits"], k0, pp, L.k, mp)
+        assert_routing_equal(tap, ref, ctx)
+        if p is not None:
+            assert (ref["n_base"] < k0).any(), "the top-p cut should bite in this case"
+        ref_out = oracle.moe_combine(L.x, L.w_gate, L.w_up, L.w_down, ref["expert_idx"], ref["gate_w"])
+        err = np.abs(out.cpu().numpy().astype(np.float64) - ref_out).max() / np.abs(ref_out).max()
+        say("%s: T=%d, max|d|/max|ref| = %.2e" % (ctx, ref["n_active"], err))
+        assert err <= TOL[L.dtype], ctx
