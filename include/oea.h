@@ -40,6 +40,7 @@ typedef enum { OEA_F32 = 0, OEA_BF16 = 1 } oea_dtype;
 #define OEA_MAX_K 32   /* experts per token */
 #define OEA_MAX_B 1024 /* tokens per decode batch */
 #define OEA_MAX_D 8192 /* embedding dimension and expert hidden dimension */
+#define OEA_MAX_POSITIONS 65535 /* decode positions per oea_route_batched call */
 
 /* Host, pure.  Static text for a status code. */
 const char *oea_status_string(int status);
@@ -73,6 +74,18 @@ int oea_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 int oea_route(const float *router_logits, int B, int N, int k, int k0, int32_t *expert_idx,
               float *gate_w, int32_t *n_sel, int32_t *active_list, int32_t *n_active,
               void *stream);
+
+/*
+ * oea_route for L independent decode positions in one launch (Section 4: each position and layer
+ * is routed on its own; the paper's language-modelling evaluation routes all positions of a
+ * sequence this way).  Position l uses rows [l*B, (l+1)*B) of the logits and nothing else.
+ *   router_logits [L,B,N]; token_mask [L,B] uint8 or NULL (0 = padding token);
+ *   expert_idx, gate_w [L,B,k]; n_sel [L,B]; active_list [L,N]; n_active [L].
+ * Limits as oea_route, 1 <= L <= OEA_MAX_POSITIONS.
+ */
+int oea_route_batched(const float *router_logits, const uint8_t *token_mask, int L, int B, int N,
+                      int k, int k0, int32_t *expert_idx, float *gate_w, int32_t *n_sel,
+                      int32_t *active_list, int32_t *n_active, void *stream);
 
 /*
  * General OEA routing (Algorithm 2 of the paper, Section 3.2 "General OEA"): as oea_route, with

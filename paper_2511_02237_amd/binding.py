@@ -16,7 +16,7 @@ OEA_F32, OEA_BF16 = 0, 1
 OEA_OK = 0
 STATUS = {"OEA_ERR_NULL": -1, "OEA_ERR_SHAPE": -2, "OEA_ERR_K": -3, "OEA_ERR_ALIGN": -4,
           "OEA_ERR_WORKSPACE": -5, "OEA_ERR_DTYPE": -6, "OEA_ERR_HIP": -7}
-EXPORTS = ("oea_status_string", "oea_workspace_bytes", "oea_workspace_init", "oea_route", "oea_route_general",
+EXPORTS = ("oea_status_string", "oea_workspace_bytes", "oea_workspace_init", "oea_route", "oea_route_batched", "oea_route_general",
            "moe_decode", "moe_decode_ex", "oea_set_kernel_path")
 
 
@@ -56,6 +56,8 @@ def lib():
         L.oea_set_kernel_path.argtypes = [ci]
         L.oea_route.restype = ci
         L.oea_route.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
+        L.oea_route_batched.restype = ci
+        L.oea_route_batched.argtypes = [vp, vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
         L.oea_route_general.restype = ci
         L.oea_route_general.argtypes = [vp, vp, ci, ci, ci, ctypes.c_double, ci, ci, vp, vp, vp, vp, vp, vp, vp]
         L.moe_decode.restype = ci
@@ -125,6 +127,25 @@ def oea_route(router_logits, k, k0, stream=None, out=None):
     _check(lib().oea_route(_ptr(router_logits), B, N, int(k), int(k0), _ptr(out["expert_idx"]),
                            _ptr(out["gate_w"]), _ptr(out["n_sel"]), _ptr(out["active_list"]),
                            _ptr(out["n_active"]), _stream(stream)))
+    return out
+
+
+def oea_route_batched(router_logits, k, k0, token_mask=None, stream=None):
+    """router_logits [L,B,N] float32 cuda: L independent positions routed in one launch."""
+    assert router_logits.is_cuda and router_logits.dtype == torch.float32 and router_logits.is_contiguous()
+    L, B, N = router_logits.shape
+    dev = router_logits.device
+    if token_mask is not None:
+        assert token_mask.is_cuda and token_mask.dtype == torch.uint8 and tuple(token_mask.shape) == (L, B)
+        assert token_mask.is_contiguous()
+    out = dict(expert_idx=torch.empty((L, B, k), dtype=torch.int32, device=dev),
+               gate_w=torch.empty((L, B, k), dtype=torch.float32, device=dev),
+               n_sel=torch.empty((L, B), dtype=torch.int32, device=dev),
+               active_list=torch.empty((L, N), dtype=torch.int32, device=dev),
+               n_active=torch.empty((L,), dtype=torch.int32, device=dev))
+    _check(lib().oea_route_batched(_ptr(router_logits), _ptr(token_mask), L, B, N, int(k), int(k0),
+                                   _ptr(out["expert_idx"]), _ptr(out["gate_w"]), _ptr(out["n_sel"]),
+                                   _ptr(out["active_list"]), _ptr(out["n_active"]), _stream(stream)))
     return out
 
 

@@ -106,7 +106,19 @@ extern "C" int oea_route(const float* router_logits, int B, int N, int k, int k0
   int rc = check_route_sizes(B, N, k, k0);
   if (rc != OEA_OK) return rc;
   RouteOut o{expert_idx, gate_w, n_sel, active_list, n_active, nullptr, nullptr, nullptr};
-  hipError_t e = launch_route(router_logits, nullptr, B, N, k, k0, o, static_cast<hipStream_t>(stream));
+  hipError_t e = launch_route(router_logits, nullptr, 1, B, N, k, k0, o, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? OEA_OK : OEA_ERR_HIP;
+}
+
+extern "C" int oea_route_batched(const float* router_logits, const uint8_t* token_mask, int L, int B, int N, int k,
+                                 int k0, int32_t* expert_idx, float* gate_w, int32_t* n_sel, int32_t* active_list,
+                                 int32_t* n_active, void* stream) {
+  if (!router_logits || !expert_idx || !gate_w || !n_sel || !active_list || !n_active) return OEA_ERR_NULL;
+  if (L < 1 || L > OEA_MAX_POSITIONS) return OEA_ERR_SHAPE;
+  int rc = check_route_sizes(B, N, k, k0);
+  if (rc != OEA_OK) return rc;
+  RouteOut o{expert_idx, gate_w, n_sel, active_list, n_active, nullptr, nullptr, nullptr};
+  hipError_t e = launch_route(router_logits, token_mask, L, B, N, k, k0, o, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? OEA_OK : OEA_ERR_HIP;
 }
 

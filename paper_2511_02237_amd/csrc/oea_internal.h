@@ -57,7 +57,8 @@ struct RouteGeneralArgs {
 
 // launchers (each returns the hipError_t of the launch)
 hipError_t launch_fill_zero(uint32_t* p, size_t n_words, hipStream_t s);
-hipError_t launch_route(const float* logits, const uint8_t* token_mask, int B, int N, int k, int k0,
+// L independent positions: logits [L,B,N]; every output has a leading dimension L
+hipError_t launch_route(const float* logits, const uint8_t* token_mask, int L, int B, int N, int k, int k0,
                         RouteOut o, hipStream_t s);
 hipError_t launch_router_and_route(const void* x, const void* w_router, const float* bias,
                                    const uint8_t* token_mask, int B, int d, int N, int k, int k0,

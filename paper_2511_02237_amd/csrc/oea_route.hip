@@ -8,14 +8,31 @@ namespace {
 
 constexpr int kRouteThreads = 1024;
 
+// One workgroup routes one decode position (blockIdx.x): its B rows of logits and its own output slices.
+// Positions are independent (Section 4: every position and layer is routed separately), so a grid
+// of L workgroups routes L positions in one launch.
 template <int NV>
 __global__ __launch_bounds__(kRouteThreads) void route_kernel(const float* logits, const uint8_t* token_mask,
                                                               int B, int N, int k, int k0, RouteOut o) {
   extern __shared__ uint32_t lds[];
-  if (B <= kRouteThreads / 64)
+  const size_t pos = blockIdx.x;
+  logits += pos * B * N;
+  if (token_mask) token_mask += pos * B;
+  o.expert_idx += pos * B * k;
+  o.gate_w += pos * B * k;
+  o.n_sel += pos * B;
+  o.active_list += pos * N;
+  o.n_active += pos;
+  if (NV <= 2 && k <= 16 && B <= 4 * (kRouteThreads / 64)) {
+    // few experts: one DPP row of 16 lanes per token, four tokens per wavefront
+    RowCarry<4 * NV> c;
+    route_union_rows<4 * NV, kRouteThreads>(logits, token_mask, B, N, k0, o, lds, c);
+    route_fill_rows<4 * NV, kRouteThreads>(B, N, k, k0, o, lds, c);
+  } else if (B <= kRouteThreads / 64) {
     route_block<NV, kRouteThreads, 1>(logits, token_mask, B, N, k, k0, o, lds);
-  else
+  } else {
     route_block<NV, kRouteThreads, 0>(logits, token_mask, B, N, k, k0, o, lds);
+  }
 }
 
 template <int NV>
@@ -106,7 +123,7 @@ hipError_t launch_fill_zero(uint32_t* p, size_t n_words, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_route(const float* logits, const uint8_t* token_mask, int B, int N, int k, int k0,
+hipError_t launch_route(const float* logits, const uint8_t* token_mask, int L, int B, int N, int k, int k0,
                         RouteOut o, hipStream_t s) {
   const size_t lds = route_lds_bytes(B, N);
   switch (nv_for(N)) {
@@ -117,7 +134,7 @@ hipError_t launch_route(const float* logits, const uint8_t* token_mask, int B, i
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);           \
       if (e != hipSuccess) return e;                                                                      \
     }                                                                                                     \
-    hipLaunchKernelGGL(route_kernel<NV>, dim3(1), dim3(kRouteThreads), lds, s, logits, token_mask, B, N, k, \
+    hipLaunchKernelGGL(route_kernel<NV>, dim3(L), dim3(kRouteThreads), lds, s, logits, token_mask, B, N, k, \
                        k0, o);                                                                            \
   } break;
     OEA_CASE(1)

@@ -23,6 +23,7 @@ def L():
     lib.oea_workspace_bytes.argtypes = [ci] * 5
     lib.oea_workspace_init.argtypes = [vp, sz, vp]
     lib.oea_route.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
+    lib.oea_route_batched.argtypes = [vp, vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
     lib.oea_route_general.argtypes = [vp, vp, ci, ci, ci, ctypes.c_double, ci, ci, vp, vp, vp, vp, vp, vp, vp]
     lib.moe_decode.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp]
     lib.moe_decode_ex.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp, vp]
@@ -79,6 +80,14 @@ def test_route_argument_checks(L):
     assert call(a0=None) == -1 and call(a5=None) == -1 and call(a9=None) == -1
     assert call(a1=0) == -2 and call(a1=1025) == -2 and call(a2=0) == -2 and call(a2=513) == -2
     assert call(a4=0) == -3 and call(a4=9) == -3 and call(a3=129) == -3 and call(a3=33, a4=33) == -3
+
+
+def test_route_batched_argument_checks(L):
+    ok = [P, None, 4, 16, 128, 8, 3, P, P, P, P, P, None]
+    assert L.oea_route_batched(*([None] + ok[1:])) == -1
+    assert L.oea_route_batched(*(ok[:2] + [0] + ok[3:])) == -2
+    assert L.oea_route_batched(*(ok[:2] + [70000] + ok[3:])) == -2
+    assert L.oea_route_batched(*(ok[:6] + [9] + ok[7:])) == -3
 
 
 def test_route_general_argument_checks(L):
