@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--kernel-path", type=int, default=0, help="0 automatic (fused kernel), 1 generic, 2 three kernels")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain device copy of known size (reference for rocprofv3 --pmc byte counters)")
+    ap.add_argument("--sweep", default="", help="comma list of batch sizes: time each (k0 from --k0s, default 3,5,8) "
+                                                "and fit latency = c + b*T + a*pairs instead of the one-line report")
     ap.add_argument("--launch", default="stream", choices=["stream", "graph"],
                     help="timed steps launched one by one, or captured into one HIP graph and replayed (measured: same latency)")
     ap.add_argument("--verbose", action="store_true")
@@ -97,6 +99,36 @@ class Hip:
 
 def main():
     args = parse()
+    if args.sweep:
+        return sweep(args)
+    print(json.dumps(run(args)))
+
+
+def sweep(args):
+    """Batch sweep on one workload: latency against unique experts T and (token, expert) pairs, fitted
+    as latency = c + b*T + a*pairs (the two terms of the paper's latency model, Eq. 2)."""
+    import numpy as np
+    rows = []
+    for B in [int(v) for v in args.sweep.split(",")]:
+        a = argparse.Namespace(**vars(args))
+        a.batch, a.trials, a.no_cpu, a.sweep = B, 1, True, ""
+        a.k0s = args.k0s or "3,5,8"
+        a.k0 = int(a.k0s.split(",")[0])
+        r = run(a)
+        for k0, v in r["per_k0"].items():
+            rows.append(dict(B=B, k0=int(k0), T=v["unique_experts"], pairs=v["pairs"], latency_us=v["latency_us"],
+                             frac_of_peak=v["frac_of_peak"]))
+    A = np.array([[1.0, r_["T"], r_["pairs"]] for r_ in rows])
+    y = np.array([r_["latency_us"] for r_ in rows])
+    coef, *_ = np.linalg.lstsq(A, y, rcond=None)
+    pred = A @ coef
+    r2 = 1.0 - float(((pred - y) ** 2).sum() / ((y - y.mean()) ** 2).sum())
+    print(json.dumps(dict(workload=args.workload, rows=rows,
+                          fit=dict(intercept_us=round(float(coef[0]), 2), us_per_unique_expert=round(float(coef[1]), 4),
+                                   us_per_pair=round(float(coef[2]), 4), r2=round(r2, 5)))))
+
+
+def run(args):
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path is a single-GPU kernel pipeline; no "
               "collectives are part of it). Re-run with --gpus 1.", file=sys.stderr)
@@ -336,7 +368,7 @@ def main():
                 layer_frac_of_hbm_peak=table[str(args.k0)]["frac_of_peak"],
                 per_k0=table, latency_vs_unique_experts_fit=fit, parity_max_rel_err=parity,
                 roofline=roofline, cpu_baseline=cpu)
-    print(json.dumps(line))
+    return line
 
 
 if __name__ == "__main__":

@@ -139,10 +139,12 @@ int moe_decode(const void *x, const void *W_router, const void *W_gate, const vo
 
 /*
  * Host.  Test aid: which expert-FFN kernels later moe_decode calls of this process use.
- *   0 = automatic: the single fused kernel for the shapes it is built for, else three kernels
- *       (streaming expert kernels when the staged token vectors fit in LDS, else generic ones)
- *   1 = three kernels, generic expert kernels only (any batch size; vectors staged per expert)
- *   2 = three kernels, automatic choice between streaming and generic expert kernels
+ *   0 = automatic: the single fused kernel for the shapes and batch sizes it is built for, else
+ *       three kernels (router + routing, gate/up, down) with the best expert kernels that apply
+ *   1 = three kernels, generic expert kernels only (any shape and batch size)
+ *   2 = three kernels, streaming expert kernels with fixed shares when the token vectors fit in
+ *       LDS, else generic ones
+ *   3 = three kernels, the fused kernel's stage code as expert kernels where the shape allows
  * Returns OEA_OK, or OEA_ERR_SHAPE for another value.  Not thread-safe against running calls.
  */
 int oea_set_kernel_path(int path);

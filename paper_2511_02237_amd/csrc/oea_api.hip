@@ -84,7 +84,7 @@ extern "C" size_t oea_workspace_bytes(int B, int d, int N, int I, int k) {
 static int g_kernel_path = 0;
 
 extern "C" int oea_set_kernel_path(int path) {
-  if (path < 0 || path > 2) return OEA_ERR_SHAPE;
+  if (path < 0 || path > 3) return OEA_ERR_SHAPE;
   g_kernel_path = path;
   set_force_generic(path == 1);
   return OEA_OK;
@@ -187,9 +187,14 @@ extern "C" int moe_decode_ex(const void* x, const void* W_router, const void* W_
                                 N, k, k0, dt, logits, out, reinterpret_cast<uint32_t*>(ws + w.ctrl), ro,
                                 general ? &ga : nullptr, s);
     if (e != hipSuccess || !mark(1) || !mark(2)) return OEA_ERR_HIP;
-    e = launch_expert_gate_up(x, W_gate, W_up, h, B, d, N, I, k, dt, g, s);
+    const bool stage_kernels = g_kernel_path == 0 || g_kernel_path == 3;
+    e = stage_kernels ? try_launch_stage_kernels(0, x, W_gate, W_up, h, nullptr, B, d, N, I, k, dt, g, s)
+                      : hipErrorNotSupported;
+    if (e == hipErrorNotSupported) e = launch_expert_gate_up(x, W_gate, W_up, h, B, d, N, I, k, dt, g, s);
     if (e != hipSuccess || !mark(3) || !mark(4)) return OEA_ERR_HIP;
-    e = launch_expert_down(h, W_down, out, B, d, N, I, k, dt, g, s);
+    e = stage_kernels ? try_launch_stage_kernels(1, h, W_down, nullptr, nullptr, out, B, d, N, I, k, dt, g, s)
+                      : hipErrorNotSupported;
+    if (e == hipErrorNotSupported) e = launch_expert_down(h, W_down, out, B, d, N, I, k, dt, g, s);
     if (e != hipSuccess || !mark(5)) return OEA_ERR_HIP;
   }
 

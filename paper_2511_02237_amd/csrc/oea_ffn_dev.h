@@ -187,14 +187,16 @@ __device__ __forceinline__ void load_tile(uint4 (&w)[NM][RG][NCH], const WT* wa,
 // one (expert, token) pair against the tile held in w: dot products, reduction over the row's lanes, epilogue
 // use_buf: the results go to the wavefront's result buffer in LDS (entry eidx + row of the
 // tile) instead of memory; flush_results writes them out when the wavefront has streamed all its rows.
-template <typename WT, int STAGE, int NM, int LPR, int NCH, int RG, bool FULL, bool COH = false, bool EBUF = false>
+// GATHER: the staged vectors are indexed by pair in the gate/up stage too (x rows gathered per pair).
+template <typename WT, int STAGE, int NM, int LPR, int NCH, int RG, bool FULL, bool COH = false, bool EBUF = false,
+          bool GATHER = false>
 __device__ __forceinline__ void token_step(const uint4 (&w)[NM][RG][NCH], const int* l_tok, const float* l_gw,
                                            const uint4* l_vec, WT* h_out, float* out, int rows, int L16, int off0,
                                            int lsub, int lrow, int rloc, int nrows, int pair, float* ebuf = nullptr,
                                            bool use_buf = false, int eidx = 0) {
   constexpr int R = 64 / LPR;
   const int tok = l_tok[pair];
-  const uint4* vq = l_vec + (size_t)(STAGE == 0 ? tok : pair) * L16;
+  const uint4* vq = l_vec + (size_t)(STAGE == 0 && !GATHER ? tok : pair) * L16;
   uint4 v[NCH];
 #pragma unroll
   for (int ch = 0; ch < NCH; ++ch) {
@@ -251,7 +253,8 @@ __device__ __forceinline__ void token_step(const uint4 (&w)[NM][RG][NCH], const 
 // rare expert with more pairs than that.
 constexpr int kUnrollTok = 8;
 
-template <typename WT, int STAGE, int NM, int LPR, int NCH, int RG, bool FULL, bool COH = false, bool EBUF = false>
+template <typename WT, int STAGE, int NM, int LPR, int NCH, int RG, bool FULL, bool COH = false, bool EBUF = false,
+          bool GATHER = false>
 __device__ __forceinline__ void compute_tile(const uint4 (&w)[NM][RG][NCH], const int* l_tok, const float* l_gw,
                                              const uint4* l_vec, WT* h_out, float* out, int rows, int L16,
                                              int off0, int lsub, int lrow, const TileRef t, int nrows,
@@ -259,12 +262,12 @@ __device__ __forceinline__ void compute_tile(const uint4 (&w)[NM][RG][NCH], cons
 #pragma unroll
   for (int q = 0; q < kUnrollTok; ++q)
     if (q < t.cnt)
-      token_step<WT, STAGE, NM, LPR, NCH, RG, FULL, COH, EBUF>(w, l_tok, l_gw, l_vec, h_out, out, rows, L16, off0, lsub,
+      token_step<WT, STAGE, NM, LPR, NCH, RG, FULL, COH, EBUF, GATHER>(w, l_tok, l_gw, l_vec, h_out, out, rows, L16, off0, lsub,
                                                                lrow, t.rloc, nrows, t.vb + q, ebuf, use_buf,
                                                                t.ebase + q * t.estride);
   if (t.cnt > kUnrollTok)
     for (int q = kUnrollTok; q < t.cnt; ++q)
-      token_step<WT, STAGE, NM, LPR, NCH, RG, FULL, COH, EBUF>(w, l_tok, l_gw, l_vec, h_out, out, rows, L16, off0, lsub,
+      token_step<WT, STAGE, NM, LPR, NCH, RG, FULL, COH, EBUF, GATHER>(w, l_tok, l_gw, l_vec, h_out, out, rows, L16, off0, lsub,
                                                                lrow, t.rloc, nrows, t.vb + q, ebuf, use_buf,
                                                                t.ebase + q * t.estride);
 }

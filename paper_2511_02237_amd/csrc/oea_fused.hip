@@ -196,12 +196,16 @@ __device__ __forceinline__ int wg_first_row(const int* l_off, int T, int rows, i
 // issued between the weight loads would have to complete (the memory counter retires in order)
 // before the NEXT tile's data counts as arrived.  If they do not fit (many rows of a very popular
 // expert) they are written directly instead.
-template <typename WT, int STAGE, int LPR, int NCH, int RG, typename Mid>
+// The pairs of the workgroup's experts are numbered 0..nvec-1 in the grouped order; only those in
+// [c0, c1) are processed (their vectors are what l_vec holds, in that order), which lets a caller with
+// little LDS walk a long pair list in pieces.  GATHER: see token_step.
+template <typename WT, int STAGE, int LPR, int NCH, int RG, bool GATHER = false, typename Mid>
 __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_out, float* out, int rows, int L,
                                             int R0, int R1, int N, int pairs_max, int cap_vec, const int* l_active,
                                             const int* l_off, const int* l_tok, const float* l_gw,
                                             const uint4* l_vec, float* ebuf, int ecap, uint32_t* l_next, Mid mid,
-                                            unsigned long long* tl_wave = nullptr) {
+                                            unsigned long long* tl_wave = nullptr, int c0 = 0,
+                                            int c1 = 0x7fffffff) {
   constexpr int EPL = 16 / int(sizeof(WT));
   constexpr int R = 64 / LPR;
   constexpr int NM = STAGE == 0 ? 2 : 1;
@@ -254,22 +258,30 @@ __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_ou
   const int off2 = nseg > 1 ? uniform(l_off[a0 + 2]) : off1;
   const int off3 = nseg > 2 ? uniform(l_off[a0 + 3]) : off2;
   const int nvec = off3 - off0;
-  if (off0 < 0 || off1 < off0 || off2 < off1 || off3 < off2 || nvec > cap_vec || off0 + nvec > pairs_max)
-    wg_has = false;  // never true, as above
-  const SegView sv{rows, a0, e0, e1, e2, off1 - off0, off2 - off1, off3 - off2, hi, lo};
-  const int* const s_tok = l_tok + (wg_has ? off0 : 0);
-  const float* const s_gw = l_gw + (wg_has ? off0 : 0);
+  if (off0 < 0 || off1 < off0 || off2 < off1 || off3 < off2 || off0 + nvec > pairs_max) wg_has = false;  // never true
+  // pairs of each segment inside [c0, c1)
+  const int q0 = c0 < 0 ? 0 : c0, q1 = c1 < nvec ? c1 : nvec;
+  auto clip = [&](int from, int to) __attribute__((always_inline)) {  // pairs [from,to) of the list, cut to [q0,q1)
+    const int a = from > q0 ? from : q0, b = to < q1 ? to : q1;
+    return b > a ? b - a : 0;
+  };
+  const int n0 = clip(0, off1 - off0), n1 = clip(off1 - off0, off2 - off0), n2 = clip(off2 - off0, off3 - off0);
+  if (n0 + n1 + n2 > cap_vec) wg_has = false;  // the caller staged at most cap_vec vectors
+  const int base = wg_has ? off0 + q0 : 0;     // first pair of the piece
+  const SegView sv{rows, a0, e0, e1, e2, n0, n1, n2, hi, lo};
+  const int* const s_tok = l_tok + base;
+  const float* const s_gw = l_gw + base;
   const int n_res = result_entries(sv);
   const bool use_buf = n_res <= ecap * kFfnWaves;
 
   if (wg_has && nA > 0) {
     while (true) {
-      compute_tile<WT, STAGE, NM, LPR, NCH, RG, true, true, true>(wA, s_tok, s_gw, l_vec, h_out, out, rows, L16, off0,
+      compute_tile<WT, STAGE, NM, LPR, NCH, RG, true, true, true, GATHER>(wA, s_tok, s_gw, l_vec, h_out, out, rows, L16, base,
                                                                   lsub, lrow, tile_ref_buffered(sv, rA), nA, ebuf, use_buf);
       take_tile(rA, nA);
       load_tile<WT, NM, LPR, NCH, RG, true>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv, rA), nA);
       if (nB <= 0) break;
-      compute_tile<WT, STAGE, NM, LPR, NCH, RG, true, true, true>(wB, s_tok, s_gw, l_vec, h_out, out, rows, L16, off0,
+      compute_tile<WT, STAGE, NM, LPR, NCH, RG, true, true, true, GATHER>(wB, s_tok, s_gw, l_vec, h_out, out, rows, L16, base,
                                                                   lsub, lrow, tile_ref_buffered(sv, rB), nB, ebuf, use_buf);
       take_tile(rB, nB);
       load_tile<WT, NM, LPR, NCH, RG, true>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv, rB), nB);
@@ -280,7 +292,7 @@ __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_ou
   if (tl_wave && lane == 0) tl_wave[blockIdx.x * kFfnWaves + (tid >> 6)] = wall_clock64();
 #endif
   __syncthreads();  // every wavefront's results are in the buffer
-  if (wg_has && use_buf) flush_results<WT, STAGE>(sv, ebuf, s_tok, s_gw, h_out, out, off0, tid);
+  if (wg_has && use_buf) flush_results<WT, STAGE>(sv, ebuf, s_tok, s_gw, h_out, out, base, tid);
 }
 
 // Layout of the per-expert completion words in the control area: counter and flag of the expert at
@@ -548,7 +560,107 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
 #endif
 }
 
-int g_fused_cus = -1;  // CUs when the residency check passed, 0 when it failed, -1 before the check
+int g_fused_cus = -1;  // CUs of the device (0: query failed), -1 before the query
+
+// ---------------------------------------------------------------------------------------------
+// One expert stage as a kernel of its own, for batches the fused kernel does not take (B > 32):
+// the routing result is read from the workspace, the work is cut by cost as above, and every
+// workgroup stages only the token vectors of ITS experts' pairs (gathered rows of x for the gate/up
+// stage, rows of h for the down stage).  If a workgroup's pairs exceed its LDS share it walks them
+// in pieces and streams its weight rows once per piece: always correct, rarely needed.
+struct StageParams {
+  const void* wa;   // stage 0: W_gate; stage 1: W_down   [N, rows, L]
+  const void* wb;   // stage 0: W_up
+  const void* vec;  // stage 0: x [B, L]; stage 1: h [P, L]
+  void* h_out;      // stage 0: h [P, rows]
+  float* out;       // stage 1: out [B, rows]
+  Grouping g;
+  int rows, L, N, B, pairs_max;
+  int cap_vec;   // vectors of length L the LDS vector area holds
+  int cap_list;  // entries of the staged pair lists
+  int ecap;      // floats of result buffer per wavefront
+};
+
+template <typename WT, int STAGE, int LPR, int NCH, int RG>
+__global__ __launch_bounds__(kFfnThreads) void expert_stage_kernel(StageParams p) {
+  extern __shared__ uint4 lds4[];
+  constexpr int EPL = 16 / int(sizeof(WT));
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int N = p.N, rows = p.rows, L = p.L;
+  const int L16 = L / EPL;
+  // LDS: [dump 16 B][active N][off N+4][counter 4][tok cap_list][gw cap_list][vectors][results]
+  int* const l_active = reinterpret_cast<int*>(lds4 + 1);
+  int* const l_off = l_active + N;
+  uint32_t* const l_next = reinterpret_cast<uint32_t*>(l_off + N + 4);
+  int* const l_tok = reinterpret_cast<int*>(l_next + 4);
+  float* const l_gw = reinterpret_cast<float*>(l_tok + p.cap_list);
+  uint4* const l_vec = lds4 + 1 + (2 * (size_t)N + 8 + 2 * (size_t)p.cap_list + 3) / 4;
+  float* const ebuf = reinterpret_cast<float*>(l_vec + (size_t)p.cap_vec * L16);
+
+  int T = *p.g.n_active;
+  T = T < 0 ? 0 : (T > N ? N : T);
+  for (int i = tid; i < N; i += kFfnThreads) l_active[i] = i < T ? p.g.active_list[i] : 0;
+  for (int i = tid; i <= N; i += kFfnThreads) l_off[i] = p.g.grp_off[i <= T ? i : T];
+  __syncthreads();
+  const int beta = STAGE == 0 ? kBetaUp : kBetaDown;
+  const int R0 = wg_first_row(l_off, T, rows, beta, blockIdx.x, gridDim.x, lane);
+  const int R1 = wg_first_row(l_off, T, rows, beta, blockIdx.x + 1, gridDim.x, lane);
+  if (R0 >= R1) return;  // uniform over the workgroup
+  const int a0 = R0 / rows, a1 = (R1 - 1) / rows;
+  if (a1 - a0 + 1 > kMaxSeg) return;  // excluded by the launcher's choice of grid; keeps the code below in bounds
+  const int off0 = l_off[a0];
+  int nvec = l_off[a1 + 1] - off0;
+  if (off0 < 0 || nvec < 0 || off0 + nvec > p.pairs_max) return;  // never true after a valid routing
+  if (nvec > p.cap_list) nvec = p.cap_list;  // cap_list >= kMaxSeg * B covers every valid routing
+  // pair lists of this workgroup's experts; addressed by the global pair number below
+  for (int i = tid; i < nvec; i += kFfnThreads) {
+    const int t = p.g.grp_tok[off0 + i];
+    l_tok[i] = t < 0 ? 0 : (t >= p.B ? p.B - 1 : t);
+    l_gw[i] = p.g.grp_gw[off0 + i];
+  }
+  const uint4* const vsrc = reinterpret_cast<const uint4*>(p.vec);
+  for (int c0 = 0; c0 < nvec; c0 += p.cap_vec) {
+    const int c1 = c0 + p.cap_vec < nvec ? c0 + p.cap_vec : nvec;
+    __syncthreads();  // the lists are written; the previous piece is done with the vector area
+    if (tid == 0) *l_next = 0;
+    for (int i16 = tid; i16 < (c1 - c0) * L16; i16 += kFfnThreads) {
+      const int v = i16 / L16, c = i16 - v * L16;
+      const size_t row = STAGE == 0 ? (size_t)l_tok[c0 + v] : (size_t)(off0 + c0 + v);
+      l_vec[i16] = vsrc[row * L16 + c];
+    }
+    __syncthreads();
+    fused_stage<WT, STAGE, LPR, NCH, RG, true>(
+        static_cast<const WT*>(p.wa), static_cast<const WT*>(p.wb), static_cast<WT*>(p.h_out), p.out, rows, L, R0, R1,
+        N, p.pairs_max, p.cap_vec, l_active, l_off, l_tok - off0, l_gw - off0, l_vec, ebuf, p.ecap, l_next,
+        [](int, int) {}, nullptr, c0, c1);
+  }
+}
+
+template <typename WT, int STAGE, int LPR, int NCH, int RG>
+hipError_t launch_stage_one(StageParams p, hipStream_t s) {
+  auto kern = expert_stage_kernel<WT, STAGE, LPR, NCH, RG>;
+  const int grid = g_fused_cus;
+  // LDS plan: lists, then as many vectors as fit beside a result buffer of 1024 floats per wavefront
+  p.cap_list = kMaxSeg * p.B < p.pairs_max ? kMaxSeg * p.B : p.pairs_max;
+  const size_t fixed = 16 + ((2 * (size_t)p.N + 8 + 2 * (size_t)p.cap_list + 3) / 4) * 16;
+  p.ecap = 1024;
+  const size_t res = (size_t)p.ecap * kFfnWaves * sizeof(float);
+  if (fixed + res + (size_t)p.L * sizeof(WT) > kFusedLdsMax) return hipErrorNotSupported;
+  size_t cap = (kFusedLdsMax - fixed - res) / ((size_t)p.L * sizeof(WT));
+  if (cap > (size_t)p.cap_list) cap = p.cap_list;
+  p.cap_vec = (int)cap;
+  const size_t lds = fixed + cap * p.L * sizeof(WT) + res;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLdsMax);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kFfnThreads), lds, s, p);
+  return hipGetLastError();
+}
+
 
 template <typename WT, int LPR0, int NCH0, int LPR1, int NCH1, int NV>
 hipError_t launch_fused_one(const FusedParams& p, size_t lds_bytes, hipStream_t s) {
@@ -634,6 +746,43 @@ hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_g
   p.spin_limit = 4u << 20;  // polls of >= 100 ns each: gives up after about a second
   if (shape30) return launch_fused_one<uint16_t, 32, 8, 16, 6, 2>(p, lds_bytes, s);
   return launch_fused_one<uint16_t, 64, 8, 32, 6, 2>(p, lds_bytes, s);
+}
+
+// The two expert stages as separate kernels built from the fused kernel's stage code (batches the
+// fused kernel does not take); hipErrorNotSupported for shapes they are not built for.
+hipError_t try_launch_stage_kernels(int stage, const void* vec, const void* wa, const void* wb, void* h_out,
+                                    float* out, int B, int d, int N, int I, int k, oea_dtype dt, Grouping g,
+                                    hipStream_t s) {
+  if (dt != OEA_BF16 || N > 128) return hipErrorNotSupported;
+  const bool shape30 = d == 2048 && I == 768, shape235 = d == 4096 && I == 1536;
+  if (!shape30 && !shape235) return hipErrorNotSupported;
+  if (g_fused_cus < 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hipErrorUnknown;
+    g_fused_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 0;
+  }
+  const int grid = g_fused_cus;
+  if (grid < 1) return hipErrorNotSupported;
+  // a workgroup's cost share must not span more than kMaxSeg experts (see try_launch_fused)
+  const int beta_hi = kBetaUp > kBetaDown ? kBetaUp : kBetaDown, beta_lo = kBetaUp < kBetaDown ? kBetaUp : kBetaDown;
+  const long long share_num = (long long)kRowCost * N + (long long)beta_hi * B * k;
+  if (int(share_num / ((long long)grid * (kRowCost + beta_lo))) + 2 > kMaxSeg) return hipErrorNotSupported;
+  StageParams p{};
+  p.wa = wa;
+  p.wb = wb;
+  p.vec = vec;
+  p.h_out = h_out;
+  p.out = out;
+  p.g = g;
+  p.rows = stage == 0 ? I : d;
+  p.L = stage == 0 ? d : I;
+  p.N = N;
+  p.B = B;
+  p.pairs_max = B * k;
+  if (shape30)
+    return stage == 0 ? launch_stage_one<uint16_t, 0, 32, 8, 1>(p, s) : launch_stage_one<uint16_t, 1, 16, 6, 2>(p, s);
+  return stage == 0 ? launch_stage_one<uint16_t, 0, 64, 8, 1>(p, s) : launch_stage_one<uint16_t, 1, 32, 6, 2>(p, s);
 }
 
 }  // namespace oea

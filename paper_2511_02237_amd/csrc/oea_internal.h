@@ -77,6 +77,11 @@ hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_g
                             float* logits, void* h, RouteOut ro, uint32_t* ctrl, int B, int d, int N, int I,
                             int k, int k0, oea_dtype dt, hipStream_t s);
 
+// one expert stage (0 gate/up, 1 down) with the fused kernel's stage code, for larger batches
+hipError_t try_launch_stage_kernels(int stage, const void* vec, const void* wa, const void* wb, void* h_out,
+                                    float* out, int B, int d, int N, int I, int k, oea_dtype dt, Grouping g,
+                                    hipStream_t s);
+
 size_t route_lds_bytes(int B, int N);
 void set_force_generic(bool on);
 

@@ -433,3 +433,35 @@ def test_route_batched_positions(torch, B_, oracle):
     torch.cuda.synchronize()
     us = e0.elapsed_time(e1) * 1e3 / 10
     say("oea_route_batched: %d positions of B=16, N=128 in %.1f us (%.1f M positions/s)" % (L, us, L / us))
+
+
+# ---- larger batches: the expert stages as separate kernels
+
+def test_stage_kernels_at_b16(torch, B_, oracle):
+    """Kernel path 3 runs the stage kernels also where the fused kernel would apply."""
+    L = W.make_layer("qwen3_30b", 77)
+    dev = {f: B_.to_device(getattr(L, f)) for f in ("x", "w_router", "w_gate", "w_up", "w_down")}
+    B_.set_kernel_path(3)
+    try:
+        for k0 in (1, 3, 8):
+            out, tap = run_layer_dev(torch, B_, L, dev, k0)
+            err, ref = check_layer(oracle, L, k0, out, tap, "stage kernels B=16 k0=%d" % k0)
+            say("stage kernels B=16 k0=%d T=%d err=%.2e" % (k0, ref["n_active"], err))
+    finally:
+        B_.set_kernel_path(0)
+
+
+def test_stage_kernels_many_tokens_per_expert(torch, B_, oracle):
+    """B=64 near-identical tokens: every active expert serves all of them, so a workgroup's pair list
+    exceeds its LDS share and is walked in pieces."""
+    L0 = W.make_layer("qwen3_30b", 78, B=64)
+    x = np.repeat(L0.x[:1], 64, axis=0).copy()
+    x[1::2] = L0.x[1:2]  # two distinct tokens, alternating
+    L = W.Layer(**{**L0.__dict__, "x": np.ascontiguousarray(x)})
+    dev = {f: B_.to_device(getattr(L, f)) for f in ("x", "w_router", "w_gate", "w_up", "w_down")}
+    for k0 in (2, 8):
+        out, tap = run_layer_dev(torch, B_, L, dev, k0)
+        err, ref = check_layer(oracle, L, k0, out, tap, "B=64 duplicated tokens k0=%d" % k0)
+        cnt = np.bincount(ref["expert_idx"][ref["expert_idx"] >= 0], minlength=L.N)
+        say("B=64 duplicated tokens k0=%d: T=%d, most pairs on one expert %d, err=%.2e" % (k0, ref["n_active"], cnt.max(), err))
+        assert cnt.max() >= 32
