@@ -28,6 +28,8 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const float* logit
     RowCarry<4 * NV> c;
     route_union_rows<4 * NV, kRouteThreads>(logits, token_mask, B, N, k0, o, lds, c);
     route_fill_rows<4 * NV, kRouteThreads>(B, N, k, k0, o, lds, c);
+  } else if (NV <= 2 && k <= 16) {
+    route_rows_any<4 * NV, kRouteThreads>(logits, token_mask, B, N, k, k0, o, lds);
   } else if (B <= kRouteThreads / 64) {
     route_block<NV, kRouteThreads, 1>(logits, token_mask, B, N, k, k0, o, lds);
   } else {
@@ -61,20 +63,33 @@ __global__ __launch_bounds__(kRouteThreads) void router_route_kernel(
     for (size_t i = lo + tid; i < hi; i += kRouteThreads) o4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
   }
 
+  // TB tokens at a time per wavefront: the router row chunk is loaded once for all of them and their
+  // loads and reductions overlap (one token at a time was bound by load latency)
+  constexpr int TB = 4;
   const WT* wr = w_router + (size_t)e * d;
-  for (int t = wave; t < B; t += (kRouteThreads / 64)) {
-    const WT* xr = x + (size_t)t * d;
-    double acc = 0.0;
+  for (int t0 = wave * TB; t0 < B; t0 += (kRouteThreads / 64) * TB) {
+    double acc[TB];
+#pragma unroll
+    for (int i = 0; i < TB; ++i) acc[i] = 0.0;
     for (int c = lane * EPL; c < d; c += 64 * EPL) {
-      uint4 a = *reinterpret_cast<const uint4*>(xr + c);
-      uint4 b = *reinterpret_cast<const uint4*>(wr + c);
-      acc = frag_dot_f64<WT>(a, b, acc);
+      const uint4 b = *reinterpret_cast<const uint4*>(wr + c);
+      uint4 a[TB];
+#pragma unroll
+      for (int i = 0; i < TB; ++i) {
+        const int t = t0 + i < B ? t0 + i : B - 1;
+        a[i] = *reinterpret_cast<const uint4*>(x + (size_t)t * d + c);
+      }
+#pragma unroll
+      for (int i = 0; i < TB; ++i) acc[i] = frag_dot_f64<WT>(a[i], b, acc[i]);
     }
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    for (int off = 32; off >= 1; off >>= 1)
+#pragma unroll
+      for (int i = 0; i < TB; ++i) acc[i] += __shfl_xor(acc[i], off, 64);
     if (lane == 0) {
-      if (bias) acc += double(bias[e]);
-      logits[(size_t)t * N + e] = float(acc);
+#pragma unroll
+      for (int i = 0; i < TB; ++i)
+        if (t0 + i < B) logits[(size_t)(t0 + i) * N + e] = float(acc[i] + (bias ? double(bias[e]) : 0.0));
     }
   }
 
@@ -95,9 +110,15 @@ __global__ __launch_bounds__(kRouteThreads) void router_route_kernel(
   const bool last = lds[0] != 0u;
   __syncthreads();
   if (!last) return;
-  if (general)
+  if (general) {
     route_block_general<NV, kRouteThreads>(logits, token_mask, B, N, k0, g, o, lds);
-  else if (B <= kRouteThreads / 64)
+  } else if (NV <= 2 && k <= 16 && B <= 4 * (kRouteThreads / 64)) {
+    RowCarry<4 * NV> c;  // few experts: one DPP row of 16 lanes per token
+    route_union_rows<4 * NV, kRouteThreads>(logits, token_mask, B, N, k0, o, lds, c);
+    route_fill_rows<4 * NV, kRouteThreads>(B, N, k, k0, o, lds, c);
+  } else if (NV <= 2 && k <= 16) {
+    route_rows_any<4 * NV, kRouteThreads>(logits, token_mask, B, N, k, k0, o, lds);
+  } else if (B <= kRouteThreads / 64)
     route_block<NV, kRouteThreads, 1>(logits, token_mask, B, N, k, k0, o, lds);
   else
     route_block<NV, kRouteThreads, 0>(logits, token_mask, B, N, k, k0, o, lds);

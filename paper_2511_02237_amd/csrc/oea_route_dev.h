@@ -495,6 +495,66 @@ __device__ void route_block(const float* __restrict__ logits, const uint8_t* __r
   route_fill<NV, NT, TPW>(logits, token_mask, B, N, k, k0, o, lds, c);
 }
 
+// Row-per-token routing for any B: the tokens are taken in groups of 4*NT/64 (four per wavefront).
+// Nothing is carried between the phases; Phase 2 is the closed form on its own (the k best members
+// of U, which contain the baseline).  N <= 16*NK, k <= 16.
+template <int NK, int NT>
+__device__ void route_rows_any(const float* __restrict__ logits, const uint8_t* __restrict__ token_mask, int B,
+                               int N, int k, int k0, RouteOut o, uint32_t* lds) {
+  constexpr int GROUP = 4 * (NT / 64);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 15, row = lane >> 4;
+  const int NWB = (B + 31) >> 5;
+  uint32_t* U = lds;
+  uint32_t* colmask = lds + 64;
+
+  for (int i = tid; i < int(route_lds_words(B, N)); i += NT) lds[i] = 0;
+  __syncthreads();
+  for (int t0 = 0; t0 < B; t0 += GROUP) {  // ---- Phase 1: baselines and their union
+    const int t = t0 + wave * 4 + row;
+    const bool live = t < B && !(token_mask && token_mask[t] == 0);
+    RowCarry<NK> c;
+    c.n = 0;
+    c.sel_id = c.sel_key = c.top_key = 0;
+#pragma unroll
+    for (int j = 0; j < NK; ++j) {
+      const int e = li + 16 * j;
+      c.key[j] = (live && e < N) ? make_key(logits[(size_t)(live ? t : 0) * N + e]) : 0;
+    }
+    for (int r = 0; r < k0; ++r) row_pick<NK>(c, li, r);
+    if (li < c.n) atomicOr(&U[c.sel_id >> 5], 1u << (c.sel_id & 31));
+  }
+  __syncthreads();
+  route_active<NT>(N, o, lds);
+  for (int t0 = 0; t0 < B; t0 += GROUP) {  // ---- Phase 2 in closed form, weights
+    const int t = t0 + wave * 4 + row;
+    const bool have = t < B;
+    const bool live = have && !(token_mask && token_mask[t] == 0);
+    RowCarry<NK> c;
+    c.n = 0;
+    c.sel_id = c.sel_key = c.top_key = 0;
+#pragma unroll
+    for (int j = 0; j < NK; ++j) {
+      const int e = li + 16 * j;
+      const bool cand = live && e < N && ((U[e >> 5] >> (e & 31)) & 1u);
+      c.key[j] = cand ? make_key(logits[(size_t)(live ? t : 0) * N + e]) : 0;
+    }
+    for (int r = 0; r < k; ++r) row_pick<NK>(c, li, r);
+    const float w = li < c.n ? expf(from_orderable(c.sel_key) - from_orderable(c.top_key)) : 0.f;
+    const float z = row_sum_f32(w);
+    if (have) {
+      if (li < k) {
+        o.expert_idx[(size_t)t * k + li] = li < c.n ? int(c.sel_id) : -1;
+        o.gate_w[(size_t)t * k + li] = li < c.n ? w / z : 0.f;
+      }
+      if (li < c.n) atomicOr(&colmask[c.sel_id * NWB + (t >> 5)], 1u << (t & 31));
+      if (li == 0) o.n_sel[t] = c.n;
+    }
+  }
+  __syncthreads();
+  route_group<NT>(B, N, k, o, lds);
+}
+
 // ---------------------------------------------------------------------------------------------
 // General OEA (Algorithm 2 of the paper): the baseline of a token is cut by a top-p rule as well
 // (n_i = min(k0, t_i), t_i = least t whose t best experts hold softmax mass >= p), piggybacking
