@@ -39,6 +39,8 @@ namespace {
 constexpr size_t kFusedLdsMax = 156 * 1024;
 #define OEA_MAX_FUSED_N 128  // experts the fused kernel handles (completion words in the control area)
 constexpr int kFusedStage = 8;  // staging loads kept in flight per thread
+constexpr int kBalBase = 1024 + 2 * OEA_MAX_FUSED_N * 32;  // ctrl word of the speed-weight state: w[2][256], rate[256]
+constexpr int kBalMaxWg = 256;                             // workgroups it covers
 
 struct FusedParams {
   const void* x;
@@ -63,7 +65,7 @@ struct FusedParams {
 // words of LDS in front of the vector area (after the 16-byte dump slot)
 __host__ __device__ inline size_t fused_meta_words(int B, int N, int k) {
   const size_t P = (size_t)B * k;
-  size_t w = route_lds_words(B, N) + 4 * P + (size_t)B + (size_t)N + 4 + (size_t)N + 4 + (size_t)B * N;
+  size_t w = route_lds_words(B, N) + 4 * P + (size_t)B + (size_t)N + 4 + (size_t)N + 4 + (size_t)B * N + kBalMaxWg + 4;
   return (w + 3) & ~size_t(3);
 }
 
@@ -161,17 +163,26 @@ constexpr int kRowCost = 64;
 constexpr int kBetaUp = OEA_BETA_UP;      // per pair, gate/up stage
 constexpr int kBetaDown = OEA_BETA_DOWN;  // per pair, down stage (also makes up for what is left of the gate/up skew)
 
+// ---- speed weights of the workgroups.
+// Workgroups do not stream equally fast (on the measured device the odd-numbered XCDs ran 2-4 %
+// behind the even ones, every call), and the layer ends with the slowest.  The workspace keeps a
+// weight per workgroup, an exponential average of its measured share-per-time; the cost range is
+// cut in proportion to the weights.  Call n reads buffer n%2 and the rates of call n-1 and writes
+// buffer (n+1)%2 (workgroup 0 only), so every workgroup of a call derives the same boundaries.
+
 // First row of workgroup b (b in [0,G]) in the concatenated numbering.  Called by whole wavefronts
 // (every lane tests two positions of the active list, T <= 128); the result is wave-uniform and the
 // same in every workgroup.
-__device__ __forceinline__ int wg_first_row(const int* l_off, int T, int rows, int beta, int b, int G, int lane) {
+__device__ __forceinline__ int wg_first_row(const int* l_off, int T, int rows, int beta, int b, int G, int lane,
+                                            const float* l_frac = nullptr) {
   if (b <= 0 || T <= 0) return 0;
   if (b >= G) return T * rows;
   // All quantities are integers below 2^40, exact in double; the divisions go through double because
   // 64-bit integer division is a long instruction sequence on this GPU.  Every workgroup evaluates
   // the same expression for boundary b, so neighbours agree on it.
   const double total = double(kRowCost) * T + double(beta) * l_off[T];  // in units of one row
-  const double x = floor(total * rows * b / G);
+  // l_frac[b]: share of the total cost given to the workgroups before b (speed-weighted); else equal shares
+  const double x = l_frac ? floor(total * rows * double(l_frac[b])) : floor(total * rows * b / G);
   const int a0 = lane, a1 = lane + 64;
   const double p0 = double(rows) * (double(kRowCost) * a0 + double(beta) * l_off[a0 < T ? a0 : T]);
   const double p1 = double(rows) * (double(kRowCost) * a1 + double(beta) * l_off[a1 < T ? a1 : T]);
@@ -182,6 +193,61 @@ __device__ __forceinline__ int wg_first_row(const int* l_off, int T, int rows, i
   double r = floor((x - double(rows) * (double(kRowCost) * lo + double(beta) * off_lo)) / w);
   r = r < 0 ? 0 : (r > rows ? rows : r);
   return uniform(lo * rows + int(r));
+}
+
+// Executed by ONE wavefront: new weights from the state and the rates of the previous call, their
+// cumulative shares -> l_frac[0..G] (l_frac[0] = 0, l_frac[G] = 1).  write_back: store the new state.
+__device__ __forceinline__ void balance_shares(uint32_t* ctrl, uint32_t parity, int G, bool write_back, float* l_frac,
+                                               int lane) {
+  float* const st = reinterpret_cast<float*>(ctrl + kBalBase);
+  const float* const w_old = st + (parity & 1u) * kBalMaxWg;
+  float* const w_new = st + ((parity & 1u) ^ 1u) * kBalMaxWg;
+  const float* const rate = st + 2 * kBalMaxWg;
+  float w[4], r[4];
+  float sum_r = 0.f, n_r = 0.f;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int b = lane * 4 + j;
+    w[j] = b < G ? __hip_atomic_load(w_old + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
+    r[j] = b < G ? __hip_atomic_load(rate + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
+    if (!(w[j] > 0.5f && w[j] < 2.f)) w[j] = 1.f;  // fresh (zeroed) or damaged state
+    if (!(r[j] > 0.f && r[j] < 1e30f)) r[j] = 0.f;  // no measurement
+    sum_r += r[j];
+    n_r += r[j] > 0.f ? 1.f : 0.f;
+  }
+  sum_r = wave_sum_f32(sum_r);
+  n_r = wave_sum_f32(n_r);
+  const float mean = n_r > 0.f ? sum_r / n_r : 1.f;
+  float local = 0.f;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int b = lane * 4 + j;
+    if (r[j] > 0.f) {
+      float rel = r[j] / mean;  // this workgroup's speed relative to the average of the last call
+      rel = rel < 0.8f ? 0.8f : (rel > 1.25f ? 1.25f : rel);
+      // the measured speed was obtained WITH the old weight's share, so it estimates the speed itself
+      w[j] = 0.75f * w[j] + 0.25f * rel;
+      w[j] = w[j] < 0.7f ? 0.7f : (w[j] > 1.4f ? 1.4f : w[j]);
+    }
+    if (b >= G) w[j] = 0.f;
+    if (write_back && b < G) __hip_atomic_store(w_new + b, w[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    local += w[j];
+  }
+  float incl = local;  // inclusive scan of the lanes' sums
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const float v = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += v;
+  }
+  const float total = __shfl(incl, 63, 64);
+  float run = incl - local;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int b = lane * 4 + j;
+    if (b < G) l_frac[b] = run / total;
+    run += w[j];
+  }
+  if (lane == 0) l_frac[G] = 1.f;
 }
 
 // One mat-vec stage of the fused kernel.  Same tile loop as expert_stream_kernel; the routing
@@ -361,7 +427,8 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   int* const l_tok = l_off + N + 4;
   float* const l_gw = reinterpret_cast<float*>(l_tok + P);
   float* const l_logits = l_gw + P;  // [B,N]
-  uint4* const l_vec = lds4 + 1 + fused_meta_words(B, N, k) / 4;  // after l_logits
+  float* const l_frac = l_logits + B * N;  // [G+1] cumulative cost shares of the workgroups
+  uint4* const l_vec = lds4 + 1 + fused_meta_words(B, N, k) / 4;
 
 #ifdef OEA_TIMELINE
   if (threadIdx.x == 0 && blockIdx.x == 0) g_tl_ctrl = p.ctrl;
@@ -374,7 +441,7 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
 #endif
   OEA_TL(p.ctrl, 0);
   uint32_t gen0 = 0;  // thread 0: barrier generation at the start of this call
-  if (tid == 0) gen0 = grid_generation(p.ctrl);
+  if (tid == 0 || tid == 64) gen0 = grid_generation(p.ctrl);  // thread 64: parity of the call for the speed weights
   // ---- phase R1.  x of the batch -> LDS: loads first, written after the logits
   const int d16 = d / EPL;
   const int n16_x = B * d16;
@@ -447,6 +514,9 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
 
   OEA_TL(p.ctrl, 1);
   grid_arrive(p.ctrl, gen0 + 1);  // logits and cleared out words are in memory
+  const bool balanced = G <= kBalMaxWg;
+  if (balanced && wave == 1)  // while thread 0 waits at the barrier
+    balance_shares(p.ctrl, uint32_t(__builtin_amdgcn_readfirstlane(int(gen0))), G, wg == 0, l_frac, lane);
   grid_wait(p.ctrl, gen0 + 1, p.spin_limit);
   OEA_TL(p.ctrl, 2);
 
@@ -475,8 +545,12 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   }
   int T = uniform(l_nact[0]);
   T = T < 0 ? 0 : (T > N ? N : T);
-  const int RA0 = wg_first_row(l_off, T, I, kBetaUp, wg, G, lane), RA1 = wg_first_row(l_off, T, I, kBetaUp, wg + 1, G, lane);
-  const int RB0 = wg_first_row(l_off, T, d, kBetaDown, wg, G, lane), RB1 = wg_first_row(l_off, T, d, kBetaDown, wg + 1, G, lane);
+  const float* const frac = balanced ? l_frac : nullptr;
+  const int RA0 = wg_first_row(l_off, T, I, kBetaUp, wg, G, lane, frac);
+  const int RA1 = wg_first_row(l_off, T, I, kBetaUp, wg + 1, G, lane, frac);
+  const int RB0 = wg_first_row(l_off, T, d, kBetaDown, wg, G, lane, frac);
+  const int RB1 = wg_first_row(l_off, T, d, kBetaDown, wg + 1, G, lane, frac);
+  const unsigned long long tA0 = wall_clock64();
   OEA_TL(p.ctrl, 3);
 
   // ---- phase A: gate/up
@@ -488,6 +562,7 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
                                     , reinterpret_cast<unsigned long long*>(static_cast<char*>(p.h) + (size_t)P * I * 2) + 2048
 #endif
                                     );
+  const unsigned long long tA1 = wall_clock64();
   signal_hidden_done(p.ctrl, RA0, RA1, I);
 #ifdef OEA_TIMELINE
   if (threadIdx.x == 0) {
@@ -501,6 +576,7 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   const int I16 = I / EPL;
   const uint32_t spin_limit = p.spin_limit;
   const int cap_vec = p.cap_vec;
+  unsigned long long tB0 = 0;
   fused_stage<WT, 1, LPR1, NCH1, 2>(
       static_cast<const WT*>(p.w_down), static_cast<const WT*>(nullptr), static_cast<WT*>(nullptr), p.out, d, I, RB0,
       RB1, N, P, p.cap_vec, l_active, l_off, l_tok, l_gw, l_vec,
@@ -546,11 +622,20 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
         }
         __syncthreads();
         OEA_TL(ctrl, 7);
+        tB0 = wall_clock64();
       }
 #ifdef OEA_TIMELINE
       , reinterpret_cast<unsigned long long*>(static_cast<char*>(p.h) + (size_t)P * I * 2) + 4096
 #endif
       );
+  if (balanced && tid == 0) {  // this workgroup's speed in this call: cost share per clock tick of streaming
+    const unsigned long long tB1 = wall_clock64();
+    const float ticks = float((tA1 - tA0) + (tB1 - tB0));
+    const float share = l_frac[wg + 1] - l_frac[wg];
+    const bool measured = RA1 - RA0 >= 16 && RB1 - RB0 >= 64 && tB0 != 0 && ticks > 100.f && share > 0.f;
+    __hip_atomic_store(reinterpret_cast<float*>(ctrl + kBalBase) + 2 * kBalMaxWg + wg, measured ? share / ticks : 0.f,
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
   OEA_TL(p.ctrl, 8);
 #ifdef OEA_TIMELINE
   if (threadIdx.x == 0) {  // per-workgroup stamps in the unused upper half of the bf16 h buffer
