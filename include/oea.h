@@ -51,7 +51,10 @@ size_t oea_workspace_bytes(int B, int d, int N, int I, int k);
 /*
  * Prepare a workspace: enqueues a fill kernel that zeroes its control words.  Call once after
  * allocating (or re-using for something else) a workspace, before the first moe_decode on it.
- * Each moe_decode leaves the control words zero again, so one call serves any number of layers.
+ * Each moe_decode leaves the words it synchronises through zero again, so one call serves any
+ * number of layers.  The workspace also carries a small load-balancing state from call to call (a
+ * speed estimate per workgroup that steers how the weight rows are shared out); it changes
+ * timing only, and the order of the floating-point additions into `out`.
  */
 int oea_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 
