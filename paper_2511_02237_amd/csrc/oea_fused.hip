@@ -65,7 +65,7 @@ struct FusedParams {
 // words of LDS in front of the vector area (after the 16-byte dump slot)
 __host__ __device__ inline size_t fused_meta_words(int B, int N, int k) {
   const size_t P = (size_t)B * k;
-  size_t w = route_lds_words(B, N) + 4 * P + (size_t)B + (size_t)N + 4 + (size_t)N + 4 + (size_t)B * N + kBalMaxWg + 4;
+  size_t w = route_lds_words(B, N) + 4 * P + (size_t)B + (size_t)N + 4 + (size_t)N + 4 + kBalMaxWg + 4;
   return (w + 3) & ~size_t(3);
 }
 
@@ -426,8 +426,7 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   int* const l_off = l_nact + 4;
   int* const l_tok = l_off + N + 4;
   float* const l_gw = reinterpret_cast<float*>(l_tok + P);
-  float* const l_logits = l_gw + P;  // [B,N]
-  float* const l_frac = l_logits + B * N;  // [G+1] cumulative cost shares of the workgroups
+  float* const l_frac = l_gw + P;  // [G+1] cumulative cost shares of the workgroups
   uint4* const l_vec = lds4 + 1 + fused_meta_words(B, N, k) / 4;
 
 #ifdef OEA_TIMELINE
@@ -520,17 +519,15 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   grid_wait(p.ctrl, gen0 + 1, p.spin_limit);
   OEA_TL(p.ctrl, 2);
 
-  // ---- phase R2: routing, replicated per workgroup, result in LDS
-  for (int i = tid; i < B * N; i += kFfnThreads)  // device-coherent loads: written by other workgroups
-    l_logits[i] = __hip_atomic_load(p.logits + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  if (tid == 0) l_nact[1] = l_nact[2] = 0;  // tile counters of the two stages
-  __syncthreads();
+  // ---- phase R2: routing, replicated per workgroup, result in LDS.  Every row of 16 lanes reads
+  // its token's logits straight from memory (device-coherent loads: written by other workgroups).
+  if (tid == 0) l_nact[1] = l_nact[2] = 0;  // tile counters of the two stages (a barrier follows in the routing)
   OEA_TL(p.ctrl, 9);
   const RouteOut lo{l_idx, l_gatew, l_nsel, l_active, l_nact, l_off, l_tok, l_gw};
   uint32_t* const ctrl = p.ctrl;
   {
     RowCarry<4 * NV> carry;  // one DPP row of 16 lanes per token, 4 * NV keys per lane
-    route_union_rows<4 * NV, kFfnThreads>(l_logits, p.token_mask, B, N, p.k0, lo, l_route, carry);
+    route_union_rows<4 * NV, kFfnThreads, true>(p.logits, p.token_mask, B, N, p.k0, lo, l_route, carry);
     route_fill_rows<4 * NV, kFfnThreads>(B, N, k, p.k0, lo, l_route, carry);
   }
   __syncthreads();

@@ -93,6 +93,23 @@ __host__ __device__ inline size_t route_lds_words(int B, int N) {
   return 64 + (size_t)N * ((B + 31) / 32) + (size_t)N;
 }
 
+// inclusive prefix sum over the 64 lanes: shifts inside each row of 16 lanes by DPP (zero shifted in),
+// then the three row totals are added through scalar registers
+template <int CTRL>
+__device__ __forceinline__ int dpp_shr_i32(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true);
+}
+__device__ __forceinline__ int wave_incl_scan_i32(int v, int lane) {
+  v += dpp_shr_i32<0x111>(v);  // row_shr:1
+  v += dpp_shr_i32<0x112>(v);  // row_shr:2
+  v += dpp_shr_i32<0x114>(v);  // row_shr:4
+  v += dpp_shr_i32<0x118>(v);  // row_shr:8
+  const int r0 = __builtin_amdgcn_readlane(v, 15), r1 = __builtin_amdgcn_readlane(v, 31);
+  const int r2 = __builtin_amdgcn_readlane(v, 47);
+  const int row = lane >> 4;
+  return v + (row >= 1 ? r0 : 0) + (row >= 2 ? r1 : 0) + (row >= 3 ? r2 : 0);
+}
+
 // Tail of the first half: the members of the union bit mask U (lds[0..15]) in ascending order ->
 // o.active_list, their number -> *o.n_active.  Called by all NT threads after a barrier that
 // completes U; the results are complete after the caller's next barrier.
@@ -140,12 +157,7 @@ __device__ __forceinline__ void route_group(int B, int N, int k, RouteOut o, uin
   int cnt = 0;
   if (in_u)
     for (int w = 0; w < NWB; ++w) cnt += __popc(colmask[e * NWB + w]);
-  int incl = cnt;  // inclusive scan of cnt inside the wave
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    int v = __shfl_up(incl, off, 64);
-    if (lane >= off) incl += v;
-  }
+  const int incl = wave_incl_scan_i32(cnt, lane);  // inclusive scan of cnt inside the wave
   if (lane == 63) scan[16 + wave] = uint32_t(incl);
   if (lane == 0) scan[32 + wave] = uint32_t(__popcll(ballot));
   __syncthreads();
@@ -420,7 +432,9 @@ __device__ __forceinline__ void row_pick(RowCarry<NK>& c, int li, int rank) {
   c.n += valid ? 1 : 0;
 }
 
-template <int NK, int NT>
+// COHERENT: the logits were written by other workgroups of the same launch (device-coherent stores);
+// they are read with device-coherent loads instead of plain ones.
+template <int NK, int NT, bool COHERENT = false>
 __device__ __forceinline__ void route_union_rows(const float* __restrict__ logits,
                                                  const uint8_t* __restrict__ token_mask, int B, int N, int k0,
                                                  RouteOut o, uint32_t* lds, RowCarry<NK>& c) {
@@ -439,11 +453,15 @@ __device__ __forceinline__ void route_union_rows(const float* __restrict__ logit
   c.sel_id = 0;
   c.sel_key = 0;
   c.top_key = 0;
+  float lg[NK];
 #pragma unroll
-  for (int j = 0; j < NK; ++j) {
+  for (int j = 0; j < NK; ++j) {  // unconditional loads (clamped address): all in flight together
     const int e = li + 16 * j;
-    c.key[j] = (live && e < N) ? make_key(logits[(size_t)(live ? t : 0) * N + e]) : 0;
+    const float* src = logits + (size_t)(live ? t : 0) * N + (e < N ? e : N - 1);
+    lg[j] = COHERENT ? __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *src;
   }
+#pragma unroll
+  for (int j = 0; j < NK; ++j) c.key[j] = (live && li + 16 * j < N) ? make_key(lg[j]) : 0;
   __syncthreads();  // U is cleared
   OEA_ROUTE_TL(10);
   // ---- Phase 1 of Algorithm 1: S_i^base = the k0 best experts
