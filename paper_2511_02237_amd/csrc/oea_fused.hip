@@ -2,18 +2,21 @@
 //
 //   phase R1  router GEMV, spread over all workgroups (fp64 accumulation, one dot product per
 //             wavefront); x of the batch is staged into LDS meanwhile; `out` is cleared
-//   -- grid barrier --
+//   -- grid barrier (two-level arrival counters, no cache maintenance) --
 //   phase R2  OEA routing (Algorithm 1), computed redundantly by EVERY workgroup from the logits
-//             into its own LDS: no second barrier, no routing metadata read back from memory
-//   phase A   gate/up mat-vec stage over the active experts (streaming, double-buffered tiles)
-//             the first down-stage weight tiles are requested BEFORE the barrier, so HBM keeps
-//             streaming while the workgroups synchronise
-//   -- grid barrier --  (the hidden vectors h of all experts must be complete)
-//   phase B   down mat-vec stage, accumulated into `out` with the gate weights (Eq. 1)
+//             into its own LDS: no second barrier, no routing metadata read back from memory;
+//             then the cost-weighted cut of both stages' rows over the workgroups
+//   phase A   gate/up mat-vec stage over the active experts: the wavefronts take tiles from a
+//             counter in LDS, stream them double-buffered, collect the hidden units in LDS and
+//             write them out at the end; then the workgroup adds its rows to the completion
+//             counters of its experts
+//   phase B   down mat-vec stage: first tiles requested, then the workgroup waits (bounded) for the
+//             completion flags of ITS experts only, stages their hidden vectors and streams;
+//             results are added into `out` with the gate weights at the end (Eq. 1)
 //
 // Compared with three back-to-back kernels this removes two dispatch gaps with their pipeline
 // drain/fill and every dependent metadata load.  All 256 workgroups must be resident at once: the
-// launcher checks that a workgroup fits on every CU and the barrier spins for a bounded time only.
+// launcher checks that a workgroup fits on every CU and every wait spins for a bounded time only.
 #include "oea_ffn_dev.h"
 #ifdef OEA_TIMELINE
 namespace oea {
