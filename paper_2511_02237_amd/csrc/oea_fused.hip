@@ -60,7 +60,9 @@ struct FusedParams {
   uint32_t* ctrl;  // [3] error flag, [32] and [256 + 32 i] barrier arrivals, [64] barrier generation (separate
                    // 128-byte lines), from [1024] the per-expert completion counters and flags (done_count, done_flag)
   int B, d, N, I, k, k0;
-  int cap_vec;     // most (expert, token) pairs one workgroup can meet in one stage
+  int cap_vec;     // most (expert, token) pairs one workgroup can meet in one stage (large batches: vectors per
+                   // piece in the gate/up stage)
+  int cap_vec1;    // large batches: vectors per piece in the down stage
   int ecap0, ecap1;  // floats of LDS result buffer per wavefront, gate/up and down stage (0 = none)
   uint32_t spin_limit;
 };
@@ -645,6 +647,232 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
 #endif
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same single-kernel layer for larger batches (32 < B <= 128), where x of the whole batch no
+// longer fits in LDS: a workgroup stages only the vectors of ITS experts' pairs (gathered rows of x
+// for the gate/up stage, rows of h for the down stage) and, should they exceed its LDS share, walks
+// them in pieces (streaming its weight rows once per piece).  The routing takes the tokens in groups
+// of 32 (four per wavefront).
+template <typename WT, int LPR0, int NCH0, int LPR1, int NCH1, int NV>
+__global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedParams p) {
+  extern __shared__ uint4 lds4[];
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  constexpr int EPL = 16 / int(sizeof(WT));
+  const int B = p.B, d = p.d, N = p.N, I = p.I, k = p.k;
+  const int P = B * k;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = uniform(tid >> 6);
+  const int G = gridDim.x, wg = blockIdx.x;
+  const WT* const x = static_cast<const WT*>(p.x);
+  uint32_t* const ctrl = p.ctrl;
+
+  uint32_t* const l_route = reinterpret_cast<uint32_t*>(lds4 + 1);
+  int* const l_idx = reinterpret_cast<int*>(l_route + route_lds_words(B, N));
+  float* const l_gatew = reinterpret_cast<float*>(l_idx + P);
+  int* const l_nsel = reinterpret_cast<int*>(l_gatew + P);
+  int* const l_active = l_nsel + B;
+  int* const l_nact = l_active + N;
+  int* const l_off = l_nact + 4;
+  int* const l_tok = l_off + N + 4;
+  float* const l_gw = reinterpret_cast<float*>(l_tok + P);
+  float* const l_frac = l_gw + P;
+  uint4* const l_vec = lds4 + 1 + fused_meta_words(B, N, k) / 4;
+  const int d16 = d / EPL, I16 = I / EPL;
+
+  uint32_t gen0 = 0;
+  if (tid == 0 || tid == 64) gen0 = grid_generation(ctrl);
+  {  // clear this workgroup's slice of out[B,d]
+    const int total = B * d;
+    const int per = (total + G - 1) / G;
+    const int lo = per * wg, hi = lo + per < total ? lo + per : total;
+    for (int i = lo + tid; i < hi; i += kFfnThreads)
+      __hip_atomic_store(p.out + i, 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  if (wg == 0 && tid < N) {
+    __hip_atomic_store(done_count(ctrl, tid), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(done_flag(ctrl, tid), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  {  // router logits: a wavefront takes one expert and four tokens at a time (the router row chunk is
+     // loaded once for the four, their loads and reductions overlap)
+    constexpr int TB = 4;
+    const WT* const wr = static_cast<const WT*>(p.w_router);
+    const int nblk = (B + TB - 1) / TB;
+    for (int u = wg * kFfnWaves + wave; u < N * nblk; u += G * kFfnWaves) {
+      const int e = u / nblk, t0 = (u - e * nblk) * TB;
+      const WT* wre = wr + (size_t)e * d;
+      double acc[TB];
+#pragma unroll
+      for (int i = 0; i < TB; ++i) acc[i] = 0.0;
+      for (int c = lane * EPL; c < d; c += 64 * EPL) {
+        const uint4 b = *reinterpret_cast<const uint4*>(wre + c);
+        uint4 a[TB];
+#pragma unroll
+        for (int i = 0; i < TB; ++i) a[i] = *reinterpret_cast<const uint4*>(x + (size_t)(t0 + i < B ? t0 + i : B - 1) * d + c);
+#pragma unroll
+        for (int i = 0; i < TB; ++i) acc[i] = frag_dot_f64<WT>(a[i], b, acc[i]);
+      }
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1)
+#pragma unroll
+        for (int i = 0; i < TB; ++i) acc[i] += __shfl_xor(acc[i], off, 64);
+      if (lane == 0) {
+#pragma unroll
+        for (int i = 0; i < TB; ++i)
+          if (t0 + i < B)
+            __hip_atomic_store(p.logits + (size_t)(t0 + i) * N + e, float(acc[i] + (p.bias ? double(p.bias[e]) : 0.0)),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+  }
+  grid_arrive(ctrl, gen0 + 1);
+  const bool balanced = G <= kBalMaxWg;
+  if (balanced && wave == 1)
+    balance_shares(ctrl, uint32_t(__builtin_amdgcn_readfirstlane(int(gen0))), G, wg == 0, l_frac, lane);
+  grid_wait(ctrl, gen0 + 1, p.spin_limit);
+
+  if (tid == 0) l_nact[1] = l_nact[2] = 0;
+  const RouteOut lo{l_idx, l_gatew, l_nsel, l_active, l_nact, l_off, l_tok, l_gw};
+  route_rows_any<4 * NV, kFfnThreads, true>(p.logits, p.token_mask, B, N, k, p.k0, lo, l_route);
+  __syncthreads();
+  if (wg == 0) {  // publish the routing result
+    for (int i = tid; i < P; i += kFfnThreads) {
+      p.ro.expert_idx[i] = l_idx[i];
+      p.ro.gate_w[i] = l_gatew[i];
+    }
+    for (int i = tid; i < B; i += kFfnThreads) p.ro.n_sel[i] = l_nsel[i];
+    for (int i = tid; i < N; i += kFfnThreads) p.ro.active_list[i] = l_active[i];
+    if (tid == 0) *p.ro.n_active = l_nact[0];
+  }
+  int T = uniform(l_nact[0]);
+  T = T < 0 ? 0 : (T > N ? N : T);
+  const float* const frac = balanced ? l_frac : nullptr;
+  const int RA0 = wg_first_row(l_off, T, I, kBetaUp, wg, G, lane, frac);
+  const int RA1 = wg_first_row(l_off, T, I, kBetaUp, wg + 1, G, lane, frac);
+  const int RB0 = wg_first_row(l_off, T, d, kBetaDown, wg, G, lane, frac);
+  const int RB1 = wg_first_row(l_off, T, d, kBetaDown, wg + 1, G, lane, frac);
+
+  // pairs of the experts a row range touches: [first pair, count)
+  auto pairs_of = [&](int R0, int R1, int rows, int& off0, int& nvec) __attribute__((always_inline)) {
+    off0 = 0;
+    nvec = 0;
+    if (R0 >= R1) return;
+    const int a0 = R0 / rows, a1 = (R1 - 1) / rows;
+    off0 = uniform(l_off[a0]);
+    nvec = uniform(l_off[a1 + 1]) - off0;
+    if (off0 < 0 || nvec < 0 || off0 + nvec > P) nvec = 0;  // never true for a valid routing
+  };
+  const unsigned long long tA0 = wall_clock64();
+
+  // ---- phase A: gate/up, in pieces of at most cap0 pairs
+  {
+    int off0, nvec;
+    pairs_of(RA0, RA1, I, off0, nvec);
+    const int cap0 = p.cap_vec;
+    float* const ebuf = reinterpret_cast<float*>(l_vec + (size_t)cap0 * d16);
+    for (int c0 = 0; c0 == 0 || c0 < nvec; c0 += cap0) {
+      const int c1 = c0 + cap0 < nvec ? c0 + cap0 : nvec;
+      if (c0 > 0) {  // the previous piece is flushed; hand the tiles out again
+        __syncthreads();
+        if (tid == 0) l_nact[1] = 0;
+        __syncthreads();
+      }
+      fused_stage<WT, 0, LPR0, NCH0, 1, true>(
+          static_cast<const WT*>(p.w_gate), static_cast<const WT*>(p.w_up), static_cast<WT*>(p.h), p.out, I, d, RA0,
+          RA1, N, P, cap0, l_active, l_off, l_tok, l_gw, l_vec, ebuf, p.ecap0, reinterpret_cast<uint32_t*>(l_nact + 1),
+          [&](int, int) {  // runs once the first weight tiles are requested: x rows of the piece's pairs -> LDS
+            const u32x4* src = reinterpret_cast<const u32x4*>(x);
+            const int n16 = (c1 - c0) * d16;
+            for (int base = 0; base < n16; base += kFusedStage * kFfnThreads) {
+              u32x4 t4[kFusedStage];
+#pragma unroll
+              for (int j = 0; j < kFusedStage; ++j) {
+                int i16 = base + j * kFfnThreads + tid;
+                i16 = i16 < n16 ? i16 : n16 - 1;
+                const int v = i16 / d16, c = i16 - v * d16;
+                t4[j] = src[(size_t)l_tok[off0 + c0 + v] * d16 + c];
+              }
+#pragma unroll
+              for (int j = 0; j < kFusedStage; ++j) {
+                const int i16 = base + j * kFfnThreads + tid;
+                *reinterpret_cast<u32x4*>(i16 < n16 ? l_vec + i16 : lds4) = t4[j];
+              }
+            }
+            __syncthreads();
+          },
+          nullptr, c0, c1);
+    }
+  }
+  const unsigned long long tA1 = wall_clock64();
+  signal_hidden_done(ctrl, RA0, RA1, I);
+
+  // ---- phase B: down, in pieces of at most cap1 pairs
+  unsigned long long tB0 = 0;
+  {
+    int off0, nvec;
+    pairs_of(RB0, RB1, d, off0, nvec);
+    const int cap1 = p.cap_vec1;
+    float* const ebuf = reinterpret_cast<float*>(l_vec + (size_t)cap1 * I16);
+    const WT* const hsrc = static_cast<const WT*>(p.h);
+    const uint32_t spin_limit = p.spin_limit;
+    for (int c0 = 0; c0 == 0 || c0 < nvec; c0 += cap1) {
+      const int c1 = c0 + cap1 < nvec ? c0 + cap1 : nvec;
+      if (c0 > 0) {
+        __syncthreads();
+        if (tid == 0) l_nact[2] = 0;
+        __syncthreads();
+      }
+      fused_stage<WT, 1, LPR1, NCH1, 2, true>(
+          static_cast<const WT*>(p.w_down), static_cast<const WT*>(nullptr), static_cast<WT*>(nullptr), p.out, d, I,
+          RB0, RB1, N, P, cap1, l_active, l_off, l_tok, l_gw, l_vec, ebuf, p.ecap1,
+          reinterpret_cast<uint32_t*>(l_nact + 2),
+          [&](int a0, int nseg) {
+            if (c0 == 0) {  // wait, bounded, until the hidden vectors of this workgroup's experts are complete
+              if (tid == 0) {
+                uint32_t spins = 0;
+                for (int sgm = 0; sgm < nseg; ++sgm)
+                  while (__hip_atomic_load(done_flag(ctrl, a0 + sgm), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+                    __builtin_amdgcn_s_sleep(2);
+                    if (++spins > spin_limit) {
+                      atomicExch(ctrl + 3, 1u);
+                      break;
+                    }
+                  }
+              }
+              __syncthreads();
+            }
+            // h rows of the piece's pairs: written by other workgroups, device-coherent 16-byte loads
+            const int n16 = (c1 - c0) * I16;
+            __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<WT*>(hsrc + (size_t)(off0 + c0) * I), 0, n16 * 16, 0x00020000);
+            for (int base = 0; base < n16; base += kFusedStage * kFfnThreads) {
+              u32x4 t4[kFusedStage];
+#pragma unroll
+              for (int j = 0; j < kFusedStage; ++j) {
+                const int i16 = base + j * kFfnThreads + tid;
+                t4[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (i16 < n16 ? i16 : n16 - 1) * 16, 0, 1 | 16);
+              }
+#pragma unroll
+              for (int j = 0; j < kFusedStage; ++j) {
+                const int i16 = base + j * kFfnThreads + tid;
+                *reinterpret_cast<u32x4*>(i16 < n16 ? l_vec + i16 : lds4) = t4[j];
+              }
+            }
+            __syncthreads();
+            if (c0 == 0) tB0 = wall_clock64();
+          },
+          nullptr, c0, c1);
+    }
+  }
+  if (balanced && tid == 0) {
+    const unsigned long long tB1 = wall_clock64();
+    const float ticks = float((tA1 - tA0) + (tB1 - tB0));
+    const float share = l_frac[wg + 1] - l_frac[wg];
+    const bool measured = RA1 - RA0 >= 16 && RB1 - RB0 >= 64 && tB0 != 0 && ticks > 100.f && share > 0.f;
+    __hip_atomic_store(reinterpret_cast<float*>(ctrl + kBalBase) + 2 * kBalMaxWg + wg, measured ? share / ticks : 0.f,
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
 int g_fused_cus = -1;  // CUs of the device (0: query failed), -1 before the query
 
 // ---------------------------------------------------------------------------------------------
@@ -765,6 +993,24 @@ hipError_t launch_fused_one(const FusedParams& p, size_t lds_bytes, hipStream_t 
   return hipGetLastError();
 }
 
+template <typename WT, int LPR0, int NCH0, int LPR1, int NCH1, int NV>
+hipError_t launch_fused_gather_one(const FusedParams& p, size_t lds_bytes, hipStream_t s) {
+  auto kern = moe_fused_gather_kernel<WT, LPR0, NCH0, LPR1, NCH1, NV>;
+  static int checked = 0;  // 1 = usable, -1 = not
+  if (checked == 0) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLdsMax);
+    if (e != hipSuccess) return e;
+    int per_cu = 0;
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, kFfnThreads, kFusedLdsMax);
+    if (e != hipSuccess) return e;
+    checked = per_cu >= 1 ? 1 : -1;
+  }
+  if (checked < 0) return hipErrorNotSupported;
+  hipLaunchKernelGGL(kern, dim3(g_fused_cus), dim3(kFfnThreads), lds_bytes, s, p);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 // The fused kernel when the shape is one it is built for; hipErrorNotSupported otherwise.
@@ -772,7 +1018,7 @@ hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_g
                             const void* w_down, const float* bias, const uint8_t* token_mask, float* out,
                             float* logits, void* h, RouteOut ro, uint32_t* ctrl, int B, int d, int N, int I,
                             int k, int k0, oea_dtype dt, hipStream_t s) {
-  if (dt != OEA_BF16 || N > 128 || B > 32 || k > 16) return hipErrorNotSupported;
+  if (dt != OEA_BF16 || N > 128 || B > 128 || k > 16) return hipErrorNotSupported;
   const bool shape30 = d == 2048 && I == 768, shape235 = d == 4096 && I == 1536;
   if (!shape30 && !shape235) return hipErrorNotSupported;
   if (g_fused_cus < 0) {
@@ -788,21 +1034,41 @@ hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_g
   const long long share_num = (long long)kRowCost * N + (long long)beta_hi * B * k;
   const int nseg_max = int(share_num / ((long long)grid * (kRowCost + beta_lo))) + 2;
   if (nseg_max > kMaxSeg) return hipErrorNotSupported;
-  long long cap_vec = (long long)nseg_max * B;
-  if (cap_vec > (long long)B * k) cap_vec = (long long)B * k;
-  const size_t vec_x = (size_t)B * d * 2, vec_h = (size_t)cap_vec * I * 2;
   const size_t fixed = 16 + fused_meta_words(B, N, k) * 4;
-  if (fixed + (vec_x > vec_h ? vec_x : vec_h) > kFusedLdsMax) return hipErrorNotSupported;
-  // what is left of the LDS holds the wavefronts' result buffers (at most 2048 floats each)
-  auto result_cap = [&](size_t vec) {
-    size_t per_wave = (kFusedLdsMax - fixed - vec) / (kFfnWaves * sizeof(float));
-    per_wave = per_wave > 2048 ? 2048 : per_wave & ~size_t(3);
-    return per_wave >= 64 ? (int)per_wave : 0;
-  };
-  const int ecap0 = result_cap(vec_x), ecap1 = result_cap(vec_h);
-  const size_t need0 = vec_x + (size_t)ecap0 * kFfnWaves * sizeof(float);
-  const size_t need1 = vec_h + (size_t)ecap1 * kFfnWaves * sizeof(float);
-  size_t lds_bytes = fixed + (need0 > need1 ? need0 : need1);
+  const bool gather = B > 32;  // x of the whole batch does not fit beside the rest: stage per workgroup
+  long long cap_vec = (long long)nseg_max * B, cap_vec1 = 0;
+  if (cap_vec > (long long)B * k) cap_vec = (long long)B * k;
+  int ecap0 = 0, ecap1 = 0;
+  size_t lds_bytes = 0;
+  if (!gather) {
+    const size_t vec_x = (size_t)B * d * 2, vec_h = (size_t)cap_vec * I * 2;
+    if (fixed + (vec_x > vec_h ? vec_x : vec_h) > kFusedLdsMax) return hipErrorNotSupported;
+    // what is left of the LDS holds the wavefronts' result buffers (at most 2048 floats each)
+    auto result_cap = [&](size_t vec) {
+      size_t per_wave = (kFusedLdsMax - fixed - vec) / (kFfnWaves * sizeof(float));
+      per_wave = per_wave > 2048 ? 2048 : per_wave & ~size_t(3);
+      return per_wave >= 64 ? (int)per_wave : 0;
+    };
+    ecap0 = result_cap(vec_x);
+    ecap1 = result_cap(vec_h);
+    const size_t need0 = vec_x + (size_t)ecap0 * kFfnWaves * sizeof(float);
+    const size_t need1 = vec_h + (size_t)ecap1 * kFfnWaves * sizeof(float);
+    lds_bytes = fixed + (need0 > need1 ? need0 : need1);
+  } else {
+    // result buffers of 1024 (gate/up) and 2048 (down: more rows per workgroup, shorter vectors) floats
+    // per wavefront; the rest of the LDS holds the staged vectors of a piece
+    ecap0 = 1024;
+    ecap1 = 2048;
+    const size_t res0 = (size_t)ecap0 * kFfnWaves * sizeof(float), res1 = (size_t)ecap1 * kFfnWaves * sizeof(float);
+    if (fixed + res0 + 4 * (size_t)d * 2 > kFusedLdsMax || fixed + res1 + 4 * (size_t)I * 2 > kFusedLdsMax)
+      return hipErrorNotSupported;
+    const long long c0 = (long long)((kFusedLdsMax - fixed - res0) / ((size_t)d * 2));
+    const long long c1 = (long long)((kFusedLdsMax - fixed - res1) / ((size_t)I * 2));
+    cap_vec1 = c1 < cap_vec ? c1 : cap_vec;
+    cap_vec = c0 < cap_vec ? c0 : cap_vec;
+    const size_t need0 = (size_t)cap_vec * d * 2 + res0, need1 = (size_t)cap_vec1 * I * 2 + res1;
+    lds_bytes = fixed + (need0 > need1 ? need0 : need1);
+  }
   const size_t alone = 84 * 1024;  // more than half of a CU's LDS: exactly one workgroup per CU
   if (lds_bytes < alone) lds_bytes = alone;
 
@@ -826,9 +1092,14 @@ hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_g
   p.k = k;
   p.k0 = k0;
   p.cap_vec = (int)cap_vec;
+  p.cap_vec1 = (int)cap_vec1;
   p.ecap0 = ecap0;
   p.ecap1 = ecap1;
   p.spin_limit = 4u << 20;  // polls of >= 100 ns each: gives up after about a second
+  if (gather) {
+    if (shape30) return launch_fused_gather_one<uint16_t, 32, 8, 16, 6, 2>(p, lds_bytes, s);
+    return launch_fused_gather_one<uint16_t, 64, 8, 32, 6, 2>(p, lds_bytes, s);
+  }
   if (shape30) return launch_fused_one<uint16_t, 32, 8, 16, 6, 2>(p, lds_bytes, s);
   return launch_fused_one<uint16_t, 64, 8, 32, 6, 2>(p, lds_bytes, s);
 }

@@ -516,9 +516,13 @@ __device__ void route_block(const float* __restrict__ logits, const uint8_t* __r
 // Row-per-token routing for any B: the tokens are taken in groups of 4*NT/64 (four per wavefront).
 // Nothing is carried between the phases; Phase 2 is the closed form on its own (the k best members
 // of U, which contain the baseline).  N <= 16*NK, k <= 16.
-template <int NK, int NT>
+template <int NK, int NT, bool COHERENT = false>
 __device__ void route_rows_any(const float* __restrict__ logits, const uint8_t* __restrict__ token_mask, int B,
                                int N, int k, int k0, RouteOut o, uint32_t* lds) {
+  auto logit_at = [&](int t, int e) __attribute__((always_inline)) {  // COHERENT: see route_union_rows
+    const float* src = logits + (size_t)t * N + e;
+    return COHERENT ? __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *src;
+  };
   constexpr int GROUP = 4 * (NT / 64);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int li = lane & 15, row = lane >> 4;
@@ -537,7 +541,7 @@ __device__ void route_rows_any(const float* __restrict__ logits, const uint8_t* 
 #pragma unroll
     for (int j = 0; j < NK; ++j) {
       const int e = li + 16 * j;
-      c.key[j] = (live && e < N) ? make_key(logits[(size_t)(live ? t : 0) * N + e]) : 0;
+      c.key[j] = (live && e < N) ? make_key(logit_at(t, e)) : 0;
     }
     for (int r = 0; r < k0; ++r) row_pick<NK>(c, li, r);
     if (li < c.n) atomicOr(&U[c.sel_id >> 5], 1u << (c.sel_id & 31));
@@ -555,7 +559,7 @@ __device__ void route_rows_any(const float* __restrict__ logits, const uint8_t* 
     for (int j = 0; j < NK; ++j) {
       const int e = li + 16 * j;
       const bool cand = live && e < N && ((U[e >> 5] >> (e & 31)) & 1u);
-      c.key[j] = cand ? make_key(logits[(size_t)(live ? t : 0) * N + e]) : 0;
+      c.key[j] = cand ? make_key(logit_at(t, e)) : 0;
     }
     for (int r = 0; r < k; ++r) row_pick<NK>(c, li, r);
     const float w = li < c.n ? expf(from_orderable(c.sel_key) - from_orderable(c.top_key)) : 0.f;
