@@ -127,13 +127,13 @@ int oea_route_general(const float *router_logits, const uint8_t *token_mask, int
  *   workspace         device scratch of >= oea_workspace_bytes(B,d,N,I,k) bytes, 16-byte aligned,
  *                     prepared once by oea_workspace_init.  Two calls that share a workspace must
  *                     be ordered on the same stream.
- * For the Qwen3-30B-A3B and Qwen3-235B-A22B layer shapes (bf16, N <= 128, k <= 16, B <= 32) the
+ * For the Qwen3-30B-A3B and Qwen3-235B-A22B layer shapes (bf16, N <= 128, k <= 16, B <= 128) the
  * whole layer runs as ONE persistent kernel with one workgroup per compute unit, one grid-wide
  * barrier and per-expert completion flags; it expects the device to itself while it runs (a
  * workgroup that cannot be placed delays the others; every wait is bounded, after about a second
- * the call gives up and its output is undefined).  Larger batches of these shapes run as three
- * kernels (router + routing, gate/up stage, down stage) that share the fused kernel's stage code;
- * every other shape, and fp32 storage, runs as three kernels with generic expert kernels.
+ * the call gives up and its output is undefined).  Still larger batches of these shapes run as
+ * three kernels (router + routing, gate/up stage, down stage) that share the fused kernel's stage
+ * code; every other shape, and fp32 storage, runs as three kernels with generic expert kernels.
  * Arithmetic: router logits are accumulated in fp64 and rounded once to fp32; expert mat-vecs
  * multiply in the storage type and accumulate in fp32; with bf16 storage the hidden vector is
  * rounded to bf16 between the two mat-vecs (as a bf16 model does).
