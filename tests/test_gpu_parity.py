@@ -451,7 +451,7 @@ def test_stage_kernels_at_b16(torch, B_, oracle):
         B_.set_kernel_path(0)
 
 
-def test_stage_kernels_many_tokens_per_expert(torch, B_, oracle):
+def test_many_tokens_per_expert(torch, B_, oracle):
     """B=64 near-identical tokens: every active expert serves all of them, so a workgroup's pair list
     exceeds its LDS share and is walked in pieces."""
     L0 = W.make_layer("qwen3_30b", 78, B=64)
@@ -459,9 +459,15 @@ def test_stage_kernels_many_tokens_per_expert(torch, B_, oracle):
     x[1::2] = L0.x[1:2]  # two distinct tokens, alternating
     L = W.Layer(**{**L0.__dict__, "x": np.ascontiguousarray(x)})
     dev = {f: B_.to_device(getattr(L, f)) for f in ("x", "w_router", "w_gate", "w_up", "w_down")}
-    for k0 in (2, 8):
-        out, tap = run_layer_dev(torch, B_, L, dev, k0)
-        err, ref = check_layer(oracle, L, k0, out, tap, "B=64 duplicated tokens k0=%d" % k0)
-        cnt = np.bincount(ref["expert_idx"][ref["expert_idx"] >= 0], minlength=L.N)
-        say("B=64 duplicated tokens k0=%d: T=%d, most pairs on one expert %d, err=%.2e" % (k0, ref["n_active"], cnt.max(), err))
-        assert cnt.max() >= 32
+    try:
+        for path in (0, 3):  # the single kernel for larger batches, and the separate stage kernels
+            B_.set_kernel_path(path)
+            for k0 in (2, 8):
+                out, tap = run_layer_dev(torch, B_, L, dev, k0)
+                err, ref = check_layer(oracle, L, k0, out, tap, "B=64 duplicated tokens k0=%d path %d" % (k0, path))
+                cnt = np.bincount(ref["expert_idx"][ref["expert_idx"] >= 0], minlength=L.N)
+                say("B=64 duplicated tokens k0=%d path %d: T=%d, most pairs on one expert %d, err=%.2e"
+                    % (k0, path, ref["n_active"], cnt.max(), err))
+                assert cnt.max() >= 32
+    finally:
+        B_.set_kernel_path(0)
