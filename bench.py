@@ -286,6 +286,27 @@ def run(args):
             torch.cuda.synchronize()
         kern[k0] = (acc / n * 1e3).tolist()  # us: router+route, gate/up, down
 
+    # ---- spread of single calls and the cache-warm latency (token batch 0; outside the timed region):
+    # an event pair around every call of a back-to-back run; then the same with ONE weight set, which
+    # at small T is served from the 256 MB infinity cache instead of HBM (reported as such, never as value)
+    def per_call(k0, n_sets):
+        n = min(args.steps, 200)
+        ev = [hip.event() for _ in range(n + 1)]
+        calls = [make_call(xs[0], sets[r], k0) for r in range(n_sets)]
+        for it in range(args.warmup):
+            assert calls[it % n_sets]() == 0
+        torch.cuda.synchronize()
+        hip.record(ev[0], sptr)
+        for it in range(n):
+            calls[it % n_sets]()
+            hip.record(ev[it + 1], sptr)
+        torch.cuda.synchronize()
+        us = np.array([hip.elapsed_ms(ev[i], ev[i + 1]) * 1e3 for i in range(n)])
+        return dict(median=round(float(np.median(us)), 2), p10=round(float(np.percentile(us, 10)), 2),
+                    p90=round(float(np.percentile(us, 90)), 2))
+    per_call_us = {str(k0): per_call(k0, R) for k0 in sorted({args.k0, k})}
+    cache_warm_us = {str(k0): per_call(k0, 1) for k0 in sorted({args.k0, k})}
+
     # ---- report
     def mean_over_trials(dct, k0):
         return float(np.mean([dct[(ti, k0)] for ti in range(len(xs))]))
@@ -366,7 +387,8 @@ def run(args):
                 latency_ratio_vs_topk=round(value / table[str(k)]["latency_us"], 4),
                 unique_expert_ratio_vs_topk=round(table[str(args.k0)]["unique_experts"] / table[str(k)]["unique_experts"], 4),
                 layer_frac_of_hbm_peak=table[str(args.k0)]["frac_of_peak"],
-                per_k0=table, latency_vs_unique_experts_fit=fit, parity_max_rel_err=parity,
+                per_k0=table, per_call_us=per_call_us, cache_warm_single_weight_set_us=cache_warm_us,
+                latency_vs_unique_experts_fit=fit, parity_max_rel_err=parity,
                 roofline=roofline, cpu_baseline=cpu)
     return line
 
