@@ -312,6 +312,14 @@ def test_full_size_235b_shape(torch, B_, oracle):
                 say(ctx, "T=%d err=%.2e" % (ref["n_active"], err))
         finally:
             B_.set_kernel_path(0)
+    # a larger batch on the same weights: the single kernel with per-workgroup staging (vectors of
+    # 8 KB leave room for about a dozen per workgroup, so pieces occur)
+    L48 = W.make_layer("qwen3_235b", 3001, B=48, N=1, I=8)  # only its x is used
+    Lb = W.Layer(**{**L.__dict__, "B": 48, "x": L48.x})
+    devb = dict(dev, x=B_.to_device(Lb.x))
+    out, tap = run_layer_dev(torch, B_, Lb, devb, 3)
+    err, ref = check_layer(oracle, Lb, 3, out, tap, "qwen3_235b B=48 k0=3")
+    say("qwen3_235b B=48 k0=3 T=%d err=%.2e" % (ref["n_active"], err))
 
 
 # ---- general OEA (Algorithm 2): top-p cut of the baseline, k_max, rank window max_p
