@@ -200,21 +200,38 @@ __device__ __forceinline__ int wg_first_row(const int* l_off, int T, int rows, i
   return uniform(lo * rows + int(r));
 }
 
+// The state is READ before the workgroup arrives at the grid barrier (balance_load) and evaluated after
+// (balance_shares): no workgroup can pass that barrier, let alone reach the end of the kernel where it
+// writes its new rate, before every workgroup has arrived, so all of them read the same values.
+struct BalanceIn {
+  float w[4], r[4];  // lane l holds workgroups 4 l .. 4 l + 3
+};
+__device__ __forceinline__ BalanceIn balance_load(uint32_t* ctrl, uint32_t parity, int G, int lane) {
+  const float* const st = reinterpret_cast<const float*>(ctrl + kBalBase);
+  const float* const w_old = st + (parity & 1u) * kBalMaxWg;
+  const float* const rate = st + 2 * kBalMaxWg;
+  BalanceIn in;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int b = lane * 4 + j;
+    in.w[j] = b < G ? __hip_atomic_load(w_old + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
+    in.r[j] = b < G ? __hip_atomic_load(rate + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
+  }
+  return in;
+}
+
 // Executed by ONE wavefront: new weights from the state and the rates of the previous call, their
 // cumulative shares -> l_frac[0..G] (l_frac[0] = 0, l_frac[G] = 1).  write_back: store the new state.
 __device__ __forceinline__ void balance_shares(uint32_t* ctrl, uint32_t parity, int G, bool write_back, float* l_frac,
-                                               int lane) {
+                                               int lane, const BalanceIn in) {
   float* const st = reinterpret_cast<float*>(ctrl + kBalBase);
-  const float* const w_old = st + (parity & 1u) * kBalMaxWg;
   float* const w_new = st + ((parity & 1u) ^ 1u) * kBalMaxWg;
-  const float* const rate = st + 2 * kBalMaxWg;
   float w[4], r[4];
   float sum_r = 0.f, n_r = 0.f;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const int b = lane * 4 + j;
-    w[j] = b < G ? __hip_atomic_load(w_old + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
-    r[j] = b < G ? __hip_atomic_load(rate + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
+    w[j] = in.w[j];
+    r[j] = in.r[j];
     if (!(w[j] > 0.5f && w[j] < 2.f)) w[j] = 1.f;  // fresh (zeroed) or damaged state
     if (!(r[j] > 0.f && r[j] < 1e30f)) r[j] = 0.f;  // no measurement
     sum_r += r[j];
@@ -446,6 +463,9 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   OEA_TL(p.ctrl, 0);
   uint32_t gen0 = 0;  // thread 0: barrier generation at the start of this call
   if (tid == 0 || tid == 64) gen0 = grid_generation(p.ctrl);  // thread 64: parity of the call for the speed weights
+  const bool balanced = G <= kBalMaxWg;
+  BalanceIn bal_in{};
+  if (balanced && wave == 1) bal_in = balance_load(p.ctrl, uint32_t(__builtin_amdgcn_readfirstlane(int(gen0))), G, lane);
   // ---- phase R1.  x of the batch -> LDS: loads first, written after the logits
   const int d16 = d / EPL;
   const int n16_x = B * d16;
@@ -518,9 +538,8 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
 
   OEA_TL(p.ctrl, 1);
   grid_arrive(p.ctrl, gen0 + 1);  // logits and cleared out words are in memory
-  const bool balanced = G <= kBalMaxWg;
   if (balanced && wave == 1)  // while thread 0 waits at the barrier
-    balance_shares(p.ctrl, uint32_t(__builtin_amdgcn_readfirstlane(int(gen0))), G, wg == 0, l_frac, lane);
+    balance_shares(p.ctrl, uint32_t(__builtin_amdgcn_readfirstlane(int(gen0))), G, wg == 0, l_frac, lane, bal_in);
   grid_wait(p.ctrl, gen0 + 1, p.spin_limit);
   OEA_TL(p.ctrl, 2);
 
@@ -681,6 +700,9 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedPara
 
   uint32_t gen0 = 0;
   if (tid == 0 || tid == 64) gen0 = grid_generation(ctrl);
+  const bool balanced = G <= kBalMaxWg;
+  BalanceIn bal_in{};
+  if (balanced && wave == 1) bal_in = balance_load(ctrl, uint32_t(__builtin_amdgcn_readfirstlane(int(gen0))), G, lane);
   {  // clear this workgroup's slice of out[B,d]
     const int total = B * d;
     const int per = (total + G - 1) / G;
@@ -725,9 +747,8 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedPara
     }
   }
   grid_arrive(ctrl, gen0 + 1);
-  const bool balanced = G <= kBalMaxWg;
   if (balanced && wave == 1)
-    balance_shares(ctrl, uint32_t(__builtin_amdgcn_readfirstlane(int(gen0))), G, wg == 0, l_frac, lane);
+    balance_shares(ctrl, uint32_t(__builtin_amdgcn_readfirstlane(int(gen0))), G, wg == 0, l_frac, lane, bal_in);
   grid_wait(ctrl, gen0 + 1, p.spin_limit);
 
   if (tid == 0) l_nact[1] = l_nact[2] = 0;
