@@ -286,9 +286,11 @@ def test_fused_kernel_repeatable_and_masked(torch, B_, oracle):
 
 
 def test_full_size_30b_batch_sweep(torch, B_, oracle):
-    L0 = W.make_layer("qwen3_30b", 2100, B=128)
+    L0 = W.make_layer("qwen3_30b", 2100, B=160)
     dev_w = {f: B_.to_device(getattr(L0, f)) for f in ("w_router", "w_gate", "w_up", "w_down")}
-    for B in (1, 2, 8, 32, 64, 128):
+    # up to 32: single kernel with x resident; 64, 128: single kernel with per-workgroup staging;
+    # 160: router kernel and the two stage kernels
+    for B in (1, 2, 8, 32, 64, 128, 160):
         L = W.Layer(**{**L0.__dict__, "B": B, "x": np.ascontiguousarray(L0.x[:B])})
         dev = dict(dev_w, x=B_.to_device(L.x))
         for k0 in ((3, 8) if B <= 32 else (3,)):
