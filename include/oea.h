@@ -155,6 +155,14 @@ int moe_decode(const void *x, const void *W_router, const void *W_gate, const vo
  */
 int oea_set_kernel_path(int path);
 
+/*
+ * Measurement aid: enqueue a kernel that reads `bytes` bytes (>= 1 MiB) at `buf` once, with the
+ * access pattern the expert kernels stream weights with, and discards them.  Timing it over memory
+ * that is not in any cache gives the practical read ceiling of the device, the yardstick next to
+ * the published HBM peak.  `sink` (4 bytes of device memory, may be NULL) is never written in practice.
+ */
+int oea_read_probe(const void *buf, size_t bytes, void *sink, void *stream);
+
 /* Optional inputs and taps for moe_decode_ex; every pointer may be NULL. */
 typedef struct {
   const float *router_bias;   /* [N] fp32 added to the logits (synthetic skewed-popularity workload) */

@@ -17,7 +17,7 @@ OEA_OK = 0
 STATUS = {"OEA_ERR_NULL": -1, "OEA_ERR_SHAPE": -2, "OEA_ERR_K": -3, "OEA_ERR_ALIGN": -4,
           "OEA_ERR_WORKSPACE": -5, "OEA_ERR_DTYPE": -6, "OEA_ERR_HIP": -7}
 EXPORTS = ("oea_status_string", "oea_workspace_bytes", "oea_workspace_init", "oea_route", "oea_route_batched", "oea_route_general",
-           "moe_decode", "moe_decode_ex", "oea_set_kernel_path")
+           "moe_decode", "moe_decode_ex", "oea_set_kernel_path", "oea_read_probe")
 
 
 class OeaError(RuntimeError):
@@ -60,6 +60,8 @@ def lib():
         L.oea_route_batched.argtypes = [vp, vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
         L.oea_route_general.restype = ci
         L.oea_route_general.argtypes = [vp, vp, ci, ci, ci, ctypes.c_double, ci, ci, vp, vp, vp, vp, vp, vp, vp]
+        L.oea_read_probe.restype = ci
+        L.oea_read_probe.argtypes = [vp, sz, vp, vp]
         L.moe_decode.restype = ci
         L.moe_decode.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp]
         L.moe_decode_ex.restype = ci
@@ -128,6 +130,12 @@ def oea_route(router_logits, k, k0, stream=None, out=None):
                            _ptr(out["gate_w"]), _ptr(out["n_sel"]), _ptr(out["active_list"]),
                            _ptr(out["n_active"]), _stream(stream)))
     return out
+
+
+def read_probe(buf, stream=None):
+    """Enqueue one streaming read of the tensor `buf` (measurement aid, see oea_read_probe)."""
+    assert buf.is_cuda and buf.is_contiguous()
+    _check(lib().oea_read_probe(_ptr(buf), buf.numel() * buf.element_size(), None, _stream(stream)))
 
 
 def oea_route_batched(router_logits, k, k0, token_mask=None, stream=None):

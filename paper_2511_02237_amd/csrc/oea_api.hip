@@ -90,6 +90,14 @@ extern "C" int oea_set_kernel_path(int path) {
   return OEA_OK;
 }
 
+extern "C" int oea_read_probe(const void* buf, size_t bytes, void* sink, void* stream) {
+  if (!buf) return OEA_ERR_NULL;
+  if (!aligned16(buf)) return OEA_ERR_ALIGN;
+  if (bytes < (size_t)1 << 20) return OEA_ERR_SHAPE;
+  hipError_t e = launch_read_probe(buf, bytes, static_cast<uint32_t*>(sink), static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? OEA_OK : OEA_ERR_HIP;
+}
+
 extern "C" int oea_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
   if (!workspace) return OEA_ERR_NULL;
   if (!aligned16(workspace)) return OEA_ERR_ALIGN;

@@ -313,6 +313,27 @@ __global__ __launch_bounds__(kFfnThreads) void expert_stream_kernel(FfnParams p)
   }
 }
 
+// Measurement aid: read `n16` 16-byte granules once with the access pattern of the expert kernels
+// (each wavefront a contiguous share, 16 non-temporal 1 KB requests in flight) and do nothing with
+// them.  Its rate is the practical ceiling for streaming weights on the device at hand.
+__global__ __launch_bounds__(kFfnThreads) void read_probe_kernel(const uint4* __restrict__ src, size_t n16,
+                                                                  uint32_t* sink) {
+  const int lane = threadIdx.x & 63;
+  const size_t wave = (size_t)blockIdx.x * kFfnWaves + (threadIdx.x >> 6);
+  const size_t nwaves = (size_t)gridDim.x * kFfnWaves;
+  const size_t per = (n16 / nwaves) & ~size_t(1023);  // whole batches of 16 x 64 granules; the remainder is skipped
+  const uint4* p = src + wave * per;
+  uint32_t acc = 0;
+  for (size_t i = 0; i < per; i += 1024) {
+    uint4 v[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) v[j] = load_stream16(p + i + j * 64 + lane);
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc ^= v[j].x ^ v[j].y ^ v[j].z ^ v[j].w;
+  }
+  if (acc == 0x9e3779b9u && sink) *sink = acc;  // keeps the loads alive; practically never taken
+}
+
 int g_num_cus = 0;
 
 int num_cus() {
@@ -427,6 +448,12 @@ hipError_t launch_stage(int stage, FfnParams p, int B, int k, hipStream_t s) {
 }  // namespace
 
 void set_force_generic(bool on) { g_force_generic = on; }
+
+hipError_t launch_read_probe(const void* buf, size_t bytes, uint32_t* sink, hipStream_t s) {
+  hipLaunchKernelGGL(read_probe_kernel, dim3(num_cus()), dim3(kFfnThreads), 0, s, static_cast<const uint4*>(buf),
+                     bytes / 16, sink);
+  return hipGetLastError();
+}
 
 hipError_t launch_expert_gate_up(const void* x, const void* w_gate, const void* w_up, void* h, int B,
                                  int d, int N, int I, int k, oea_dtype dt, Grouping g, hipStream_t s) {

@@ -83,6 +83,7 @@ hipError_t try_launch_stage_kernels(int stage, const void* vec, const void* wa, 
                                     float* out, int B, int d, int N, int I, int k, oea_dtype dt, Grouping g,
                                     hipStream_t s);
 
+hipError_t launch_read_probe(const void* buf, size_t bytes, uint32_t* sink, hipStream_t s);
 size_t route_lds_bytes(int B, int N);
 void set_force_generic(bool on);
 

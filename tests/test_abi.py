@@ -22,6 +22,7 @@ def L():
     lib.oea_workspace_bytes.restype = sz
     lib.oea_workspace_bytes.argtypes = [ci] * 5
     lib.oea_workspace_init.argtypes = [vp, sz, vp]
+    lib.oea_read_probe.argtypes = [vp, sz, vp, vp]
     lib.oea_route.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
     lib.oea_route_batched.argtypes = [vp, vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
     lib.oea_route_general.argtypes = [vp, vp, ci, ci, ci, ctypes.c_double, ci, ci, vp, vp, vp, vp, vp, vp, vp]
@@ -132,6 +133,12 @@ def test_workspace_init_argument_checks(L):
     assert L.oea_workspace_init(None, 1024, None) == -1
     assert L.oea_workspace_init(P + 4, 1024, None) == -4
     assert L.oea_workspace_init(P, 8, None) == -5
+
+
+def test_read_probe_argument_checks(L):
+    assert L.oea_read_probe(None, 1 << 20, None, None) == -1
+    assert L.oea_read_probe(P + 4, 1 << 20, None, None) == -4
+    assert L.oea_read_probe(P, (1 << 20) - 16, None, None) == -2
 
 
 def test_binding_module_names_match_the_abi():

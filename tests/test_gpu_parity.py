@@ -522,3 +522,13 @@ def test_graph_capture_and_replay(torch, B_, oracle):
             err = np.abs(got.cpu().numpy() - want).max() / np.abs(want).max()
             assert err <= 1e-5, "replay %d %s: %.2e" % (rep, name, err)
     say("graph replays match the eager result")
+
+
+def test_read_probe_runs_and_leaves_memory_alone(torch, B_):
+    # the measurement aid only reads: the buffer is unchanged afterwards and the launch succeeds
+    # for sizes that are not a multiple of its batch
+    buf = torch.arange((3 << 20) + 4096, dtype=torch.int32, device="cuda:0")
+    keep = buf.clone()
+    B_.read_probe(buf)
+    torch.cuda.synchronize()
+    assert torch.equal(buf, keep)
