@@ -567,10 +567,16 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   int T = uniform(l_nact[0]);
   T = T < 0 ? 0 : (T > N ? N : T);
   const float* const frac = balanced ? l_frac : nullptr;
-  const int RA0 = wg_first_row(l_off, T, I, kBetaUp, wg, G, lane, frac);
-  const int RA1 = wg_first_row(l_off, T, I, kBetaUp, wg + 1, G, lane, frac);
-  const int RB0 = wg_first_row(l_off, T, d, kBetaDown, wg, G, lane, frac);
-  const int RB1 = wg_first_row(l_off, T, d, kBetaDown, wg + 1, G, lane, frac);
+  // the four cut points of this workgroup (both ends, both stages): one wavefront each, shared through
+  // the routing scratch, which nothing reads any more
+  if (wave < 4) {
+    const int cut = wg_first_row(l_off, T, wave < 2 ? I : d, wave < 2 ? kBetaUp : kBetaDown, wg + (wave & 1), G, lane,
+                                 frac);
+    if (lane == 0) l_route[wave] = uint32_t(cut);
+  }
+  __syncthreads();
+  const int RA0 = uniform(int(l_route[0])), RA1 = uniform(int(l_route[1]));
+  const int RB0 = uniform(int(l_route[2])), RB1 = uniform(int(l_route[3]));
   const unsigned long long tA0 = wall_clock64();
   OEA_TL(p.ctrl, 3);
 
@@ -767,10 +773,16 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedPara
   int T = uniform(l_nact[0]);
   T = T < 0 ? 0 : (T > N ? N : T);
   const float* const frac = balanced ? l_frac : nullptr;
-  const int RA0 = wg_first_row(l_off, T, I, kBetaUp, wg, G, lane, frac);
-  const int RA1 = wg_first_row(l_off, T, I, kBetaUp, wg + 1, G, lane, frac);
-  const int RB0 = wg_first_row(l_off, T, d, kBetaDown, wg, G, lane, frac);
-  const int RB1 = wg_first_row(l_off, T, d, kBetaDown, wg + 1, G, lane, frac);
+  // the four cut points of this workgroup (both ends, both stages): one wavefront each, shared through
+  // the routing scratch, which nothing reads any more
+  if (wave < 4) {
+    const int cut = wg_first_row(l_off, T, wave < 2 ? I : d, wave < 2 ? kBetaUp : kBetaDown, wg + (wave & 1), G, lane,
+                                 frac);
+    if (lane == 0) l_route[wave] = uint32_t(cut);
+  }
+  __syncthreads();
+  const int RA0 = uniform(int(l_route[0])), RA1 = uniform(int(l_route[1]));
+  const int RB0 = uniform(int(l_route[2])), RB1 = uniform(int(l_route[3]));
 
   // pairs of the experts a row range touches: [first pair, count)
   auto pairs_of = [&](int R0, int R1, int rows, int& off0, int& nvec) __attribute__((always_inline)) {

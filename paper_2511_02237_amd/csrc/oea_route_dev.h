@@ -115,22 +115,21 @@ __device__ __forceinline__ int wave_incl_scan_i32(int v, int lane) {
 // completes U; the results are complete after the caller's next barrier.
 template <int NT>
 __device__ __forceinline__ void route_active(int N, RouteOut o, uint32_t* lds) {
-  constexpr int NW = NT / 64;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  uint32_t* U = lds;
-  uint32_t* scan = lds + 16;
+  const int tid = threadIdx.x;
+  const uint32_t* U = lds;
+  // position of expert e among the members = members below it, counted from the mask words
+  // themselves (at most 16 of them): no scan across the wavefronts, no barrier
   const int e = tid;
-  const bool in_u = e < N && ((U[e >> 5] >> (e & 31)) & 1u);
-  const uint64_t ballot = __ballot(in_u);
-  if (lane == 0) scan[wave] = uint32_t(__popcll(ballot));
-  __syncthreads();
-  int pos_base = 0, T = 0;
-  for (int w = 0; w < NW; ++w) {
-    const int a = int(scan[w]);
-    if (w < wave) pos_base += a;
-    T += a;
+  const int nw = (N + 31) >> 5;
+  int T = 0, pos = 0;
+  for (int w = 0; w < nw; ++w) {
+    const int c = __popc(U[w]);
+    T += c;
+    pos += w < (e >> 5) ? c : 0;
   }
-  const int pos = pos_base + __popcll(ballot & ((1ull << lane) - 1ull));
+  const uint32_t mine = e < N ? U[e >> 5] : 0u;
+  const bool in_u = (mine >> (e & 31)) & 1u;
+  pos += __popc(mine & ((1u << (e & 31)) - 1u));
   if (in_u) o.active_list[pos] = e;
   if (e < N && e >= T) o.active_list[e] = -1;
   if (tid == 0) *o.n_active = T;
@@ -152,32 +151,49 @@ __device__ __forceinline__ void route_group(int B, int N, int k, RouteOut o, uin
   if (!o.grp_off) return;
   // ---- pairs per expert, CSR offsets by position in the active list
   const int e = tid;
-  const bool in_u = e < N && ((U[e >> 5] >> (e & 31)) & 1u);
-  const uint64_t ballot = __ballot(in_u);
+  const int nw = (N + 31) >> 5;
+  int T = 0, pos = 0;  // members of U, members below e (from the mask words, as in route_active)
+  for (int w = 0; w < nw; ++w) {
+    const int c = __popc(U[w]);
+    T += c;
+    pos += w < (e >> 5) ? c : 0;
+  }
+  const uint32_t mine = e < N ? U[e >> 5] : 0u;
+  const bool in_u = (mine >> (e & 31)) & 1u;
+  pos += __popc(mine & ((1u << (e & 31)) - 1u));
   int cnt = 0;
   if (in_u)
     for (int w = 0; w < NWB; ++w) cnt += __popc(colmask[e * NWB + w]);
   const int incl = wave_incl_scan_i32(cnt, lane);  // inclusive scan of cnt inside the wave
-  if (lane == 63) scan[16 + wave] = uint32_t(incl);
-  if (lane == 0) scan[32 + wave] = uint32_t(__popcll(ballot));
-  __syncthreads();
-  int pos_base = 0, cnt_base = 0, T = 0, P = 0;
-  for (int w = 0; w < NW; ++w) {
-    const int a = int(scan[32 + w]), cw = int(scan[16 + w]);
-    if (w < wave) {
-      pos_base += a;
-      cnt_base += cw;
+  int excl;
+  if (N <= 128) {
+    // the experts sit in the first two wavefronts: the second one counts the pairs of the first
+    // 64 experts itself instead of waiting for them at a barrier
+    int before = 0;
+    if (wave == 1) {
+      int c0 = 0;
+      if ((U[lane >> 5] >> (lane & 31)) & 1u)
+        for (int w = 0; w < NWB; ++w) c0 += __popc(colmask[lane * NWB + w]);
+      before = __builtin_amdgcn_readlane(wave_incl_scan_i32(c0, lane), 63);
     }
-    T += a;
-    P += cw;
+    excl = before + incl - cnt;
+    if (e == N - 1) o.grp_off[T] = excl + cnt;  // all pairs
+  } else {
+    if (lane == 63) scan[16 + wave] = uint32_t(incl);
+    __syncthreads();
+    int cnt_base = 0, P = 0;
+    for (int w = 0; w < NW; ++w) {
+      const int cw = int(scan[16 + w]);
+      cnt_base += w < wave ? cw : 0;
+      P += cw;
+    }
+    excl = cnt_base + incl - cnt;
+    if (tid == 0) o.grp_off[T] = P;
   }
-  const int pos = pos_base + __popcll(ballot & ((1ull << lane) - 1ull));
-  const int excl = cnt_base + incl - cnt;
   if (in_u) {
     o.grp_off[pos] = excl;
     eoff[e] = uint32_t(excl);
   }
-  if (tid == 0) o.grp_off[T] = P;
   __syncthreads();
   OEA_ROUTE_TL(13);
 
