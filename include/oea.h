@@ -129,7 +129,7 @@ int oea_route_general(const float *router_logits, const uint8_t *token_mask, int
  *                     be ordered on the same stream.
  * For the Qwen3-30B-A3B and Qwen3-235B-A22B layer shapes (bf16, N <= 128, k <= 16, B <= 128) the
  * whole layer runs as ONE persistent kernel with one workgroup per compute unit, one grid-wide
- * barrier and per-expert completion flags; it expects the device to itself while it runs (a
+ * barrier and per-expert completion counters; it expects the device to itself while it runs (a
  * workgroup that cannot be placed delays the others; every wait is bounded, after about a second
  * the call gives up and its output is undefined).  Still larger batches of these shapes run as
  * three kernels (router + routing, gate/up stage, down stage) that share the fused kernel's stage

@@ -7,7 +7,7 @@ namespace oea {
 
 static size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
 // control words at the start of a workspace (zeroed by init): 1024 barrier/flag words, then one
-// 128-byte line per expert for the completion counters and one for the completion flags (128 experts)
+// 128-byte line per expert for the completion counters (128 experts) and as many unused lines
 static constexpr size_t kCtrlWords = 1024 + 2 * 128 * 32 + 3 * 256;  // see WsLayout::ctrl
 
 WsLayout ws_layout(int B, int d, int N, int I, int k, int elem_bytes) {

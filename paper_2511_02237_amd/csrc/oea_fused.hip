@@ -11,7 +11,7 @@
 //             write them out at the end; then the workgroup adds its rows to the completion
 //             counters of its experts
 //   phase B   down mat-vec stage: first tiles requested, then the workgroup waits (bounded) for the
-//             completion flags of ITS experts only, stages their hidden vectors and streams;
+//             completion counters of ITS experts only, stages their hidden vectors and streams;
 //             results are added into `out` with the gate weights at the end (Eq. 1)
 //
 // Compared with three back-to-back kernels this removes two dispatch gaps with their pipeline
@@ -58,7 +58,7 @@ struct FusedParams {
   void* h;         // [B*k, I] workspace
   RouteOut ro;     // global copies of the routing result, written by workgroup 0
   uint32_t* ctrl;  // [3] error flag, [32] and [256 + 32 i] barrier arrivals, [64] barrier generation (separate
-                   // 128-byte lines), from [1024] the per-expert completion counters and flags (done_count, done_flag)
+                   // 128-byte lines), from [1024] the per-expert completion counters (done_count)
   int B, d, N, I, k, k0;
   int cap_vec;     // most (expert, token) pairs one workgroup can meet in one stage (large batches: vectors per
                    // piece in the gate/up stage)
@@ -383,20 +383,18 @@ __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_ou
   if (wg_has && use_buf) flush_results<WT, STAGE>(sv, ebuf, s_tok, s_gw, h_out, out, base, tid);
 }
 
-// Layout of the per-expert completion words in the control area: counter and flag of the expert at
-// position a of the active list each sit on a 128-byte line of their own (same-line atomics and
-// polls from many workgroups serialise badly).
+// Layout of the per-expert completion words in the control area: the counter of the expert at
+// position a of the active list sits on a 128-byte line of its own (same-line atomics and polls
+// from many workgroups serialise badly).
 constexpr int kDoneBase = 1024;  // first word
 constexpr int kDoneStride = 32;  // words between experts
 __device__ __forceinline__ uint32_t* done_count(uint32_t* ctrl, int a) { return ctrl + kDoneBase + a * kDoneStride; }
-__device__ __forceinline__ uint32_t* done_flag(uint32_t* ctrl, int a) {
-  return ctrl + kDoneBase + (OEA_MAX_FUSED_N + a) * kDoneStride;
-}
 
 // After the gate/up stage: tell the down stage which hidden vectors are complete.  Called by the whole
 // workgroup; every wavefront first drains its h stores.  Thread 0 adds the rows this workgroup
-// produced to the counter of each expert it touched; the arrival that completes an expert (all
-// `rows` hidden units) raises that expert's flag.
+// produced to the counter of each expert it touched; an expert is complete when its counter has
+// reached `rows` hidden units, which is what the consumers poll for.  (A separate flag raised by the
+// arrival that completes an expert cost that arrival a second trip to memory: about 1 us per layer.)
 // (Signalling only after the down stage's first tiles are requested, with the h stores completing
 // underneath, was measured slower: early finishers then compete with the gate/up stragglers that
 // everyone waits for.)
@@ -406,23 +404,16 @@ __device__ __forceinline__ void signal_hidden_done(uint32_t* ctrl, int R0, int R
   if (threadIdx.x != 0) return;
   if (R0 >= R1) return;
   const int a0 = R0 / rows, a1 = (R1 - 1) / rows;
-  uint32_t old[kMaxSeg] = {0, 0, 0};
-  int n[kMaxSeg] = {0, 0, 0};
 #pragma unroll
   for (int sgm = 0; sgm < kMaxSeg; ++sgm) {
     const int a = a0 + sgm;
     if (a <= a1) {
       const int lo = R0 > a * rows ? R0 : a * rows;
       const int hi = R1 < (a + 1) * rows ? R1 : (a + 1) * rows;
-      n[sgm] = hi - lo;
-      old[sgm] = __hip_atomic_fetch_add(done_count(ctrl, a), uint32_t(n[sgm]), __ATOMIC_RELAXED,
-                                        __HIP_MEMORY_SCOPE_AGENT);
+      // no value comes back: the thread does not wait for the counter's round trip
+      __hip_atomic_fetch_add(done_count(ctrl, a), uint32_t(hi - lo), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
-#pragma unroll
-  for (int sgm = 0; sgm < kMaxSeg; ++sgm)
-    if (n[sgm] > 0 && old[sgm] + uint32_t(n[sgm]) == uint32_t(rows))
-      __hip_atomic_store(done_flag(ctrl, a0 + sgm), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // d == LPR0*EPL*NCH0 and I == LPR1*EPL*NCH1 exactly; N <= 64*NV; B <= 32; k <= 16.
@@ -492,7 +483,6 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   // per-expert completion counters of the gate/up stage: cleared here, before the first grid barrier
   if (wg == 0 && tid < N) {
     __hip_atomic_store(done_count(p.ctrl, tid), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(done_flag(p.ctrl, tid), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 
   // router logits: one (token, expert) dot product per wavefront, fp64 accumulation, one rounding
@@ -612,11 +602,11 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
         OEA_TL(ctrl, 5);
         // No grid barrier here: this workgroup only needs the hidden vectors of ITS experts, which
         // its neighbours produce (both stages cut the expert list in about the same proportions).
-        // Wait, bounded, until each of them is flagged complete.
+        // Wait, bounded, until the counter of each of them says complete.
         if (tid == 0) {
           uint32_t spins = 0;
           for (int sgm = 0; sgm < nseg; ++sgm)
-            while (__hip_atomic_load(done_flag(ctrl, a0 + sgm), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+            while (__hip_atomic_load(done_count(ctrl, a0 + sgm), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < uint32_t(I)) {
               __builtin_amdgcn_s_sleep(2);
               if (++spins > spin_limit) {
                 atomicExch(ctrl + 3, 1u);
@@ -718,7 +708,6 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedPara
   }
   if (wg == 0 && tid < N) {
     __hip_atomic_store(done_count(ctrl, tid), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(done_flag(ctrl, tid), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   {  // router logits: a wavefront takes one expert and four tokens at a time (the router row chunk is
      // loaded once for the four, their loads and reductions overlap)
@@ -863,7 +852,7 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedPara
               if (tid == 0) {
                 uint32_t spins = 0;
                 for (int sgm = 0; sgm < nseg; ++sgm)
-                  while (__hip_atomic_load(done_flag(ctrl, a0 + sgm), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+                  while (__hip_atomic_load(done_count(ctrl, a0 + sgm), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < uint32_t(I)) {
                     __builtin_amdgcn_s_sleep(2);
                     if (++spins > spin_limit) {
                       atomicExch(ctrl + 3, 1u);

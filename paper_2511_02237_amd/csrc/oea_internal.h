@@ -13,7 +13,7 @@ struct WsLayout {
   size_t ctrl;         // uint32[1024 + 8192 + 768].  [9216..) is the fused kernel's load-balancing state (speed
                        // weights of the workgroups, adapted from call to call); the rest is zero between calls: [0] arrival counter of the router kernel,
                        // [3] error flag, [32], [64] and [256 + 32 i] grid-barrier words of the fused kernel, [1024..) its
-                       // per-expert completion counters and flags, one 128-byte line each
+                       // per-expert completion counters, one 128-byte line each (as many lines again are unused)
   size_t logits;       // float [B,N]
   size_t expert_idx;   // int32 [B,k]
   size_t gate_w;       // float [B,k]
