@@ -42,6 +42,10 @@ namespace {
 constexpr size_t kFusedLdsMax = 156 * 1024;
 #define OEA_MAX_FUSED_N 128  // experts the fused kernel handles (completion words in the control area)
 constexpr int kFusedStage = 8;  // staging loads kept in flight per thread
+// Small-batch kernel, down stage: two wavefronts (few active experts) or one request no weight
+// tiles before the hidden vectors are there, and stage them (see fused_stage).
+// Measured at B=16: -1.2 us with two at T=36, but +0.4 us at T=73, where one is neutral.
+constexpr int kStageWaves = 2;
 constexpr int kBalBase = 1024 + 2 * OEA_MAX_FUSED_N * 32;  // ctrl word of the speed-weight state: w[2][256], rate[256]
 constexpr int kBalMaxWg = 256;                             // workgroups it covers
 
@@ -293,7 +297,7 @@ __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_ou
                                             const int* l_off, const int* l_tok, const float* l_gw,
                                             const uint4* l_vec, float* ebuf, int ecap, uint32_t* l_next, Mid mid,
                                             unsigned long long* tl_wave = nullptr, int c0 = 0,
-                                            int c1 = 0x7fffffff) {
+                                            int c1 = 0x7fffffff, int n_defer = 0) {
   constexpr int EPL = 16 / int(sizeof(WT));
   constexpr int R = 64 / LPR;
   constexpr int NM = STAGE == 0 ? 2 : 1;
@@ -330,7 +334,10 @@ __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_ou
 
   uint4 wA[NM][RG][NCH], wB[NM][RG][NCH];
   int rA = lo, nA = 0, rB = lo, nB = 0;
-  if (wg_has) {  // uniform over the workgroup; a wavefront that finds no tile requests a placeholder
+  // The first n_defer wavefronts request nothing before mid: what they load IN mid (polled counters,
+  // staged vectors) then does not queue behind two weight tiles (loads return in issue order).
+  const bool deferred = uniform(tid >> 6) < n_defer;
+  if (wg_has && !deferred) {  // a wavefront that finds no tile requests a placeholder
     take_tile(rA, nA);
     take_tile(rB, nB);
     load_tile<WT, NM, LPR, NCH, RG, true>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv0, rA), nA);
@@ -339,6 +346,13 @@ __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_ou
   __builtin_amdgcn_sched_barrier(0);  // the requests above are issued before anything in mid
 
   mid(a0, wg_has ? nseg : 0);
+
+  if (wg_has && deferred) {
+    take_tile(rA, nA);
+    take_tile(rB, nB);
+    load_tile<WT, NM, LPR, NCH, RG, true>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv0, rA), nA);
+    load_tile<WT, NM, LPR, NCH, RG, true>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv0, rB), nB);
+  }
 
   // pair lists of this workgroup's experts
   const int off0 = uniform(l_off[a0]);
@@ -594,6 +608,7 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   const uint32_t spin_limit = p.spin_limit;
   const int cap_vec = p.cap_vec;
   unsigned long long tB0 = 0;
+  const int n_defer = 2 * T <= N ? kStageWaves : 1;
   fused_stage<WT, 1, LPR1, NCH1, 2>(
       static_cast<const WT*>(p.w_down), static_cast<const WT*>(nullptr), static_cast<WT*>(nullptr), p.out, d, I, RB0,
       RB1, N, P, p.cap_vec, l_active, l_off, l_tok, l_gw, l_vec,
@@ -624,27 +639,32 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
         const int n16 = nvec * I16;
         __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<WT*>(hsrc + (size_t)off0 * I), 0, n16 * 16, 0x00020000);
-        for (int base = 0; base < n16; base += kFusedStage * kFfnThreads) {
-          u32x4 t4[kFusedStage];
+        // staged by the wavefronts that have no weight tiles in flight
+        const int kStagers = n_defer * 64;
+        if (tid < kStagers)
+          for (int base = 0; base < n16; base += kFusedStage * kStagers) {
+            u32x4 t4[kFusedStage];
 #pragma unroll
-          for (int j = 0; j < kFusedStage; ++j) {
-            const int i16 = base + j * kFfnThreads + tid;
-            t4[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (i16 < n16 ? i16 : n16 - 1) * 16, 0, 1 | 16);
-          }
+            for (int j = 0; j < kFusedStage; ++j) {
+              const int i16 = base + j * kStagers + tid;
+              t4[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (i16 < n16 ? i16 : n16 - 1) * 16, 0, 1 | 16);
+            }
 #pragma unroll
-          for (int j = 0; j < kFusedStage; ++j) {
-            const int i16 = base + j * kFfnThreads + tid;
-            *reinterpret_cast<u32x4*>(i16 < n16 ? l_vec + i16 : lds4) = t4[j];
+            for (int j = 0; j < kFusedStage; ++j) {
+              const int i16 = base + j * kStagers + tid;
+              *reinterpret_cast<u32x4*>(i16 < n16 ? l_vec + i16 : lds4) = t4[j];
+            }
           }
-        }
         __syncthreads();
         OEA_TL(ctrl, 7);
         tB0 = wall_clock64();
       }
 #ifdef OEA_TIMELINE
       , reinterpret_cast<unsigned long long*>(static_cast<char*>(p.h) + (size_t)P * I * 2) + 4096
+#else
+      , nullptr
 #endif
-      );
+      , 0, 0x7fffffff, n_defer);
   if (balanced && tid == 0) {  // this workgroup's speed in this call: cost share per clock tick of streaming
     const unsigned long long tB1 = wall_clock64();
     const float ticks = float((tA1 - tA0) + (tB1 - tB0));
