@@ -30,7 +30,8 @@ typedef enum {
   OEA_ERR_ALIGN = -4,     /* x / weight / workspace pointer not 16-byte aligned */
   OEA_ERR_WORKSPACE = -5, /* workspace_bytes < oea_workspace_bytes(...) */
   OEA_ERR_DTYPE = -6,     /* unknown oea_dtype */
-  OEA_ERR_HIP = -7        /* a HIP runtime call failed (no device, launch failure) */
+  OEA_ERR_HIP = -7,       /* a HIP runtime call failed (no device, launch failure) */
+  OEA_ERR_TIMEOUT = -8    /* oea_workspace_check: a bounded wait inside a kernel gave up */
 } oea_status;
 
 /* storage type of x, W_router, W_gate, W_up, W_down (all the same) */
@@ -163,6 +164,16 @@ int oea_set_kernel_path(int path);
  */
 int oea_read_probe(const void *buf, size_t bytes, void *sink, void *stream);
 
+/*
+ * Host, synchronises `stream`.  The single-kernel layer waits for other workgroups in a few places;
+ * every such wait is bounded, and a workgroup whose wait runs out records that in the workspace
+ * and goes on (the call still returns, with undefined output).  This call reports it: OEA_OK if no
+ * wait has given up on this workspace since oea_workspace_init, else OEA_ERR_TIMEOUT (the record
+ * stays until the workspace is initialised again).  Callers that cannot rule out sharing the
+ * device with other kernels call it after a batch of layers.
+ */
+int oea_workspace_check(const void *workspace, size_t workspace_bytes, void *stream);
+
 /* Optional inputs and taps for moe_decode_ex; every pointer may be NULL. */
 typedef struct {
   const float *router_bias;   /* [N] fp32 added to the logits (synthetic skewed-popularity workload) */
@@ -181,6 +192,8 @@ typedef struct {
   int32_t max_p;              /* general OEA: piggyback only among the max_p best ranks; 0 or >= N = off.
                                  With either set, k plays the role of k_max and the layer runs as three
                                  kernels. */
+  uint32_t spin_limit;        /* test aid: polls after which a wait inside the single kernel gives up
+                                 (0 = the default, about a second) */
 } oea_decode_ex;
 
 /* moe_decode with the extras above (ex == NULL behaves as moe_decode). */

@@ -15,9 +15,9 @@ LIB_PATH = os.path.join(_HERE, "liboea.so")
 OEA_F32, OEA_BF16 = 0, 1
 OEA_OK = 0
 STATUS = {"OEA_ERR_NULL": -1, "OEA_ERR_SHAPE": -2, "OEA_ERR_K": -3, "OEA_ERR_ALIGN": -4,
-          "OEA_ERR_WORKSPACE": -5, "OEA_ERR_DTYPE": -6, "OEA_ERR_HIP": -7}
+          "OEA_ERR_WORKSPACE": -5, "OEA_ERR_DTYPE": -6, "OEA_ERR_HIP": -7, "OEA_ERR_TIMEOUT": -8}
 EXPORTS = ("oea_status_string", "oea_workspace_bytes", "oea_workspace_init", "oea_route", "oea_route_batched", "oea_route_general",
-           "moe_decode", "moe_decode_ex", "oea_set_kernel_path", "oea_read_probe")
+           "moe_decode", "moe_decode_ex", "oea_set_kernel_path", "oea_read_probe", "oea_workspace_check")
 
 
 class OeaError(RuntimeError):
@@ -32,7 +32,7 @@ class DecodeEx(ctypes.Structure):
                 ("gate_w_out", ctypes.c_void_p), ("n_sel_out", ctypes.c_void_p),
                 ("active_list_out", ctypes.c_void_p), ("n_active_out", ctypes.c_void_p),
                 ("h_kernel_events", ctypes.POINTER(ctypes.c_void_p)),
-                ("top_p", ctypes.c_double), ("max_p", ctypes.c_int32)]
+                ("top_p", ctypes.c_double), ("max_p", ctypes.c_int32), ("spin_limit", ctypes.c_uint32)]
 
 
 _lib = None
@@ -60,6 +60,8 @@ def lib():
         L.oea_route_batched.argtypes = [vp, vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
         L.oea_route_general.restype = ci
         L.oea_route_general.argtypes = [vp, vp, ci, ci, ci, ctypes.c_double, ci, ci, vp, vp, vp, vp, vp, vp, vp]
+        L.oea_workspace_check.restype = ci
+        L.oea_workspace_check.argtypes = [vp, sz, vp]
         L.oea_read_probe.restype = ci
         L.oea_read_probe.argtypes = [vp, sz, vp, vp]
         L.moe_decode.restype = ci
@@ -111,8 +113,13 @@ def new_workspace(B, d, N, I, k, device="cuda", stream=None):
     if n == 0:
         raise OeaError(STATUS["OEA_ERR_SHAPE"], status_string(STATUS["OEA_ERR_SHAPE"]))
     ws = torch.empty(n, dtype=torch.uint8, device=device)
-    _check(lib().oea_workspace_init(_ptr(ws), n, _stream(stream)))
+    workspace_init(ws, stream)
     return ws
+
+
+def workspace_init(ws, stream=None):
+    """Prepare (or prepare again) the control words of a workspace."""
+    _check(lib().oea_workspace_init(_ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
 
 
 def oea_route(router_logits, k, k0, stream=None, out=None):
@@ -130,6 +137,11 @@ def oea_route(router_logits, k, k0, stream=None, out=None):
                            _ptr(out["gate_w"]), _ptr(out["n_sel"]), _ptr(out["active_list"]),
                            _ptr(out["n_active"]), _stream(stream)))
     return out
+
+
+def workspace_check(ws, stream=None):
+    """Synchronise and raise OeaError (OEA_ERR_TIMEOUT) if a wait inside a kernel has given up on `ws`."""
+    _check(lib().oea_workspace_check(_ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
 
 
 def read_probe(buf, stream=None):
@@ -180,7 +192,8 @@ def oea_route_general(router_logits, k0, p, k_max, max_p, token_mask=None, strea
 
 
 def moe_decode(x, w_router, w_gate, w_up, w_down, k, k0, workspace, out=None, stream=None,
-               router_bias=None, token_mask=None, taps=False, kernel_events=None, top_p=None, max_p=None):
+               router_bias=None, token_mask=None, taps=False, kernel_events=None, top_p=None, max_p=None,
+               spin_limit=None):
     """One decode-time MoE layer with OEA routing.  Returns out [B,d] float32 (and a dict of routing
     taps when taps=True)."""
     for t in (x, w_router, w_gate, w_up, w_down):
@@ -198,11 +211,13 @@ def moe_decode(x, w_router, w_gate, w_up, w_down, k, k0, workspace, out=None, st
     args = [_ptr(x), _ptr(w_router), _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(out), B, d, N, I, int(k),
             int(k0), dt, _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)]
     if not taps and router_bias is None and token_mask is None and kernel_events is None and top_p is None \
-            and max_p is None:
+            and max_p is None and spin_limit is None:
         _check(lib().moe_decode(*args))
         return out
     ex = DecodeEx()
     tap = None
+    if spin_limit is not None:
+        ex.spin_limit = int(spin_limit)
     if top_p is not None:
         ex.top_p = float(top_p)
     if max_p is not None:

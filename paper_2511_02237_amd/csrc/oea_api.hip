@@ -57,6 +57,7 @@ extern "C" const char* oea_status_string(int status) {
     case OEA_ERR_WORKSPACE: return "workspace too small";
     case OEA_ERR_DTYPE: return "unknown dtype";
     case OEA_ERR_HIP: return "HIP runtime error";
+    case OEA_ERR_TIMEOUT: return "a bounded wait inside a kernel gave up";
     default: return "unknown status";
   }
 }
@@ -105,6 +106,18 @@ extern "C" int oea_workspace_init(void* workspace, size_t workspace_bytes, void*
   hipError_t e =
       launch_fill_zero(static_cast<uint32_t*>(workspace), oea::kCtrlWords, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? OEA_OK : OEA_ERR_HIP;
+}
+
+extern "C" int oea_workspace_check(const void* workspace, size_t workspace_bytes, void* stream) {
+  if (!workspace) return OEA_ERR_NULL;
+  if (!aligned16(workspace)) return OEA_ERR_ALIGN;
+  if (workspace_bytes < oea::kCtrlWords * sizeof(uint32_t)) return OEA_ERR_WORKSPACE;
+  uint32_t gave_up = 0;  // control word 3: set by a workgroup whose wait ran out
+  if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) return OEA_ERR_HIP;
+  if (hipMemcpy(&gave_up, static_cast<const uint32_t*>(workspace) + 3, sizeof(gave_up), hipMemcpyDeviceToHost) !=
+      hipSuccess)
+    return OEA_ERR_HIP;
+  return gave_up ? OEA_ERR_TIMEOUT : OEA_OK;
 }
 
 extern "C" int oea_route(const float* router_logits, int B, int N, int k, int k0, int32_t* expert_idx,
@@ -184,7 +197,8 @@ extern "C" int moe_decode_ex(const void* x, const void* W_router, const void* W_
   if (g_kernel_path == 0 && !general)
     e = try_launch_fused(x, W_router, W_gate, W_up, W_down, ex ? ex->router_bias : nullptr,
                          ex ? ex->token_mask : nullptr, out, logits, h, ro,
-                         reinterpret_cast<uint32_t*>(ws + w.ctrl), B, d, N, I, k, k0, dt, s);
+                         reinterpret_cast<uint32_t*>(ws + w.ctrl), B, d, N, I, k, k0, dt, s,
+                         ex ? ex->spin_limit : 0u);
   if (e == hipSuccess) {  // one kernel: the inner event pairs collapse onto its end
     for (int i = 1; i < 6; ++i)
       if (!mark(i)) return OEA_ERR_HIP;

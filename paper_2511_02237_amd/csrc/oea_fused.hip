@@ -1059,7 +1059,7 @@ hipError_t launch_fused_gather_one(const FusedParams& p, size_t lds_bytes, hipSt
 hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_gate, const void* w_up,
                             const void* w_down, const float* bias, const uint8_t* token_mask, float* out,
                             float* logits, void* h, RouteOut ro, uint32_t* ctrl, int B, int d, int N, int I,
-                            int k, int k0, oea_dtype dt, hipStream_t s) {
+                            int k, int k0, oea_dtype dt, hipStream_t s, uint32_t spin_limit) {
   if (dt != OEA_BF16 || N > 128 || B > 128 || k > 16) return hipErrorNotSupported;
   const bool shape30 = d == 2048 && I == 768, shape235 = d == 4096 && I == 1536;
   if (!shape30 && !shape235) return hipErrorNotSupported;
@@ -1137,7 +1137,7 @@ hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_g
   p.cap_vec1 = (int)cap_vec1;
   p.ecap0 = ecap0;
   p.ecap1 = ecap1;
-  p.spin_limit = 4u << 20;  // polls of >= 100 ns each: gives up after about a second
+  p.spin_limit = spin_limit ? spin_limit : 4u << 20;  // polls of >= 100 ns each: gives up after about a second
   if (gather) {
     if (shape30) return launch_fused_gather_one<uint16_t, 32, 8, 16, 6, 2>(p, lds_bytes, s);
     return launch_fused_gather_one<uint16_t, 64, 8, 32, 6, 2>(p, lds_bytes, s);

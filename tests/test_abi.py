@@ -23,6 +23,7 @@ def L():
     lib.oea_workspace_bytes.argtypes = [ci] * 5
     lib.oea_workspace_init.argtypes = [vp, sz, vp]
     lib.oea_read_probe.argtypes = [vp, sz, vp, vp]
+    lib.oea_workspace_check.argtypes = [vp, sz, vp]
     lib.oea_route.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
     lib.oea_route_batched.argtypes = [vp, vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
     lib.oea_route_general.argtypes = [vp, vp, ci, ci, ci, ctypes.c_double, ci, ci, vp, vp, vp, vp, vp, vp, vp]
@@ -47,11 +48,11 @@ def test_every_declared_symbol_is_exported(L):
 
 def test_status_strings(L):
     seen = set()
-    for code in range(0, -8, -1):
+    for code in range(0, -9, -1):
         s = L.oea_status_string(code).decode()
         assert s and s != "unknown status"
         seen.add(s)
-    assert len(seen) == 8
+    assert len(seen) == 9
     assert L.oea_status_string(-99).decode() == "unknown status"
 
 
@@ -133,6 +134,12 @@ def test_workspace_init_argument_checks(L):
     assert L.oea_workspace_init(None, 1024, None) == -1
     assert L.oea_workspace_init(P + 4, 1024, None) == -4
     assert L.oea_workspace_init(P, 8, None) == -5
+
+
+def test_workspace_check_argument_checks(L):
+    assert L.oea_workspace_check(None, 1 << 20, None) == -1
+    assert L.oea_workspace_check(P + 4, 1 << 20, None) == -4
+    assert L.oea_workspace_check(P, 8, None) == -5
 
 
 def test_read_probe_argument_checks(L):

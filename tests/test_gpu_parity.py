@@ -532,3 +532,26 @@ def test_read_probe_runs_and_leaves_memory_alone(torch, B_):
     B_.read_probe(buf)
     torch.cuda.synchronize()
     assert torch.equal(buf, keep)
+
+
+def test_bounded_waits_report_a_timeout(torch, B_, oracle):
+    """The single-kernel layer never waits forever: with the poll limit forced down to one poll its
+    waits give up at once, every kernel still ends normally, and the workspace says so afterwards."""
+    L = W.make_layer("qwen3_30b", 93, B=4)
+    dev = {f: B_.to_device(getattr(L, f)) for f in ("x", "w_router", "w_gate", "w_up", "w_down")}
+    ws = B_.new_workspace(L.B, L.d, L.N, L.I, L.k)
+    args = (dev["x"], dev["w_router"], dev["w_gate"], dev["w_up"], dev["w_down"], L.k, 2, ws)
+    good = B_.moe_decode(*args).cpu().numpy()
+    B_.workspace_check(ws)  # nothing gave up
+    say("forcing the waits of one call to give up (poll limit 1)")
+    B_.moe_decode(*args, spin_limit=1)
+    with pytest.raises(B_.OeaError) as err:
+        B_.workspace_check(ws)
+    assert err.value.code == -8
+    # the record is sticky until the workspace is prepared again; then the layer is right again
+    B_.workspace_init(ws)
+    again = B_.moe_decode(*args).cpu().numpy()
+    B_.workspace_check(ws)
+    ref = oracle.moe_decode(L.x, L.w_router, L.w_gate, L.w_up, L.w_down, L.k, 2)
+    for got in (good, again):
+        assert np.abs(got - ref["out"]).max() / np.abs(ref["out"]).max() <= TOL[L.dtype]
