@@ -140,11 +140,14 @@ __device__ __forceinline__ int seg_n(const SegView sv, int s) {  // rows of segm
   return n > 0 ? n : 0;
 }
 __device__ __forceinline__ int seg_cnt(const SegView sv, int s) { return s == 0 ? sv.cnt0 : (s == 1 ? sv.cnt1 : sv.cnt2); }
+__device__ __forceinline__ int seg_entries(const SegView sv, int s) {  // buffer entries of segment s
+  return seg_n(sv, s) * seg_cnt(sv, s);
+}
 __device__ __forceinline__ int seg_ebase(const SegView sv, int s) {
-  return (s > 0 ? seg_n(sv, 0) * sv.cnt0 : 0) + (s > 1 ? seg_n(sv, 1) * sv.cnt1 : 0);
+  return (s > 0 ? seg_entries(sv, 0) : 0) + (s > 1 ? seg_entries(sv, 1) : 0);
 }
 __device__ __forceinline__ int result_entries(const SegView sv) {
-  return seg_n(sv, 0) * sv.cnt0 + seg_n(sv, 1) * sv.cnt1 + seg_n(sv, 2) * sv.cnt2;
+  return seg_entries(sv, 0) + seg_entries(sv, 1) + seg_entries(sv, 2);
 }
 __device__ __forceinline__ TileRef tile_ref_buffered(const SegView sv, int r) {
   TileRef t = tile_ref(sv, r);
@@ -285,17 +288,16 @@ __device__ __forceinline__ void flush_results(const SegView sv, const float* ebu
     const int n = seg_n(sv, s), cnt = seg_cnt(sv, s);
     const int rloc = seg_lo(sv, s) - (sv.a0 + s) * sv.rows;
     const int base = seg_ebase(sv, s);
-    if (n > 0)
-      for (int q = 0; q < cnt; ++q) {
-        const int pair = vb + q;
-        for (int r = tid; r < n; r += kFfnThreads) {
-          const float v = ebuf[base + q * n + r];
-          if (STAGE == 0)
-            store_h_coherent(h_out + (size_t)(off0 + pair) * sv.rows + rloc + r, v);
-          else
-            unsafeAtomicAdd(out + (size_t)s_tok[pair] * sv.rows + rloc + r, s_gw[pair] * v);
-        }
-      }
+    // one thread per (pair, row) entry, rows fastest
+    for (int i = tid; i < n * cnt; i += kFfnThreads) {
+      const int q = i / n, r = i - q * n;
+      const int pair = vb + q;
+      const float v = ebuf[base + i];
+      if (STAGE == 0)
+        store_h_coherent(h_out + (size_t)(off0 + pair) * sv.rows + rloc + r, v);
+      else
+        unsafeAtomicAdd(out + (size_t)s_tok[pair] * sv.rows + rloc + r, s_gw[pair] * v);
+    }
     vb += cnt;
   }
 }

@@ -316,43 +316,6 @@ __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_ou
   if (nseg > kMaxSeg || (unsigned)e0 >= (unsigned)N || (unsigned)e1 >= (unsigned)N || (unsigned)e2 >= (unsigned)N)
     wg_has = false;
   const int lo = R0, hi = wg_has ? R1 : R0;
-  const SegView sv0{rows, a0, e0, e1, e2, 0, 0, 0, hi, lo};  // the pair counts are not needed to address weights
-
-  // tile i of the workgroup: the tiles of segment 0, then of segment 1, ...; none crosses an expert boundary
-  const int nt0 = (seg_n(sv0, 0) + TROWS - 1) / TROWS, nt1 = (seg_n(sv0, 1) + TROWS - 1) / TROWS;
-  const int nt2 = (seg_n(sv0, 2) + TROWS - 1) / TROWS;
-  auto take_tile = [&](int& r, int& n) __attribute__((always_inline)) {
-    int i = 0;
-    if (lane == 0) i = int(atomicAdd(l_next, 1u));
-    i = uniform(i);
-    const int s = i < nt0 ? 0 : (i < nt0 + nt1 ? 1 : 2);
-    const int j = i - (s > 0 ? nt0 : 0) - (s > 1 ? nt1 : 0);
-    r = seg_lo(sv0, s) + j * TROWS;
-    n = i < nt0 + nt1 + nt2 ? tile_rows(sv0, r, TROWS) : 0;
-    if (n <= 0) r = lo;
-  };
-
-  uint4 wA[NM][RG][NCH], wB[NM][RG][NCH];
-  int rA = lo, nA = 0, rB = lo, nB = 0;
-  // The first n_defer wavefronts request nothing before mid: what they load IN mid (polled counters,
-  // staged vectors) then does not queue behind two weight tiles (loads return in issue order).
-  const bool deferred = uniform(tid >> 6) < n_defer;
-  if (wg_has && !deferred) {  // a wavefront that finds no tile requests a placeholder
-    take_tile(rA, nA);
-    take_tile(rB, nB);
-    load_tile<WT, NM, LPR, NCH, RG, true>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv0, rA), nA);
-    load_tile<WT, NM, LPR, NCH, RG, true>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv0, rB), nB);
-  }
-  __builtin_amdgcn_sched_barrier(0);  // the requests above are issued before anything in mid
-
-  mid(a0, wg_has ? nseg : 0);
-
-  if (wg_has && deferred) {
-    take_tile(rA, nA);
-    take_tile(rB, nB);
-    load_tile<WT, NM, LPR, NCH, RG, true>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv0, rA), nA);
-    load_tile<WT, NM, LPR, NCH, RG, true>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv0, rB), nB);
-  }
 
   // pair lists of this workgroup's experts
   const int off0 = uniform(l_off[a0]);
@@ -370,11 +333,54 @@ __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_ou
   const int n0 = clip(0, off1 - off0), n1 = clip(off1 - off0, off2 - off0), n2 = clip(off2 - off0, off3 - off0);
   if (n0 + n1 + n2 > cap_vec) wg_has = false;  // the caller staged at most cap_vec vectors
   const int base = wg_has ? off0 + q0 : 0;     // first pair of the piece
-  const SegView sv{rows, a0, e0, e1, e2, n0, n1, n2, hi, lo};
+  const int hi_w = wg_has ? hi : lo;
+  const SegView sv{rows, a0, e0, e1, e2, n0, n1, n2, hi_w, lo};
   const int* const s_tok = l_tok + base;
   const float* const s_gw = l_gw + base;
   const int n_res = result_entries(sv);
   const bool use_buf = n_res <= ecap * kFfnWaves;
+
+  // tile i of the workgroup: the tiles of segment 0, then of segment 1, ...; none crosses an expert boundary
+  const int nt0 = (seg_n(sv, 0) + TROWS - 1) / TROWS, nt1 = (seg_n(sv, 1) + TROWS - 1) / TROWS;
+  const int nt2 = (seg_n(sv, 2) + TROWS - 1) / TROWS;
+  // The wavefronts that start right away take their first two tiles by number (tile w, then tile
+  // nw + w): with few tiles everybody gets one before anybody gets two.  The counter hands out the
+  // tiles behind those (i < 0: the next tile from the counter).
+  const int wave = uniform(tid >> 6);
+  const bool deferred = wave < n_defer;  // see below
+  const int nw = kFfnWaves - n_defer;
+  auto take_tile = [&](int& r, int& n, int i = -1) __attribute__((always_inline)) {
+    if (i < 0) {
+      if (lane == 0) i = 2 * nw + int(atomicAdd(l_next, 1u));
+      i = uniform(i);
+    }
+    const int sgm = i < nt0 ? 0 : (i < nt0 + nt1 ? 1 : 2);
+    const int j = i - (sgm > 0 ? nt0 : 0) - (sgm > 1 ? nt1 : 0);
+    r = seg_lo(sv, sgm) + j * TROWS;
+    n = i < nt0 + nt1 + nt2 ? tile_rows(sv, r, TROWS) : 0;
+    if (n <= 0) r = lo;
+  };
+
+  uint4 wA[NM][RG][NCH], wB[NM][RG][NCH];
+  int rA = lo, nA = 0, rB = lo, nB = 0;
+  // The first n_defer wavefronts request nothing before mid: what they load IN mid (polled counters,
+  // staged vectors) then does not queue behind two weight tiles (loads return in issue order).
+  if (wg_has && !deferred) {  // a wavefront that finds no tile requests a placeholder
+    take_tile(rA, nA, wave - n_defer);
+    take_tile(rB, nB, nw + wave - n_defer);
+    load_tile<WT, NM, LPR, NCH, RG, true>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv, rA), nA);
+    load_tile<WT, NM, LPR, NCH, RG, true>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv, rB), nB);
+  }
+  __builtin_amdgcn_sched_barrier(0);  // the requests above are issued before anything in mid
+
+  mid(a0, wg_has ? nseg : 0);
+
+  if (wg_has && deferred) {
+    take_tile(rA, nA);
+    take_tile(rB, nB);
+    load_tile<WT, NM, LPR, NCH, RG, true>(wA, wa, wb, rows, L, lsub, lrow, tile_ref(sv, rA), nA);
+    load_tile<WT, NM, LPR, NCH, RG, true>(wB, wa, wb, rows, L, lsub, lrow, tile_ref(sv, rB), nB);
+  }
 
   if (wg_has && nA > 0) {
     while (true) {
@@ -609,11 +615,7 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   const int cap_vec = p.cap_vec;
   unsigned long long tB0 = 0;
   const int n_defer = 2 * T <= N ? kStageWaves : 1;
-  fused_stage<WT, 1, LPR1, NCH1, 2>(
-      static_cast<const WT*>(p.w_down), static_cast<const WT*>(nullptr), static_cast<WT*>(nullptr), p.out, d, I, RB0,
-      RB1, N, P, p.cap_vec, l_active, l_off, l_tok, l_gw, l_vec,
-      reinterpret_cast<float*>(l_vec + (size_t)cap_vec * I16), p.ecap1, reinterpret_cast<uint32_t*>(l_nact + 2),
-      [&](int a0, int nseg) {  // runs once the first weight tiles are requested
+  auto mid_b = [&](int a0, int nseg) {  // runs once the first weight tiles are requested
         OEA_TL(ctrl, 5);
         // No grid barrier here: this workgroup only needs the hidden vectors of ITS experts, which
         // its neighbours produce (both stages cut the expert list in about the same proportions).
@@ -658,7 +660,11 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
         __syncthreads();
         OEA_TL(ctrl, 7);
         tB0 = wall_clock64();
-      }
+      };
+  fused_stage<WT, 1, LPR1, NCH1, 2>(
+      static_cast<const WT*>(p.w_down), static_cast<const WT*>(nullptr), static_cast<WT*>(nullptr), p.out, d, I, RB0,
+      RB1, N, P, p.cap_vec, l_active, l_off, l_tok, l_gw, l_vec,
+      reinterpret_cast<float*>(l_vec + (size_t)cap_vec * I16), p.ecap1, reinterpret_cast<uint32_t*>(l_nact + 2), mid_b
 #ifdef OEA_TIMELINE
       , reinterpret_cast<unsigned long long*>(static_cast<char*>(p.h) + (size_t)P * I * 2) + 4096
 #else
