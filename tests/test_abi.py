@@ -153,3 +153,13 @@ def test_binding_module_names_match_the_abi():
     assert set(binding.EXPORTS) == set(declared_functions())
     for n in ("oea_route", "moe_decode", "workspace_bytes", "new_workspace", "status_string"):
         assert hasattr(binding, n)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is a one-GPU measurement: --gpus N > 1 exits with a message before touching a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
