@@ -56,7 +56,8 @@ def assert_routing_equal(got, ref, ctx):
 
 ROUTE_CASES = [(B, N, k, k0, kind, seed)
                for (B, N, k) in [(4, 16, 4), (16, 128, 8), (3, 7, 5), (33, 64, 6), (1, 128, 8), (128, 128, 8),
-                                 (16, 100, 8), (7, 200, 12), (5, 512, 32), (200, 130, 8), (16, 1, 1)]
+                                 (16, 100, 8), (7, 200, 12), (5, 512, 32), (200, 130, 8), (16, 1, 1),
+                                 (1024, 128, 8), (1024, 512, 32)]  # the last two: the size limits of the entry point
                for k0 in sorted({1, max(1, k // 2), k})
                for kind in W.LOGIT_KINDS
                for seed in (0, 1)]
