@@ -145,7 +145,7 @@ def test_small_layers_all_k0(torch, B_, oracle, name):
             say(ctx, "T=%d err=%.2e" % (int(tap["n_active"][0]), err))
 
 
-@pytest.mark.parametrize("B", [1, 2, 5, 16, 33, 64])
+@pytest.mark.parametrize("B", [1, 2, 5, 16, 33, 64, 300, 1024])  # 1024: the batch limit of the entry point
 def test_batch_sizes_mid_shape(torch, B_, oracle, B):
     L = W.make_layer("mid_bf16", 200 + B, B=B)
     for k0 in (1, 3, 6):
