@@ -244,6 +244,25 @@ def test_full_size_30b_shape(torch, B_, oracle, name, seeds):
             say(ctx, "T=%d sum_n_sel=%d err=%.2e" % (ref["n_active"], int(ref["n_sel"].sum()), err))
 
 
+def test_full_size_30b_every_k0_and_odd_batches(torch, B_, oracle):
+    """Single-kernel path at the benchmark shape: every k0 from 1 to k at B=16, and batches of 3 and 7
+    tokens cut from the same layer (a workgroup then owns rows of experts with a single pair)."""
+    L, dev = big_layer(B_, "qwen3_30b", 2000)
+    for B in (16, 7, 3):
+        ws = B_.new_workspace(B, L.d, L.N, L.I, L.k)
+        x_dev = dev["x"][:B].contiguous()
+        for k0 in range(1, L.k + 1):
+            out, tap = B_.moe_decode(x_dev, dev["w_router"], dev["w_gate"], dev["w_up"], dev["w_down"], L.k, k0, ws,
+                                     taps=True)
+            torch.cuda.synchronize()
+            ref = oracle.moe_decode(L.x[:B], L.w_router, L.w_gate, L.w_up, L.w_down, L.k, k0)
+            ctx = "qwen3_30b B=%d k0=%d" % (B, k0)
+            assert_routing_equal({n: v.cpu().numpy() for n, v in tap.items()}, ref, ctx)
+            err = np.abs(out.cpu().numpy() - ref["out"]).max() / np.abs(ref["out"]).max()
+            assert err <= TOL[L.dtype], "%s: %.3e" % (ctx, err)
+        B_.workspace_check(ws)
+
+
 @pytest.mark.parametrize("path", [2, 1])
 def test_full_size_30b_shape_three_kernel_paths(torch, B_, oracle, path):
     """Same layer through the three-kernel paths (streaming / generic expert kernels)."""
