@@ -279,11 +279,12 @@ __device__ __forceinline__ void balance_shares(uint32_t* ctrl, uint32_t parity, 
 // One mat-vec stage of the fused kernel.  Same tile loop as expert_stream_kernel; the routing
 // metadata comes from LDS, and `mid` runs once the first two weight tiles are in flight (it holds
 // the wait for the hidden vectors and their staging for the down stage).  Every workgroup calls mid.
+// The first n_defer wavefronts request their tiles only after mid (see below).
 //
 // The workgroup's rows [R0,R1) are cut into tiles that the wavefronts TAKE one at a time from a
 // counter in LDS (l_next, zero on entry) instead of owning fixed shares: measured with fixed shares,
 // the four wavefronts that start second on their SIMDs stream about 15 % slower than the first four,
-// and the workgroup waited for them.
+// and the workgroup waited for them.  Only a wavefront's first two tiles are fixed.
 // Results are collected in an LDS buffer and written out after the last tile: a store or atomic
 // issued between the weight loads would have to complete (the memory counter retires in order)
 // before the NEXT tile's data counts as arrived.  If they do not fit (many rows of a very popular
