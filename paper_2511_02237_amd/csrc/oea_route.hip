@@ -11,9 +11,12 @@ constexpr int kRouteThreads = 1024;
 // One workgroup routes one decode position (blockIdx.x): its B rows of logits and its own output slices.
 // Positions are independent (Section 4: every position and layer is routed separately), so a grid
 // of L workgroups routes L positions in one launch.
-template <int NV>
-__global__ __launch_bounds__(kRouteThreads) void route_kernel(const float* logits, const uint8_t* token_mask,
-                                                              int B, int N, int k, int k0, RouteOut o) {
+// NT threads (>= N): 1024 for one or few positions (most parallelism for a single routing); 256 for
+// many positions of a small batch, where four wavefronts hold the 16 token rows and four times as
+// many positions are resident per compute unit.
+template <int NV, int NT>
+__global__ __launch_bounds__(NT) void route_kernel(const float* logits, const uint8_t* token_mask, int B, int N,
+                                                   int k, int k0, RouteOut o) {
   extern __shared__ uint32_t lds[];
   const size_t pos = blockIdx.x;
   logits += pos * B * N;
@@ -23,17 +26,17 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const float* logit
   o.n_sel += pos * B;
   o.active_list += pos * N;
   o.n_active += pos;
-  if (NV <= 2 && k <= 16 && B <= 4 * (kRouteThreads / 64)) {
+  if (NV <= 2 && k <= 16 && B <= 4 * (NT / 64)) {
     // few experts: one DPP row of 16 lanes per token, four tokens per wavefront
     RowCarry<4 * NV> c;
-    route_union_rows<4 * NV, kRouteThreads>(logits, token_mask, B, N, k0, o, lds, c);
-    route_fill_rows<4 * NV, kRouteThreads>(B, N, k, k0, o, lds, c);
+    route_union_rows<4 * NV, NT>(logits, token_mask, B, N, k0, o, lds, c);
+    route_fill_rows<4 * NV, NT>(B, N, k, k0, o, lds, c);
   } else if (NV <= 2 && k <= 16) {
-    route_rows_any<4 * NV, kRouteThreads>(logits, token_mask, B, N, k, k0, o, lds);
-  } else if (B <= kRouteThreads / 64) {
-    route_block<NV, kRouteThreads, 1>(logits, token_mask, B, N, k, k0, o, lds);
+    route_rows_any<4 * NV, NT>(logits, token_mask, B, N, k, k0, o, lds);
+  } else if (B <= NT / 64) {
+    route_block<NV, NT, 1>(logits, token_mask, B, N, k, k0, o, lds);
   } else {
-    route_block<NV, kRouteThreads, 0>(logits, token_mask, B, N, k, k0, o, lds);
+    route_block<NV, NT, 0>(logits, token_mask, B, N, k, k0, o, lds);
   }
 }
 
@@ -144,27 +147,31 @@ hipError_t launch_fill_zero(uint32_t* p, size_t n_words, hipStream_t s) {
   return hipGetLastError();
 }
 
+template <int NV, int NT>
+static hipError_t launch_route_one(const float* logits, const uint8_t* token_mask, int L, int B, int N, int k, int k0,
+                                   RouteOut o, size_t lds, hipStream_t s) {
+  if (lds > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&route_kernel<NV, NT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((route_kernel<NV, NT>), dim3(L), dim3(NT), lds, s, logits, token_mask, B, N, k, k0, o);
+  return hipGetLastError();
+}
+
 hipError_t launch_route(const float* logits, const uint8_t* token_mask, int L, int B, int N, int k, int k0,
                         RouteOut o, hipStream_t s) {
   const size_t lds = route_lds_bytes(B, N);
+  // many positions of a small batch: small workgroups (the row-per-token routing needs B <= 16 for 256 threads)
+  const bool small = L >= 8 && B <= 16 && N <= 128 && k <= 16;
   switch (nv_for(N)) {
-#define OEA_CASE(NV)                                                                                      \
-  case NV: {                                                                                              \
-    if (lds > 48 * 1024) {                                                                                \
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&route_kernel<NV>),                \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);           \
-      if (e != hipSuccess) return e;                                                                      \
-    }                                                                                                     \
-    hipLaunchKernelGGL(route_kernel<NV>, dim3(L), dim3(kRouteThreads), lds, s, logits, token_mask, B, N, k, \
-                       k0, o);                                                                            \
-  } break;
-    OEA_CASE(1)
-    OEA_CASE(2)
-    OEA_CASE(4)
-    OEA_CASE(8)
-#undef OEA_CASE
+    case 1: return small ? launch_route_one<1, 256>(logits, token_mask, L, B, N, k, k0, o, lds, s)
+                         : launch_route_one<1, kRouteThreads>(logits, token_mask, L, B, N, k, k0, o, lds, s);
+    case 2: return small ? launch_route_one<2, 256>(logits, token_mask, L, B, N, k, k0, o, lds, s)
+                         : launch_route_one<2, kRouteThreads>(logits, token_mask, L, B, N, k, k0, o, lds, s);
+    case 4: return launch_route_one<4, kRouteThreads>(logits, token_mask, L, B, N, k, k0, o, lds, s);
+    default: return launch_route_one<8, kRouteThreads>(logits, token_mask, L, B, N, k, k0, o, lds, s);
   }
-  return hipGetLastError();
 }
 
 template <typename WT>
