@@ -46,6 +46,9 @@ def parse():
                                                 "and fit latency = c + b*T + a*pairs instead of the one-line report")
     ap.add_argument("--launch", default="stream", choices=["stream", "graph"],
                     help="timed steps launched one by one, or captured into one HIP graph and replayed (measured: same latency)")
+    ap.add_argument("--route-positions", type=int, default=0,
+                    help="instead of the layer: time oea_route_batched over this many decode positions of the workload's "
+                         "B, N, k at --k0 (the routing step alone, as a simulation over a trace would call it)")
     ap.add_argument("--verbose", action="store_true")
     return ap.parse_args()
 
@@ -102,7 +105,39 @@ def main():
     args = parse()
     if args.sweep:
         return sweep(args)
+    if args.route_positions:
+        return route_throughput(args)
     print(json.dumps(run(args)))
+
+
+def route_throughput(args):
+    """Routing alone: L independent decode positions (Section 4 of the paper routes every position of
+    a sequence separately) in one launch of oea_route_batched, on seeded Gaussian logits."""
+    import torch
+
+    from paper_2511_02237_amd import binding, workloads
+    assert args.gpus == 1 and torch.cuda.is_available()
+    cfg = workloads.CONFIGS[args.workload]
+    N, k, B, L = cfg["N"], cfg["k"], args.batch, args.route_positions
+    g = torch.Generator(device="cuda")
+    g.manual_seed(777)
+    lg = torch.randn((L, B, N), generator=g, device="cuda", dtype=torch.float32)
+    for _ in range(args.warmup):
+        res = binding.oea_route_batched(lg, k, args.k0)
+    torch.cuda.synchronize()
+    t_a = time.perf_counter()
+    for _ in range(args.steps):
+        binding.oea_route_batched(lg, k, args.k0)
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t_a) / args.steps * 1e6
+    moved = L * (B * N * 4 + 2 * B * k * 4 + B * 4 + N * 4 + 4)  # logits in; indices, weights, counts, active list out
+    print(json.dumps(dict(metric="OEA routing throughput (decode positions / s), B=%d N=%d k=%d k0=%d" % (B, N, k, args.k0),
+                          value=round(L / us * 1e6, 1), unit="positions/s", n_gpus=1, steps=args.steps,
+                          warmup=args.warmup, ms_per_step=round(us / 1e3, 6), higher_is_better=True, dtype="f32",
+                          data="synthetic", config=dict(workload="%d positions of %s routing" % (L, args.workload)),
+                          mean_unique_experts=round(float(res["n_active"].float().mean().item()), 2),
+                          bytes_moved=moved, GBps=round(moved / us / 1e3, 1),
+                          frac_of_hbm_peak=round(moved / us / 1e3 / HBM_PEAK_GBS, 4))))
 
 
 def sweep(args):
