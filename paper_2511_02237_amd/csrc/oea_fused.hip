@@ -642,8 +642,9 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
         const int n16 = nvec * I16;
         __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<WT*>(hsrc + (size_t)off0 * I), 0, n16 * 16, 0x00020000);
-        // staged by the wavefronts that have no weight tiles in flight
-        const int kStagers = n_defer * 64;
+        // staged by the wavefronts that have no weight tiles in flight, unless that would take them
+        // more than two rounds of loads (many pairs): then by everybody
+        const int kStagers = n16 <= 2 * kFusedStage * n_defer * 64 ? n_defer * 64 : kFfnThreads;
         if (tid < kStagers)
           for (int base = 0; base < n16; base += kFusedStage * kStagers) {
             u32x4 t4[kFusedStage];
