@@ -481,6 +481,23 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   // ---- phase R1.  x of the batch -> LDS: loads first, written after the logits
   const int d16 = d / EPL;
   const int n16_x = B * d16;
+  // the operands of this wavefront's (first) logit are requested first: loads return in issue
+  // order, and the logits are what the other workgroups wait for
+  constexpr int XC = LPR0 * NCH0 / 64;  // 16-byte chunks of a row per lane (d == LPR0 * EPL * NCH0)
+  const WT* const wr = static_cast<const WT*>(p.w_router);
+  const int idx0 = wg * kFfnWaves + wave;
+  const bool has0 = idx0 < B * N;
+  uint4 la[XC], lb[XC];
+  {
+    const int ii = has0 ? idx0 : 0;
+    const int t = ii / N, e = ii - t * N;
+#pragma unroll
+    for (int c = 0; c < XC; ++c) {
+      la[c] = *reinterpret_cast<const uint4*>(x + (size_t)t * d + (lane + 64 * c) * EPL);
+      lb[c] = *reinterpret_cast<const uint4*>(wr + (size_t)e * d + (lane + 64 * c) * EPL);
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
   u32x4 stg[kFusedStage];
   {
     const u32x4* src = reinterpret_cast<const u32x4*>(x);
@@ -508,8 +525,18 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
 
   // router logits: one (token, expert) dot product per wavefront, fp64 accumulation, one rounding
   {
-    const WT* const wr = static_cast<const WT*>(p.w_router);
-    for (int idx = wg * kFfnWaves + wave; idx < B * N; idx += G * kFfnWaves) {
+    if (has0) {
+      double acc = 0.0;
+#pragma unroll
+      for (int c = 0; c < XC; ++c) acc = frag_dot_f64<WT>(la[c], lb[c], acc);
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
+      if (lane == 0) {
+        if (p.bias) acc += double(p.bias[idx0 % N]);
+        __hip_atomic_store(p.logits + idx0, float(acc), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+    for (int idx = idx0 + G * kFfnWaves; idx < B * N; idx += G * kFfnWaves) {
       const int t = idx / N, e = idx - t * N;
       const WT* xr = x + (size_t)t * d;
       const WT* wre = wr + (size_t)e * d;
