@@ -535,36 +535,49 @@ __device__ void route_block(const float* __restrict__ logits, const uint8_t* __r
 template <int NK, int NT, bool COHERENT = false>
 __device__ void route_rows_any(const float* __restrict__ logits, const uint8_t* __restrict__ token_mask, int B,
                                int N, int k, int k0, RouteOut o, uint32_t* lds) {
-  auto logit_at = [&](int t, int e) __attribute__((always_inline)) {  // COHERENT: see route_union_rows
-    const float* src = logits + (size_t)t * N + e;
-    return COHERENT ? __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *src;
-  };
   constexpr int GROUP = 4 * (NT / 64);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int li = lane & 15, row = lane >> 4;
   const int NWB = (B + 31) >> 5;
   uint32_t* U = lds;
   uint32_t* colmask = lds + 64;
+  // the logits of the row's token in group t0 (clamped addresses: every lane loads, all in flight
+  // together).  COHERENT: see route_union_rows.  The next group's are requested before the current
+  // group's selection rounds, so that only the first load of each phase is waited for.
+  auto load_group = [&](float (&lg)[NK], int t0) __attribute__((always_inline)) {
+    const int t = t0 + wave * 4 + row;
+    const float* src = logits + (size_t)(t < B ? t : B - 1) * N;
+#pragma unroll
+    for (int j = 0; j < NK; ++j) {
+      const int e = li + 16 * j;
+      const float* q = src + (e < N ? e : N - 1);
+      lg[j] = COHERENT ? __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *q;
+    }
+  };
 
+  float cur[NK], nxt[NK];
+  load_group(cur, 0);
   for (int i = tid; i < int(route_lds_words(B, N)); i += NT) lds[i] = 0;
   __syncthreads();
   for (int t0 = 0; t0 < B; t0 += GROUP) {  // ---- Phase 1: baselines and their union
+    // after the last group: the first group again, for Phase 2
+    load_group(nxt, t0 + GROUP < B ? t0 + GROUP : 0);
     const int t = t0 + wave * 4 + row;
     const bool live = t < B && !(token_mask && token_mask[t] == 0);
     RowCarry<NK> c;
     c.n = 0;
     c.sel_id = c.sel_key = c.top_key = 0;
 #pragma unroll
-    for (int j = 0; j < NK; ++j) {
-      const int e = li + 16 * j;
-      c.key[j] = (live && e < N) ? make_key(logit_at(t, e)) : 0;
-    }
+    for (int j = 0; j < NK; ++j) c.key[j] = (live && li + 16 * j < N) ? make_key(cur[j]) : 0;
     for (int r = 0; r < k0; ++r) row_pick<NK>(c, li, r);
     if (li < c.n) atomicOr(&U[c.sel_id >> 5], 1u << (c.sel_id & 31));
+#pragma unroll
+    for (int j = 0; j < NK; ++j) cur[j] = nxt[j];
   }
   __syncthreads();
   route_active<NT>(N, o, lds);
   for (int t0 = 0; t0 < B; t0 += GROUP) {  // ---- Phase 2 in closed form, weights
+    if (t0 + GROUP < B) load_group(nxt, t0 + GROUP);
     const int t = t0 + wave * 4 + row;
     const bool have = t < B;
     const bool live = have && !(token_mask && token_mask[t] == 0);
@@ -575,7 +588,7 @@ __device__ void route_rows_any(const float* __restrict__ logits, const uint8_t* 
     for (int j = 0; j < NK; ++j) {
       const int e = li + 16 * j;
       const bool cand = live && e < N && ((U[e >> 5] >> (e & 31)) & 1u);
-      c.key[j] = cand ? make_key(logit_at(t, e)) : 0;
+      c.key[j] = cand ? make_key(cur[j]) : 0;
     }
     for (int r = 0; r < k; ++r) row_pick<NK>(c, li, r);
     const float w = li < c.n ? expf(from_orderable(c.sel_key) - from_orderable(c.top_key)) : 0.f;
@@ -588,6 +601,8 @@ __device__ void route_rows_any(const float* __restrict__ logits, const uint8_t* 
       if (li < c.n) atomicOr(&colmask[c.sel_id * NWB + (t >> 5)], 1u << (t & 31));
       if (li == 0) o.n_sel[t] = c.n;
     }
+#pragma unroll
+    for (int j = 0; j < NK; ++j) cur[j] = nxt[j];
   }
   __syncthreads();
   route_group<NT>(B, N, k, o, lds);
