@@ -803,7 +803,7 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedPara
 
   if (tid == 0) l_nact[1] = l_nact[2] = 0;
   const RouteOut lo{l_idx, l_gatew, l_nsel, l_active, l_nact, l_off, l_tok, l_gw};
-  route_rows_any<4 * NV, kFfnThreads, true>(p.logits, p.token_mask, B, N, k, p.k0, lo, l_route);
+  route_rows_groups<4 * NV, kFfnThreads, 4, true>(p.logits, p.token_mask, B, N, k, p.k0, lo, l_route);  // B <= 128
   __syncthreads();
   if (wg == 0) {  // publish the routing result
     for (int i = tid; i < P; i += kFfnThreads) {

@@ -608,6 +608,81 @@ __device__ void route_rows_any(const float* __restrict__ logits, const uint8_t* 
   route_group<NT>(B, N, k, o, lds);
 }
 
+// The same for up to MAXG token groups with the candidate keys KEPT in registers between the phases
+// (as route_union_rows / route_fill_rows do for one group): Phase 2 continues after the k0 picks
+// of Phase 1 instead of starting over, and the logits are read once.  B <= MAXG * 4 * NT/64.
+template <int NK, int NT, int MAXG, bool COHERENT = false>
+__device__ void route_rows_groups(const float* __restrict__ logits, const uint8_t* __restrict__ token_mask, int B,
+                                  int N, int k, int k0, RouteOut o, uint32_t* lds) {
+  constexpr int GROUP = 4 * (NT / 64);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 15, row = lane >> 4;
+  const int NWB = (B + 31) >> 5;
+  uint32_t* U = lds;
+  uint32_t* colmask = lds + 64;
+  auto load_group = [&](float (&lg)[NK], int t0) __attribute__((always_inline)) {
+    const int t = t0 + wave * 4 + row;
+    const float* src = logits + (size_t)(t < B ? t : B - 1) * N;
+#pragma unroll
+    for (int j = 0; j < NK; ++j) {
+      const int e = li + 16 * j;
+      const float* q = src + (e < N ? e : N - 1);
+      lg[j] = COHERENT ? __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *q;
+    }
+  };
+
+  RowCarry<NK> c[MAXG];
+  float cur[NK], nxt[NK];
+  load_group(cur, 0);
+  for (int i = tid; i < int(route_lds_words(B, N)); i += NT) lds[i] = 0;
+  __syncthreads();
+#pragma unroll
+  for (int g = 0; g < MAXG; ++g) {  // ---- Phase 1: baselines and their union
+    const int t0 = g * GROUP;
+    if (t0 < B) {
+      if (t0 + GROUP < B) load_group(nxt, t0 + GROUP);  // requested before this group's rounds
+      const int t = t0 + wave * 4 + row;
+      const bool live = t < B && !(token_mask && token_mask[t] == 0);
+      c[g].t = t < B ? t : -1;
+      c[g].n = 0;
+      c[g].sel_id = c[g].sel_key = c[g].top_key = 0;
+#pragma unroll
+      for (int j = 0; j < NK; ++j) c[g].key[j] = (live && li + 16 * j < N) ? make_key(cur[j]) : 0;
+      for (int r = 0; r < k0; ++r) row_pick<NK>(c[g], li, r);
+      if (li < c[g].n) atomicOr(&U[c[g].sel_id >> 5], 1u << (c[g].sel_id & 31));
+#pragma unroll
+      for (int j = 0; j < NK; ++j) cur[j] = nxt[j];
+    }
+  }
+  __syncthreads();
+  route_active<NT>(N, o, lds);
+#pragma unroll
+  for (int g = 0; g < MAXG; ++g) {  // ---- Phase 2: continue on the candidates that are in U, up to k picks
+    if (g * GROUP < B) {
+#pragma unroll
+      for (int j = 0; j < NK; ++j) {
+        const int e = li + 16 * j;  // e < 16*NK <= 512: inside U's 16 words
+        if (!((U[e >> 5] >> (e & 31)) & 1u)) c[g].key[j] = 0;
+      }
+      // a live token holds exactly k0 picks here (k0 <= N), so the next rank is the round number
+      for (int r = k0; r < k; ++r) row_pick<NK>(c[g], li, r);
+      const float w = li < c[g].n ? expf(from_orderable(c[g].sel_key) - from_orderable(c[g].top_key)) : 0.f;
+      const float z = row_sum_f32(w);
+      if (c[g].t >= 0) {
+        const int t = c[g].t;
+        if (li < k) {
+          o.expert_idx[(size_t)t * k + li] = li < c[g].n ? int(c[g].sel_id) : -1;
+          o.gate_w[(size_t)t * k + li] = li < c[g].n ? w / z : 0.f;
+        }
+        if (li < c[g].n) atomicOr(&colmask[c[g].sel_id * NWB + (t >> 5)], 1u << (t & 31));
+        if (li == 0) o.n_sel[t] = c[g].n;
+      }
+    }
+  }
+  __syncthreads();
+  route_group<NT>(B, N, k, o, lds);
+}
+
 // ---------------------------------------------------------------------------------------------
 // General OEA (Algorithm 2 of the paper): the baseline of a token is cut by a top-p rule as well
 // (n_i = min(k0, t_i), t_i = least t whose t best experts hold softmax mass >= p), piggybacking
