@@ -31,6 +31,8 @@ __global__ __launch_bounds__(NT) void route_kernel(const float* logits, const ui
     RowCarry<4 * NV> c;
     route_union_rows<4 * NV, NT>(logits, token_mask, B, N, k0, o, lds, c);
     route_fill_rows<4 * NV, NT>(B, N, k, k0, o, lds, c);
+  } else if (NV <= 2 && k <= 16 && B <= 16 * (NT / 64)) {
+    route_rows_groups<4 * NV, NT, 4>(logits, token_mask, B, N, k, k0, o, lds);  // up to four groups, keys kept
   } else if (NV <= 2 && k <= 16) {
     route_rows_any<4 * NV, NT>(logits, token_mask, B, N, k, k0, o, lds);
   } else if (B <= NT / 64) {
@@ -119,6 +121,8 @@ __global__ __launch_bounds__(kRouteThreads) void router_route_kernel(
     RowCarry<4 * NV> c;  // few experts: one DPP row of 16 lanes per token
     route_union_rows<4 * NV, kRouteThreads>(logits, token_mask, B, N, k0, o, lds, c);
     route_fill_rows<4 * NV, kRouteThreads>(B, N, k, k0, o, lds, c);
+  } else if (NV <= 2 && k <= 16 && B <= 16 * (kRouteThreads / 64)) {
+    route_rows_groups<4 * NV, kRouteThreads, 4>(logits, token_mask, B, N, k, k0, o, lds);
   } else if (NV <= 2 && k <= 16) {
     route_rows_any<4 * NV, kRouteThreads>(logits, token_mask, B, N, k, k0, o, lds);
   } else if (B <= kRouteThreads / 64)
