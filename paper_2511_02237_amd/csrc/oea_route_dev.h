@@ -608,9 +608,9 @@ __device__ void route_rows_any(const float* __restrict__ logits, const uint8_t* 
   route_group<NT>(B, N, k, o, lds);
 }
 
-// The same for up to MAXG token groups with the candidate keys KEPT in registers between the phases
-// (as route_union_rows / route_fill_rows do for one group): Phase 2 continues after the k0 picks
-// of Phase 1 instead of starting over, and the logits are read once.  B <= MAXG * 4 * NT/64.
+// The same for up to MAXG token groups with the candidate keys of ALL groups in registers (as
+// route_union_rows / route_fill_rows hold one group's): the logits are read once, Phase 2 continues
+// after the k0 picks of Phase 1 instead of starting over.  B <= MAXG * 4 * NT/64.
 template <int NK, int NT, int MAXG, bool COHERENT = false>
 __device__ void route_rows_groups(const float* __restrict__ logits, const uint8_t* __restrict__ token_mask, int B,
                                   int N, int k, int k0, RouteOut o, uint32_t* lds) {
@@ -631,41 +631,55 @@ __device__ void route_rows_groups(const float* __restrict__ logits, const uint8_
     }
   };
 
+  // The groups' selection rounds are independent chains of dependent instructions: they are
+  // interleaved round by round, which hides most of each chain's latency.
   RowCarry<NK> c[MAXG];
-  float cur[NK], nxt[NK];
-  load_group(cur, 0);
   for (int i = tid; i < int(route_lds_words(B, N)); i += NT) lds[i] = 0;
-  __syncthreads();
 #pragma unroll
-  for (int g = 0; g < MAXG; ++g) {  // ---- Phase 1: baselines and their union
-    const int t0 = g * GROUP;
-    if (t0 < B) {
-      if (t0 + GROUP < B) load_group(nxt, t0 + GROUP);  // requested before this group's rounds
-      const int t = t0 + wave * 4 + row;
+  for (int g = 0; g < MAXG; ++g) {
+    if (g * GROUP < B) {  // uniform over the workgroup
+      float lg[NK];
+      load_group(lg, g * GROUP);
+      const int t = g * GROUP + wave * 4 + row;
       const bool live = t < B && !(token_mask && token_mask[t] == 0);
       c[g].t = t < B ? t : -1;
       c[g].n = 0;
       c[g].sel_id = c[g].sel_key = c[g].top_key = 0;
 #pragma unroll
-      for (int j = 0; j < NK; ++j) c[g].key[j] = (live && li + 16 * j < N) ? make_key(cur[j]) : 0;
-      for (int r = 0; r < k0; ++r) row_pick<NK>(c[g], li, r);
-      if (li < c[g].n) atomicOr(&U[c[g].sel_id >> 5], 1u << (c[g].sel_id & 31));
-#pragma unroll
-      for (int j = 0; j < NK; ++j) cur[j] = nxt[j];
+      for (int j = 0; j < NK; ++j) c[g].key[j] = (live && li + 16 * j < N) ? make_key(lg[j]) : 0;
     }
   }
+  __syncthreads();  // U is cleared
+  for (int r = 0; r < k0; ++r) {  // ---- Phase 1: baselines
+#pragma unroll
+    for (int g = 0; g < MAXG; ++g)
+      if (g * GROUP < B) row_pick<NK>(c[g], li, r);
+  }
+#pragma unroll
+  for (int g = 0; g < MAXG; ++g)  // ... and their union
+    if (g * GROUP < B && li < c[g].n) atomicOr(&U[c[g].sel_id >> 5], 1u << (c[g].sel_id & 31));
   __syncthreads();
   route_active<NT>(N, o, lds);
+  // ---- Phase 2: continue on the candidates that are in U, up to k picks
 #pragma unroll
-  for (int g = 0; g < MAXG; ++g) {  // ---- Phase 2: continue on the candidates that are in U, up to k picks
+  for (int g = 0; g < MAXG; ++g) {
     if (g * GROUP < B) {
 #pragma unroll
       for (int j = 0; j < NK; ++j) {
         const int e = li + 16 * j;  // e < 16*NK <= 512: inside U's 16 words
         if (!((U[e >> 5] >> (e & 31)) & 1u)) c[g].key[j] = 0;
       }
-      // a live token holds exactly k0 picks here (k0 <= N), so the next rank is the round number
-      for (int r = k0; r < k; ++r) row_pick<NK>(c[g], li, r);
+    }
+  }
+  // a live token holds exactly k0 picks here (k0 <= N), so the next rank is the round number
+  for (int r = k0; r < k; ++r) {
+#pragma unroll
+    for (int g = 0; g < MAXG; ++g)
+      if (g * GROUP < B) row_pick<NK>(c[g], li, r);
+  }
+#pragma unroll
+  for (int g = 0; g < MAXG; ++g) {
+    if (g * GROUP < B) {
       const float w = li < c[g].n ? expf(from_orderable(c[g].sel_key) - from_orderable(c[g].top_key)) : 0.f;
       const float z = row_sum_f32(w);
       if (c[g].t >= 0) {
