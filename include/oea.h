@@ -7,7 +7,8 @@
  *   - The caller owns every buffer; the library allocates no device memory.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue
  *     work and return; results are valid once the caller has synchronised the stream.  Nothing
- *     is read back to the host, so a call sequence can be captured into a HIP graph.
+ *     is read back to the host, so a call sequence can be captured into a HIP graph.  The one
+ *     exception is oea_workspace_check, which synchronises the stream and reads one word back.
  *   - Return value: OEA_OK (0) or a negative oea_status.  On error nothing was enqueued.
  *   - All matrices are row-major, expert ids are 0-based (the paper counts from 1).
  *   - Non-finite router logits give unspecified routing, but never an out-of-range index.
