@@ -32,7 +32,8 @@ typedef enum {
   OEA_ERR_WORKSPACE = -5, /* workspace_bytes < oea_workspace_bytes(...) */
   OEA_ERR_DTYPE = -6,     /* unknown oea_dtype */
   OEA_ERR_HIP = -7,       /* a HIP runtime call failed (no device, launch failure) */
-  OEA_ERR_TIMEOUT = -8    /* oea_workspace_check: a bounded wait inside a kernel gave up */
+  OEA_ERR_TIMEOUT = -8,   /* oea_workspace_check: a bounded wait inside a kernel gave up */
+  OEA_ERR_LIMIT = -9      /* moe_decode_static: oea_workspace_bytes(...) > OEA_STATIC_SCRATCH_BYTES */
 } oea_status;
 
 /* storage type of x, W_router, W_gate, W_up, W_down (all the same) */
@@ -43,6 +44,7 @@ typedef enum { OEA_F32 = 0, OEA_BF16 = 1 } oea_dtype;
 #define OEA_MAX_B 1024 /* tokens per decode batch */
 #define OEA_MAX_D 8192 /* embedding dimension and expert hidden dimension */
 #define OEA_MAX_POSITIONS 65535 /* decode positions per oea_route_batched call */
+#define OEA_STATIC_SCRATCH_BYTES 8388608 /* device scratch built into the library for moe_decode_static */
 
 /* Host, pure.  Static text for a status code. */
 const char *oea_status_string(int status);
@@ -202,6 +204,26 @@ int moe_decode_ex(const void *x, const void *W_router, const void *W_gate, const
                   const void *W_down, float *out, int B, int d, int N, int I, int k, int k0,
                   oea_dtype dt, void *workspace, size_t workspace_bytes, void *stream,
                   const oea_decode_ex *ex);
+
+/*
+ * moe_decode_ex for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same layer, same kernels,
+ * same arguments and results as moe_decode_ex (ex may be NULL), but the workspace is a device
+ * array built into the library (OEA_STATIC_SCRATCH_BYTES per GPU the library runs on, held until
+ * the process ends) instead of an argument.  The call allocates nothing and frees nothing.
+ *   - Sizes whose oea_workspace_bytes(B,d,N,I,k) exceeds OEA_STATIC_SCRATCH_BYTES are rejected
+ *     with OEA_ERR_LIMIT before anything is enqueued (8 MiB covers B <= 128 at both Qwen3 shapes).
+ *   - Every call on a GPU shares that GPU's array and finds the previous call's contents in it
+ *     (what has to start at zero is cleared by the kernels themselves): calls on one GPU must be
+ *     ordered on one stream; calls that overlap on one GPU race.
+ *   - The first call on each GPU also enqueues the kernel that prepares the array (the work of
+ *     oea_workspace_init); make that call outside stream capture.
+ *   - oea_workspace_check has no counterpart here; callers that share the device with other
+ *     kernels use moe_decode_ex with a workspace of their own.
+ */
+int moe_decode_static(const void *x, const void *W_router, const void *W_gate, const void *W_up,
+                      const void *W_down, float *out, int B, int d, int N, int I, int k, int k0,
+                      oea_dtype dt, void *stream, const oea_decode_ex *ex);
 
 #ifdef __cplusplus
 }

@@ -15,9 +15,11 @@ LIB_PATH = os.path.join(_HERE, "liboea.so")
 OEA_F32, OEA_BF16 = 0, 1
 OEA_OK = 0
 STATUS = {"OEA_ERR_NULL": -1, "OEA_ERR_SHAPE": -2, "OEA_ERR_K": -3, "OEA_ERR_ALIGN": -4,
-          "OEA_ERR_WORKSPACE": -5, "OEA_ERR_DTYPE": -6, "OEA_ERR_HIP": -7, "OEA_ERR_TIMEOUT": -8}
+          "OEA_ERR_WORKSPACE": -5, "OEA_ERR_DTYPE": -6, "OEA_ERR_HIP": -7, "OEA_ERR_TIMEOUT": -8,
+          "OEA_ERR_LIMIT": -9}
 EXPORTS = ("oea_status_string", "oea_workspace_bytes", "oea_workspace_init", "oea_route", "oea_route_batched", "oea_route_general",
-           "moe_decode", "moe_decode_ex", "oea_set_kernel_path", "oea_read_probe", "oea_workspace_check")
+           "moe_decode", "moe_decode_ex", "moe_decode_static", "oea_set_kernel_path", "oea_read_probe",
+           "oea_workspace_check")
 
 
 class OeaError(RuntimeError):
@@ -68,6 +70,8 @@ def lib():
         L.moe_decode.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp]
         L.moe_decode_ex.restype = ci
         L.moe_decode_ex.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp, ctypes.POINTER(DecodeEx)]
+        L.moe_decode_static.restype = ci
+        L.moe_decode_static.argtypes = [vp] * 6 + [ci] * 7 + [vp, ctypes.POINTER(DecodeEx)]
         _lib = L
     return _lib
 
@@ -191,11 +195,7 @@ def oea_route_general(router_logits, k0, p, k_max, max_p, token_mask=None, strea
     return out
 
 
-def moe_decode(x, w_router, w_gate, w_up, w_down, k, k0, workspace, out=None, stream=None,
-               router_bias=None, token_mask=None, taps=False, kernel_events=None, top_p=None, max_p=None,
-               spin_limit=None):
-    """One decode-time MoE layer with OEA routing.  Returns out [B,d] float32 (and a dict of routing
-    taps when taps=True)."""
+def _layer_args(x, w_router, w_gate, w_up, w_down, k, k0, out):
     for t in (x, w_router, w_gate, w_up, w_down):
         assert t.is_cuda and t.is_contiguous()
     dt = _dtype_code(x)
@@ -205,15 +205,19 @@ def moe_decode(x, w_router, w_gate, w_up, w_down, k, k0, workspace, out=None, st
     N, I, d2 = w_gate.shape
     assert d2 == d and tuple(w_router.shape) == (N, d) and tuple(w_up.shape) == (N, I, d)
     assert tuple(w_down.shape) == (N, d, I)
-    dev = x.device
     if out is None:
-        out = torch.empty((B, d), dtype=torch.float32, device=dev)
+        out = torch.empty((B, d), dtype=torch.float32, device=x.device)
     args = [_ptr(x), _ptr(w_router), _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(out), B, d, N, I, int(k),
-            int(k0), dt, _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)]
+            int(k0), dt]
+    return args, out, (B, d, N, I)
+
+
+def _extras(shape, k, dev, router_bias, token_mask, taps, kernel_events, top_p, max_p, spin_limit):
+    """The oea_decode_ex struct for the optional inputs and taps (None if none is asked for)."""
+    B, d, N, I = shape
     if not taps and router_bias is None and token_mask is None and kernel_events is None and top_p is None \
             and max_p is None and spin_limit is None:
-        _check(lib().moe_decode(*args))
-        return out
+        return None, None
     ex = DecodeEx()
     tap = None
     if spin_limit is not None:
@@ -243,7 +247,31 @@ def moe_decode(x, w_router, w_gate, w_up, w_down, k, k0, workspace, out=None, st
         ex.n_sel_out = tap["n_sel"].data_ptr()
         ex.active_list_out = tap["active_list"].data_ptr()
         ex.n_active_out = tap["n_active"].data_ptr()
+    return ex, tap
+
+
+def moe_decode(x, w_router, w_gate, w_up, w_down, k, k0, workspace, out=None, stream=None,
+               router_bias=None, token_mask=None, taps=False, kernel_events=None, top_p=None, max_p=None,
+               spin_limit=None):
+    """One decode-time MoE layer with OEA routing.  Returns out [B,d] float32 (and a dict of routing
+    taps when taps=True)."""
+    args, out, shape = _layer_args(x, w_router, w_gate, w_up, w_down, k, k0, out)
+    args += [_ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)]
+    ex, tap = _extras(shape, k, x.device, router_bias, token_mask, taps, kernel_events, top_p, max_p, spin_limit)
+    if ex is None:
+        _check(lib().moe_decode(*args))
+        return out
     _check(lib().moe_decode_ex(*args, ctypes.byref(ex)))
+    return (out, tap) if taps else out
+
+
+def moe_decode_static(x, w_router, w_gate, w_up, w_down, k, k0, out=None, stream=None, router_bias=None,
+                      token_mask=None, taps=False, top_p=None, max_p=None):
+    """moe_decode on the scratch built into the library (no workspace argument, nothing allocated by
+    the call; pass `out` to keep torch from allocating the result too)."""
+    args, out, shape = _layer_args(x, w_router, w_gate, w_up, w_down, k, k0, out)
+    ex, tap = _extras(shape, k, x.device, router_bias, token_mask, taps, None, top_p, max_p, None)
+    _check(lib().moe_decode_static(*args, _stream(stream), None if ex is None else ctypes.byref(ex)))
     return (out, tap) if taps else out
 
 

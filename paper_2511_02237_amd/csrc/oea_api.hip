@@ -1,6 +1,8 @@
 // C ABI of liboea: argument checks, workspace carving, kernel enqueue.  See include/oea.h.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "oea_internal.h"
 
 namespace oea {
@@ -58,6 +60,7 @@ extern "C" const char* oea_status_string(int status) {
     case OEA_ERR_DTYPE: return "unknown dtype";
     case OEA_ERR_HIP: return "HIP runtime error";
     case OEA_ERR_TIMEOUT: return "a bounded wait inside a kernel gave up";
+    case OEA_ERR_LIMIT: return "sizes need more scratch than the allocation-free entry point has built in";
     default: return "unknown status";
   }
 }
@@ -160,18 +163,23 @@ extern "C" int oea_route_general(const float* router_logits, const uint8_t* toke
   return e == hipSuccess ? OEA_OK : OEA_ERR_HIP;
 }
 
-extern "C" int moe_decode_ex(const void* x, const void* W_router, const void* W_gate, const void* W_up,
-                             const void* W_down, float* out, int B, int d, int N, int I, int k, int k0,
-                             oea_dtype dt, void* workspace, size_t workspace_bytes, void* stream,
-                             const oea_decode_ex* ex) {
-  if (!x || !W_router || !W_gate || !W_up || !W_down || !out || !workspace) return OEA_ERR_NULL;
+// Argument checks shared by the layer entry points (everything but the workspace).
+static int check_decode_args(const void* x, const void* W_router, const void* W_gate, const void* W_up,
+                             const void* W_down, const float* out, int B, int d, int N, int I, int k, int k0,
+                             oea_dtype dt) {
+  if (!x || !W_router || !W_gate || !W_up || !W_down || !out) return OEA_ERR_NULL;
   int rc = check_decode_sizes(B, d, N, I, k, k0, (int)dt);
   if (rc != OEA_OK) return rc;
   if (!aligned16(x) || !aligned16(W_router) || !aligned16(W_gate) || !aligned16(W_up) || !aligned16(W_down) ||
-      !aligned16(out) || !aligned16(workspace))
+      !aligned16(out))
     return OEA_ERR_ALIGN;
-  if (workspace_bytes < oea_workspace_bytes(B, d, N, I, k)) return OEA_ERR_WORKSPACE;
+  return OEA_OK;
+}
 
+// The layer on a checked workspace: carve it, enqueue the kernels and the taps.
+static int decode_enqueue(const void* x, const void* W_router, const void* W_gate, const void* W_up,
+                          const void* W_down, float* out, int B, int d, int N, int I, int k, int k0, oea_dtype dt,
+                          void* workspace, void* stream, const oea_decode_ex* ex) {
   const WsLayout w = ws_layout(B, d, N, I, k, elem_bytes_of(dt));
   char* ws = static_cast<char*>(workspace);
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -237,9 +245,74 @@ extern "C" int moe_decode_ex(const void* x, const void* W_router, const void* W_
   return OEA_OK;
 }
 
+extern "C" int moe_decode_ex(const void* x, const void* W_router, const void* W_gate, const void* W_up,
+                             const void* W_down, float* out, int B, int d, int N, int I, int k, int k0,
+                             oea_dtype dt, void* workspace, size_t workspace_bytes, void* stream,
+                             const oea_decode_ex* ex) {
+  if (!workspace) return OEA_ERR_NULL;
+  int rc = check_decode_args(x, W_router, W_gate, W_up, W_down, out, B, d, N, I, k, k0, dt);
+  if (rc != OEA_OK) return rc;
+  if (!aligned16(workspace)) return OEA_ERR_ALIGN;
+  if (workspace_bytes < oea_workspace_bytes(B, d, N, I, k)) return OEA_ERR_WORKSPACE;
+  return decode_enqueue(x, W_router, W_gate, W_up, W_down, out, B, d, N, I, k, k0, dt, workspace, stream, ex);
+}
+
 extern "C" int moe_decode(const void* x, const void* W_router, const void* W_gate, const void* W_up,
                           const void* W_down, float* out, int B, int d, int N, int I, int k, int k0,
                           oea_dtype dt, void* workspace, size_t workspace_bytes, void* stream) {
   return moe_decode_ex(x, W_router, W_gate, W_up, W_down, out, B, d, N, I, k, k0, dt, workspace,
                        workspace_bytes, stream, nullptr);
+}
+
+// ---------------------------------------------------------------------------------------------
+// moe_decode_static: the layer for callers that cannot allocate device memory.  The workspace
+// that moe_decode takes as an argument (control words, logits, routing result, hidden vectors) is
+// a file-scope device array instead; every GPU the library runs on holds its own copy of it at
+// its own address until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress: the address that call returns, kept per device, is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[OEA_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+struct StaticScratch {
+  void* ptr = nullptr;    // device address of `scratch` on this device
+  bool prepared = false;  // its control words have been cleared by a kernel on some stream
+};
+StaticScratch g_static[kMaxDevices];
+std::mutex g_static_mutex;
+}  // namespace
+
+extern "C" int moe_decode_static(const void* x, const void* W_router, const void* W_gate, const void* W_up,
+                                 const void* W_down, float* out, int B, int d, int N, int I, int k, int k0,
+                                 oea_dtype dt, void* stream, const oea_decode_ex* ex) {
+  int rc = check_decode_args(x, W_router, W_gate, W_up, W_down, out, B, d, N, I, k, k0, dt);
+  if (rc != OEA_OK) return rc;
+  const size_t need = oea_workspace_bytes(B, d, N, I, k);
+  if (need == 0 || need > (size_t)OEA_STATIC_SCRATCH_BYTES) return OEA_ERR_LIMIT;  // before any HIP call
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return OEA_ERR_HIP;
+  void* ws = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    StaticScratch& st = g_static[dev];
+    if (!st.ptr) {
+      void* p = nullptr;
+      if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return OEA_ERR_HIP;
+      st.ptr = p;
+    }
+    if (!st.prepared) {
+      // first call on this device: clear the control words with a kernel on the caller's stream,
+      // ahead of the layer (what oea_workspace_init does for a caller-owned workspace).  Under
+      // capture that kernel would only be recorded, not run: refuse.
+      hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+      if (hipStreamIsCapturing(static_cast<hipStream_t>(stream), &cs) == hipSuccess && cs != hipStreamCaptureStatusNone)
+        return OEA_ERR_HIP;
+      if (launch_fill_zero(static_cast<uint32_t*>(st.ptr), oea::kCtrlWords, static_cast<hipStream_t>(stream)) !=
+          hipSuccess)
+        return OEA_ERR_HIP;
+      st.prepared = true;
+    }
+    ws = st.ptr;
+  }
+  return decode_enqueue(x, W_router, W_gate, W_up, W_down, out, B, d, N, I, k, k0, dt, ws, stream, ex);
 }

@@ -29,6 +29,7 @@ def L():
     lib.oea_route_general.argtypes = [vp, vp, ci, ci, ci, ctypes.c_double, ci, ci, vp, vp, vp, vp, vp, vp, vp]
     lib.moe_decode.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp]
     lib.moe_decode_ex.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp, vp]
+    lib.moe_decode_static.argtypes = [vp] * 6 + [ci] * 7 + [vp, vp]
     return lib
 
 
@@ -48,11 +49,11 @@ def test_every_declared_symbol_is_exported(L):
 
 def test_status_strings(L):
     seen = set()
-    for code in range(0, -9, -1):
+    for code in range(0, -10, -1):
         s = L.oea_status_string(code).decode()
         assert s and s != "unknown status"
         seen.add(s)
-    assert len(seen) == 9
+    assert len(seen) == 10
     assert L.oea_status_string(-99).decode() == "unknown status"
 
 
@@ -128,6 +129,28 @@ def test_decode_argument_checks(L):
     assert call(a14=need - 1) == -5
     # moe_decode_ex shares the checks
     assert L.moe_decode_ex(*(ok[:14] + [16, None, None])) == -5
+
+
+def test_decode_static_argument_checks(L):
+    """The allocation-free entry point: the same checks, and sizes beyond its built-in scratch are
+    refused (all before any HIP call, so this runs without a GPU)."""
+    ok = [P, P, P, P, P, P, 16, 2048, 128, 768, 8, 3, 1, None, None]
+    def call(**kw):
+        a = list(ok)
+        for i, v in kw.items():
+            a[int(i[1:])] = v
+        return L.moe_decode_static(*a)
+    for i in range(6):
+        assert call(**{"a%d" % i: None}) == -1
+        assert call(**{"a%d" % i: P + 2}) == -4
+    assert call(a6=0) == -2 and call(a7=2052) == -2 and call(a11=9) == -3 and call(a12=7) == -6
+    limit = 8 << 20
+    assert L.oea_workspace_bytes(128, 4096, 128, 1536, 8) <= limit  # B <= 128 at both Qwen3 shapes fits
+    assert L.oea_workspace_bytes(128, 2048, 128, 768, 8) <= limit
+    assert L.oea_workspace_bytes(1024, 4096, 128, 1536, 8) > limit
+    assert call(a6=1024, a7=4096, a9=1536) == -9
+    assert call(a6=200, a7=4096, a9=1536, a10=16) == -9
+    assert "scratch" in L.oea_status_string(-9).decode()
 
 
 def test_workspace_init_argument_checks(L):
