@@ -49,6 +49,10 @@ def parse():
     ap.add_argument("--route-positions", type=int, default=0,
                     help="instead of the layer: time oea_route_batched over this many decode positions of the workload's "
                          "B, N, k at --k0 (the routing step alone, as a simulation over a trace would call it)")
+    ap.add_argument("--timeline", type=int, default=0, metavar="CALLS",
+                    help="instead of the report: per-workgroup phase stamps of the single-kernel layer, averaged over "
+                         "this many calls; needs the measurement build of the library (python -m "
+                         "paper_2511_02237_amd.build --timeline) selected with OEA_LIB=paper_2511_02237_amd/liboea_timeline.so")
     ap.add_argument("--verbose", action="store_true")
     return ap.parse_args()
 
@@ -107,6 +111,8 @@ def main():
         return sweep(args)
     if args.route_positions:
         return route_throughput(args)
+    if args.timeline:
+        return timeline(args)
     print(json.dumps(run(args)))
 
 
@@ -138,6 +144,76 @@ def route_throughput(args):
                           mean_unique_experts=round(float(res["n_active"].float().mean().item()), 2),
                           bytes_moved=moved, GBps=round(moved / us / 1e3, 1),
                           frac_of_hbm_peak=round(moved / us / 1e3 / HBM_PEAK_GBS, 4))))
+
+
+TIMELINE_SLOTS = ["kernel entered", "logits stored, x staged", "grid barrier passed", "candidate keys in registers",
+                  "Phase 1 done, union complete", "Phase 2 and gate weights done", "CSR offsets done",
+                  "routing and row cuts done", "gate/up rows streamed, h written", "completion announced",
+                  "first down tiles requested", "hidden vectors of own experts complete", "hidden vectors staged",
+                  "down rows streamed, adds issued", "adds drained"]
+
+
+def timeline(args):
+    """Where the time goes inside the single-kernel layer: the 100 MHz wall clock of every workgroup at
+    each phase boundary (measurement build of the library), relative to the first workgroup's entry,
+    averaged over calls that rotate token batches and weight sets like the headline timing."""
+    import numpy as np
+    import torch
+
+    from paper_2511_02237_amd import binding, workloads
+    assert args.gpus == 1 and torch.cuda.is_available()
+    lib = binding.lib()
+    if not hasattr(lib, "oea_timeline_read"):
+        print("bench.py --timeline: %s has no timeline stamps; build with `python -m paper_2511_02237_amd.build "
+              "--timeline` and set OEA_LIB to the library it prints" % binding.LIB_PATH, file=sys.stderr)
+        sys.exit(2)
+    lib.oea_timeline_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t]
+    cfg = workloads.CONFIGS[args.workload]
+    d, N, I, k, B = cfg["d"], cfg["N"], cfg["I"], cfg["k"], args.batch
+    dev = torch.device("cuda:0")
+    base = workloads.make_layer(args.workload, 1000 * 2, B=B, I=8)  # x, router and bias; expert weights drawn on the device
+    xs = [binding.to_device(base.x, dev)]
+    if not cfg.get("skew"):
+        xs += [binding.to_device(workloads.make_layer(args.workload, 1000 * 2 + t, B=B, N=1, I=8).x, dev)
+               for t in range(1, args.trials)]
+    w_router = binding.to_device(base.w_router, dev)
+    bias = None if base.router_bias is None else torch.from_numpy(base.router_bias).to(dev)
+    g = torch.Generator(device=dev)
+    g.manual_seed(12345)
+    R = args.weight_sets or 8
+    sets = [tuple(torch.randn(sh, generator=g, device=dev, dtype=torch.float32).mul_(0.02).to(torch.bfloat16)
+                  for sh in ((N, I, d), (N, I, d), (N, d, I))) for _ in range(R)]
+    ws = binding.new_workspace(B, d, N, I, k, device=dev)
+    out = torch.empty((B, d), dtype=torch.float32, device=dev)
+    n_slots, n_wg = 24, 256
+    buf = np.zeros(n_slots * n_wg, np.uint64)
+    acc_med, acc_max, acc_min, Ts = 0.0, 0.0, 0.0, []
+    step = 0
+    for it in range(args.warmup + args.timeline):
+        for _ in range(7):  # back-to-back calls before the sampled one, as in the timed loop
+            binding.moe_decode(xs[step % len(xs)], w_router, *sets[step % R], k, args.k0, ws, out=out, router_bias=bias)
+            step += 1
+        _, tap = binding.moe_decode(xs[step % len(xs)], w_router, *sets[step % R], k, args.k0, ws, out=out,
+                                    router_bias=bias, taps=True)
+        step += 1
+        assert lib.oea_timeline_read(buf.ctypes.data, buf.nbytes) == 0
+        if it < args.warmup:
+            continue
+        t = buf.reshape(n_slots, n_wg).astype(np.int64)
+        rel = (t[:len(TIMELINE_SLOTS)] - t[0].min()) / 100.0  # us
+        acc_med = acc_med + np.median(rel, axis=1)
+        acc_max = acc_max + rel.max(axis=1)
+        acc_min = acc_min + rel.min(axis=1)
+        Ts.append(int(tap["n_active"].item()))
+    n = args.timeline
+    rows = [dict(slot=i, phase=TIMELINE_SLOTS[i], first_wg_us=round(float(acc_min[i] / n), 2),
+                 median_wg_us=round(float(acc_med[i] / n), 2), slowest_wg_us=round(float(acc_max[i] / n), 2))
+            for i in range(len(TIMELINE_SLOTS))]
+    print(json.dumps(dict(workload="%s B=%d k0=%d" % (args.workload, B, args.k0), calls=n,
+                          mean_unique_experts=round(float(np.mean(Ts)), 2), timeline=rows)))
+    for r in rows:
+        print("| %2d | %-42s | %7.2f | %7.2f | %7.2f |" % (r["slot"], r["phase"], r["first_wg_us"], r["median_wg_us"],
+                                                       r["slowest_wg_us"]), file=sys.stderr)
 
 
 def sweep(args):

@@ -10,7 +10,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "liboea.so")
+# OEA_LIB selects another build of the same library (bench.py --timeline loads the measurement variant)
+LIB_PATH = os.environ.get("OEA_LIB") or os.path.join(_HERE, "liboea.so")
 
 OEA_F32, OEA_BF16 = 0, 1
 OEA_OK = 0

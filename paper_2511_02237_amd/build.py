@@ -27,14 +27,26 @@ def up_to_date() -> bool:
     return all(os.path.getmtime(f) <= t for f in SOURCES + HEADERS + [os.path.abspath(__file__)])
 
 
-def build(force: bool = True, extra=()) -> str:
-    if not force and up_to_date():
+TIMELINE_LIB = os.path.join(HERE, "liboea_timeline.so")
+
+
+def build(force: bool = True, extra=(), out: str = LIB) -> str:
+    if not force and out == LIB and up_to_date():
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + list(extra) + ["-o", LIB] + SOURCES
+    cmd = [hipcc] + FLAGS + list(extra) + ["-o", out] + SOURCES
     subprocess.check_call(cmd)
-    return LIB
+    return out
+
+
+def build_timeline() -> str:
+    """The measurement variant: same sources with -DOEA_TIMELINE (per-workgroup phase stamps and the
+    oea_timeline_read export), as liboea_timeline.so beside the product library."""
+    return build(force=True, extra=("-DOEA_TIMELINE",), out=TIMELINE_LIB)
 
 
 if __name__ == "__main__":
-    print(build(force=True, extra=sys.argv[1:]))
+    if sys.argv[1:2] == ["--timeline"]:
+        print(build_timeline())
+    else:
+        print(build(force=True, extra=sys.argv[1:]))

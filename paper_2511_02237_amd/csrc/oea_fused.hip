@@ -18,21 +18,7 @@
 // drain/fill and every dependent metadata load.  All 256 workgroups must be resident at once: the
 // launcher checks that a workgroup fits on every CU and every wait spins for a bounded time only.
 #include "oea_ffn_dev.h"
-#ifdef OEA_TIMELINE
-namespace oea {
-namespace {
-__device__ uint32_t* g_tl_ctrl;  // set by the kernel; lets the routing code stamp its passes
-}
-}  // namespace oea
-#define OEA_ROUTE_TL(slot_)                                                                        \
-  do {                                                                                             \
-    if (threadIdx.x == 0 && blockIdx.x == 0 && g_tl_ctrl) {                                        \
-      unsigned long long t_ = wall_clock64();                                                      \
-      g_tl_ctrl[128 + 2 * (slot_)] = uint32_t(t_);                                                 \
-      g_tl_ctrl[128 + 2 * (slot_) + 1] = uint32_t(t_ >> 32);                                       \
-    }                                                                                              \
-  } while (0)
-#endif
+#include "oea_timeline.h"
 #include "oea_route_dev.h"
 
 namespace oea {
@@ -136,24 +122,6 @@ __device__ __forceinline__ void grid_wait(uint32_t* ctrl, uint32_t next, uint32_
 
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
-// Optional timeline (build with -DOEA_TIMELINE): thread 0 of the first and of the last workgroup
-// store the 100 MHz wall clock at phase boundaries into ctrl[128..] and ctrl[192..].
-#ifdef OEA_TIMELINE
-#define OEA_TL(ctrl_, slot_)                                                                      \
-  do {                                                                                            \
-    if (threadIdx.x == 0 && (blockIdx.x == 0 || blockIdx.x == gridDim.x - 1)) {                   \
-      unsigned long long t_ = wall_clock64();                                                     \
-      uint32_t* d_ = (ctrl_) + (blockIdx.x == 0 ? 128 : 192) + 2 * (slot_);                         \
-      d_[0] = uint32_t(t_);                                                                       \
-      d_[1] = uint32_t(t_ >> 32);                                                                 \
-    }                                                                                             \
-  } while (0)
-#else
-#define OEA_TL(ctrl_, slot_) \
-  do {                       \
-  } while (0)
-#endif
-
 // ---- cost-weighted split of a stage over the workgroups.
 // A weight row of an expert with c pairs costs about (kRowCost + beta*c): streaming its bytes plus c
 // dot products per weight.  Cutting the concatenated rows of the active experts by BYTES leaves the
@@ -251,8 +219,11 @@ __device__ __forceinline__ void balance_shares(uint32_t* ctrl, uint32_t parity, 
     if (r[j] > 0.f) {
       float rel = r[j] / mean;  // this workgroup's speed relative to the average of the last call
       rel = rel < 0.8f ? 0.8f : (rel > 1.25f ? 1.25f : rel);
-      // the measured speed was obtained WITH the old weight's share, so it estimates the speed itself
-      w[j] = 0.75f * w[j] + 0.25f * rel;
+      // the measured speed was obtained WITH the old weight's share, so it estimates the speed itself.
+      // A slow average: most of a call's deviation is that call's own (routing pattern, memory
+      // system), and a weight that chases it adds noise to the next call's shares (a quarter per
+      // call instead of a twentieth was 0.3 us slower with rotating token batches)
+      w[j] = 0.95f * w[j] + 0.05f * rel;
       w[j] = w[j] < 0.7f ? 0.7f : (w[j] > 1.4f ? 1.4f : w[j]);
     }
     if (b >= G) w[j] = 0.f;
@@ -297,8 +268,7 @@ __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_ou
                                             int R0, int R1, int N, int pairs_max, int cap_vec, const int* l_active,
                                             const int* l_off, const int* l_tok, const float* l_gw,
                                             const uint4* l_vec, float* ebuf, int ecap, uint32_t* l_next, Mid mid,
-                                            unsigned long long* tl_wave = nullptr, int c0 = 0,
-                                            int c1 = 0x7fffffff, int n_defer = 0) {
+                                            int c0 = 0, int c1 = 0x7fffffff, int n_defer = 0) {
   constexpr int EPL = 16 / int(sizeof(WT));
   constexpr int R = 64 / LPR;
   constexpr int NM = STAGE == 0 ? 2 : 1;
@@ -397,9 +367,6 @@ __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_ou
       if (nA <= 0) break;
     }
   }
-#ifdef OEA_TIMELINE
-  if (tl_wave && lane == 0) tl_wave[blockIdx.x * kFfnWaves + (tid >> 6)] = wall_clock64();
-#endif
   __syncthreads();  // every wavefront's results are in the buffer
   if (wg_has && use_buf) flush_results<WT, STAGE>(sv, ebuf, s_tok, s_gw, h_out, out, base, tid);
 }
@@ -463,16 +430,7 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   float* const l_frac = l_gw + P;  // [G+1] cumulative cost shares of the workgroups
   uint4* const l_vec = lds4 + 1 + fused_meta_words(B, N, k) / 4;
 
-#ifdef OEA_TIMELINE
-  if (threadIdx.x == 0 && blockIdx.x == 0) g_tl_ctrl = p.ctrl;
-#endif
-#ifdef OEA_TIMELINE
-  if (threadIdx.x == 0) {
-    unsigned long long* tl = reinterpret_cast<unsigned long long*>(static_cast<char*>(p.h) + (size_t)p.B * p.k * p.I * 2);
-    tl[1024 + blockIdx.x] = wall_clock64();
-  }
-#endif
-  OEA_TL(p.ctrl, 0);
+  OEA_TL(0);
   uint32_t gen0 = 0;  // thread 0: barrier generation at the start of this call
   if (tid == 0 || tid == 64) gen0 = grid_generation(p.ctrl);  // thread 64: parity of the call for the speed weights
   const bool balanced = G <= kBalMaxWg;
@@ -574,23 +532,34 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
     }
   }
 
-  OEA_TL(p.ctrl, 1);
+  OEA_TL(1);
   grid_arrive(p.ctrl, gen0 + 1);  // logits and cleared out words are in memory
   if (balanced && wave == 1)  // while thread 0 waits at the barrier
     balance_shares(p.ctrl, uint32_t(__builtin_amdgcn_readfirstlane(int(gen0))), G, wg == 0, l_frac, lane, bal_in);
   grid_wait(p.ctrl, gen0 + 1, p.spin_limit);
-  OEA_TL(p.ctrl, 2);
+  OEA_TL(2);
 
   // ---- phase R2: routing, replicated per workgroup, result in LDS.  Every row of 16 lanes reads
   // its token's logits straight from memory (device-coherent loads: written by other workgroups).
   if (tid == 0) l_nact[1] = l_nact[2] = 0;  // tile counters of the two stages (a barrier follows in the routing)
-  OEA_TL(p.ctrl, 9);
   const RouteOut lo{l_idx, l_gatew, l_nsel, l_active, l_nact, l_off, l_tok, l_gw};
   uint32_t* const ctrl = p.ctrl;
+  const float* const frac = balanced ? l_frac : nullptr;
+  uint32_t* const l_cut = l_route + 48;  // [4] inside the routing scratch's block-scan words, unused at N <= 128
   {
     RowCarry<4 * NV> carry;  // one DPP row of 16 lanes per token, 4 * NV keys per lane
     route_union_rows<4 * NV, kFfnThreads, true>(p.logits, p.token_mask, B, N, p.k0, lo, l_route, carry);
-    route_fill_rows<4 * NV, kFfnThreads>(B, N, k, p.k0, lo, l_route, carry);
+    // The four cut points of this workgroup (both ends, both stages) need only the CSR offsets: the
+    // last four wavefronts compute one each while the first ones fill the pair lists.
+    route_fill_rows<4 * NV, kFfnThreads>(B, N, k, p.k0, lo, l_route, carry, [&]() {
+      if (wave >= kFfnWaves - 4) {
+        const int q = wave - (kFfnWaves - 4);
+        int T_ = uniform(l_nact[0]);
+        T_ = T_ < 0 ? 0 : (T_ > N ? N : T_);
+        const int cut = wg_first_row(l_off, T_, q < 2 ? I : d, q < 2 ? kBetaUp : kBetaDown, wg + (q & 1), G, lane, frac);
+        if (lane == 0) l_cut[q] = uint32_t(cut);
+      }
+    });
   }
   __syncthreads();
   if (wg == 0) {  // publish the routing result
@@ -604,38 +573,24 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   }
   int T = uniform(l_nact[0]);
   T = T < 0 ? 0 : (T > N ? N : T);
-  const float* const frac = balanced ? l_frac : nullptr;
-  // the four cut points of this workgroup (both ends, both stages): one wavefront each, shared through
-  // the routing scratch, which nothing reads any more
-  if (wave < 4) {
-    const int cut = wg_first_row(l_off, T, wave < 2 ? I : d, wave < 2 ? kBetaUp : kBetaDown, wg + (wave & 1), G, lane,
-                                 frac);
-    if (lane == 0) l_route[wave] = uint32_t(cut);
-  }
-  __syncthreads();
-  const int RA0 = uniform(int(l_route[0])), RA1 = uniform(int(l_route[1]));
-  const int RB0 = uniform(int(l_route[2])), RB1 = uniform(int(l_route[3]));
+  const int RA0 = uniform(int(l_cut[0])), RA1 = uniform(int(l_cut[1]));
+  const int RB0 = uniform(int(l_cut[2])), RB1 = uniform(int(l_cut[3]));
   const unsigned long long tA0 = wall_clock64();
-  OEA_TL(p.ctrl, 3);
+  OEA_TL(7);
+  OEA_TL_VAL(16, RA0);
+  OEA_TL_VAL(17, RA1);
+  OEA_TL_VAL(18, RB0);
+  OEA_TL_VAL(19, RB1);
 
   // ---- phase A: gate/up
   fused_stage<WT, 0, LPR0, NCH0, 1>(static_cast<const WT*>(p.w_gate), static_cast<const WT*>(p.w_up),
                                     static_cast<WT*>(p.h), p.out, I, d, RA0, RA1, N, P, p.cap_vec, l_active, l_off,
                                     l_tok, l_gw, l_vec, reinterpret_cast<float*>(l_vec + (size_t)B * d16), p.ecap0,
-                                    reinterpret_cast<uint32_t*>(l_nact + 1), [](int, int) {}
-#ifdef OEA_TIMELINE
-                                    , reinterpret_cast<unsigned long long*>(static_cast<char*>(p.h) + (size_t)P * I * 2) + 2048
-#endif
-                                    );
+                                    reinterpret_cast<uint32_t*>(l_nact + 1), [](int, int) {});
   const unsigned long long tA1 = wall_clock64();
+  OEA_TL(8);
   signal_hidden_done(p.ctrl, RA0, RA1, I);
-#ifdef OEA_TIMELINE
-  if (threadIdx.x == 0) {
-    unsigned long long* tl = reinterpret_cast<unsigned long long*>(static_cast<char*>(p.h) + (size_t)P * I * 2);
-    tl[512 + blockIdx.x] = wall_clock64();
-  }
-#endif
-  OEA_TL(p.ctrl, 4);
+  OEA_TL(9);
   // ---- phase B: down.  mid = barrier (h complete everywhere), then this workgroup's h rows -> LDS
   const WT* const hsrc = static_cast<const WT*>(p.h);
   const int I16 = I / EPL;
@@ -644,7 +599,7 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   unsigned long long tB0 = 0;
   const int n_defer = 2 * T <= N ? kStageWaves : 1;
   auto mid_b = [&](int a0, int nseg) {  // runs once the first weight tiles are requested
-        OEA_TL(ctrl, 5);
+        OEA_TL(10);
         // No grid barrier here: this workgroup only needs the hidden vectors of ITS experts, which
         // its neighbours produce (both stages cut the expert list in about the same proportions).
         // Wait, bounded, until the counter of each of them says complete.
@@ -660,7 +615,7 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
             }
         }
         __syncthreads();
-        OEA_TL(ctrl, 6);
+        OEA_TL(11);
         const int off0 = uniform(l_off[a0]);
         int nvec = uniform(l_off[a0 + nseg]) - off0;
         if (off0 < 0 || nvec < 0 || nvec > cap_vec || off0 + nvec > P) nvec = 0;  // never true; bounds the copy
@@ -687,19 +642,14 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
             }
           }
         __syncthreads();
-        OEA_TL(ctrl, 7);
+        OEA_TL(12);
         tB0 = wall_clock64();
       };
   fused_stage<WT, 1, LPR1, NCH1, 2>(
       static_cast<const WT*>(p.w_down), static_cast<const WT*>(nullptr), static_cast<WT*>(nullptr), p.out, d, I, RB0,
       RB1, N, P, p.cap_vec, l_active, l_off, l_tok, l_gw, l_vec,
-      reinterpret_cast<float*>(l_vec + (size_t)cap_vec * I16), p.ecap1, reinterpret_cast<uint32_t*>(l_nact + 2), mid_b
-#ifdef OEA_TIMELINE
-      , reinterpret_cast<unsigned long long*>(static_cast<char*>(p.h) + (size_t)P * I * 2) + 4096
-#else
-      , nullptr
-#endif
-      , 0, 0x7fffffff, n_defer);
+      reinterpret_cast<float*>(l_vec + (size_t)cap_vec * I16), p.ecap1, reinterpret_cast<uint32_t*>(l_nact + 2), mid_b,
+      0, 0x7fffffff, n_defer);
   if (balanced && tid == 0) {  // this workgroup's speed in this call: cost share per clock tick of streaming
     const unsigned long long tB1 = wall_clock64();
     const float ticks = float((tA1 - tA0) + (tB1 - tB0));
@@ -708,13 +658,8 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
     __hip_atomic_store(reinterpret_cast<float*>(ctrl + kBalBase) + 2 * kBalMaxWg + wg, measured ? share / ticks : 0.f,
                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-  OEA_TL(p.ctrl, 8);
-#ifdef OEA_TIMELINE
-  if (threadIdx.x == 0) {  // per-workgroup stamps in the unused upper half of the bf16 h buffer
-    unsigned long long* tl = reinterpret_cast<unsigned long long*>(static_cast<char*>(p.h) + (size_t)P * I * 2);
-    tl[blockIdx.x] = wall_clock64();
-  }
-#endif
+  OEA_TL(13);
+  OEA_TL_DRAINED(14);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -876,7 +821,7 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedPara
             }
             __syncthreads();
           },
-          nullptr, c0, c1);
+          c0, c1);
     }
   }
   const unsigned long long tA1 = wall_clock64();
@@ -937,7 +882,7 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedPara
             __syncthreads();
             if (c0 == 0) tB0 = wall_clock64();
           },
-          nullptr, c0, c1);
+          c0, c1);
     }
   }
   if (balanced && tid == 0) {
@@ -1022,7 +967,7 @@ __global__ __launch_bounds__(kFfnThreads) void expert_stage_kernel(StageParams p
     fused_stage<WT, STAGE, LPR, NCH, RG, true>(
         static_cast<const WT*>(p.wa), static_cast<const WT*>(p.wb), static_cast<WT*>(p.h_out), p.out, rows, L, R0, R1,
         N, p.pairs_max, p.cap_vec, l_active, l_off, l_tok - off0, l_gw - off0, l_vec, ebuf, p.ecap, l_next,
-        [](int, int) {}, nullptr, c0, c1);
+        [](int, int) {}, c0, c1);
   }
 }
 
@@ -1219,3 +1164,16 @@ hipError_t try_launch_stage_kernels(int stage, const void* vec, const void* wa, 
 }
 
 }  // namespace oea
+
+#ifdef OEA_TIMELINE
+// Timeline build only: copy the stamps of the last layer kernel to the host (kTlSlots x kTlWgs
+// 64-bit wall-clock values, slot-major).  Synchronises the device.
+extern "C" int oea_timeline_read(unsigned long long* h_dst, size_t bytes) {
+  if (!h_dst || bytes < sizeof(unsigned long long) * oea::kTlSlots * oea::kTlWgs) return OEA_ERR_SHAPE;
+  if (hipDeviceSynchronize() != hipSuccess) return OEA_ERR_HIP;
+  return hipMemcpyFromSymbol(h_dst, HIP_SYMBOL(oea::g_timeline), sizeof(unsigned long long) * oea::kTlSlots * oea::kTlWgs) ==
+                 hipSuccess
+             ? OEA_OK
+             : OEA_ERR_HIP;
+}
+#endif

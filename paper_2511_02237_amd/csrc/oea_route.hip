@@ -49,6 +49,9 @@ __global__ __launch_bounds__(kRouteThreads) void route_general_kernel(const floa
   route_block_general<NV, kRouteThreads>(logits, token_mask, B, N, k0, g, o, lds);
 }
 
+// First kernel of the three-kernel layer.  grid = N workgroups (one per expert e), kRouteThreads threads.
+//   part A: logits[t,e] = fp32( sum_c x[t,c] W_router[e,c] + bias[e] ), fp64 accumulation;
+//           the workgroups also clear `out` for the atomically accumulating down-projection.
 //   part B: the workgroup that arrives last at the counter routes the whole batch.
 template <typename WT, int NV>
 __global__ __launch_bounds__(kRouteThreads) void router_route_kernel(
