@@ -253,7 +253,7 @@ def run(args):
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     binding.lib()
-    binding.set_kernel_path(args.kernel_path)
+    topts = binding.test_opts(kernel_path=args.kernel_path) if args.kernel_path else None  # test aid; default: product entry points
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     hip = Hip()
@@ -302,24 +302,29 @@ def run(args):
     lib = binding.lib()
     ws_bytes = ws.numel()
 
-    def make_call(x, wset, k0, ex=None):
+    def make_call(x, wset, k0, opts=None):
         a = [ctypes.c_void_p(x.data_ptr()), ctypes.c_void_p(w_router.data_ptr()),
              ctypes.c_void_p(wset[0].data_ptr()), ctypes.c_void_p(wset[1].data_ptr()),
              ctypes.c_void_p(wset[2].data_ptr()), ctypes.c_void_p(out.data_ptr()), B, d, N, I, k, k0,
              binding.OEA_BF16, ctypes.c_void_p(ws.data_ptr()), ws_bytes, sptr]
-        if ex is None and bias is None:
+        opts = opts if opts is not None else topts
+        if opts is None and bias is None:
             return lambda: lib.moe_decode(*a)
-        exs = ex if ex is not None else binding.DecodeEx()
+        exs = binding.DecodeEx()
         if bias is not None:
             exs.router_bias = bias.data_ptr()
         ref = ctypes.byref(exs)
-        return lambda: lib.moe_decode_ex(*a, ref)
+        if opts is None:
+            return lambda: lib.moe_decode_ex(*a, ref)
+        oref = ctypes.byref(opts)
+        return lambda: lib.moe_decode_test(*a, ref, oref)
 
     # ---- routing statistics per (trial, k0): T and the number of (token, expert) pairs
     stats = {}
     for ti, x in enumerate(xs):
         for k0 in k0s:
-            _, tap = binding.moe_decode(x, w_router, *sets[0], k, k0, ws, out=out, router_bias=bias, taps=True)
+            _, tap = binding.moe_decode(x, w_router, *sets[0], k, k0, ws, out=out, router_bias=bias, taps=True,
+                                        kernel_path=args.kernel_path or None)
             torch.cuda.synchronize()
             stats[(ti, k0)] = (int(tap["n_active"].item()), int(tap["n_sel"].sum().item()))
 
@@ -328,7 +333,8 @@ def run(args):
     if not args.no_cpu:
         import oracle
         ref = oracle.moe_decode(L.x, L.w_router, L.w_gate, L.w_up, L.w_down, k, args.k0, router_bias=L.router_bias)
-        o, tap = binding.moe_decode(xs[0], w_router, *sets[0], k, args.k0, ws, router_bias=bias, taps=True)
+        o, tap = binding.moe_decode(xs[0], w_router, *sets[0], k, args.k0, ws, router_bias=bias, taps=True,
+                                    kernel_path=args.kernel_path or None)
         torch.cuda.synchronize()
         assert np.array_equal(tap["expert_idx"].cpu().numpy(), ref["expert_idx"]), "routing differs from the oracle"
         parity = float(np.abs(o.cpu().numpy() - ref["out"]).max() / np.abs(ref["out"]).max())
@@ -393,9 +399,8 @@ def run(args):
     kern = {}
     evs = (ctypes.c_void_p * 6)(*[hip.event() for _ in range(6)])
     for k0 in sorted({args.k0, k}):
-        ex = binding.DecodeEx()
-        ex.h_kernel_events = ctypes.cast(evs, ctypes.POINTER(ctypes.c_void_p))
-        calls = [make_call(xs[j % len(xs)], sets[j % R], k0, ex) for j in range(R * len(xs))]  # rotating, as timed
+        ev_opts = binding.test_opts(kernel_path=args.kernel_path, kernel_events=evs)
+        calls = [make_call(xs[j % len(xs)], sets[j % R], k0, ev_opts) for j in range(R * len(xs))]  # rotating, as timed
         acc = np.zeros(3)
         n = min(args.steps, 100)
         for it in range(args.warmup + n):

@@ -9,7 +9,11 @@
  *     work and return; results are valid once the caller has synchronised the stream.  Nothing
  *     is read back to the host, so a call sequence can be captured into a HIP graph.  The one
  *     exception is oea_workspace_check, which synchronises the stream and reads one word back.
- *   - Return value: OEA_OK (0) or a negative oea_status.  On error nothing was enqueued.
+ *   - Return value: OEA_OK (0) or a negative oea_status.  Every argument check comes before the
+ *     first enqueue, so a call refused for its arguments has enqueued nothing; OEA_ERR_HIP can
+ *     come from a launch or copy in the middle of a call, after earlier kernels were enqueued.
+ *   - The library keeps no state between calls except what it looks up once per device (compute
+ *     unit count, kernel attributes) and the built-in scratch of moe_decode_static.
  *   - All matrices are row-major, expert ids are 0-based (the paper counts from 1).
  *   - Non-finite router logits give unspecified routing, but never an out-of-range index.
  */
@@ -33,7 +37,9 @@ typedef enum {
   OEA_ERR_DTYPE = -6,     /* unknown oea_dtype */
   OEA_ERR_HIP = -7,       /* a HIP runtime call failed (no device, launch failure) */
   OEA_ERR_TIMEOUT = -8,   /* oea_workspace_check: a bounded wait inside a kernel gave up */
-  OEA_ERR_LIMIT = -9      /* moe_decode_static: oea_workspace_bytes(...) > OEA_STATIC_SCRATCH_BYTES */
+  OEA_ERR_LIMIT = -9,     /* moe_decode_static: oea_workspace_bytes(...) > OEA_STATIC_SCRATCH_BYTES */
+  OEA_ERR_WORKSPACE_STATE = -10 /* oea_workspace_check: the workspace was not prepared by
+                                   oea_workspace_init (or has been overwritten since) */
 } oea_status;
 
 /* storage type of x, W_router, W_gate, W_up, W_down (all the same) */
@@ -53,10 +59,12 @@ const char *oea_status_string(int status);
 size_t oea_workspace_bytes(int B, int d, int N, int I, int k);
 
 /*
- * Prepare a workspace: enqueues a fill kernel that zeroes its control words.  Call once after
- * allocating (or re-using for something else) a workspace, before the first moe_decode on it.
- * Each moe_decode leaves the words it synchronises through zero again, so one call serves any
- * number of layers.  The workspace also carries a small load-balancing state from call to call (a
+ * Prepare a workspace: enqueues a kernel that zeroes its control words and marks it as prepared.
+ * Call once after allocating (or re-using for something else) a workspace, before the first
+ * moe_decode on it.  Each moe_decode leaves the words it synchronises through zero again, so one
+ * call serves any number of layers.  A layer enqueued on a workspace without the mark does not
+ * wait for anything: its kernels return early, `out` is undefined (zero on the three-kernel
+ * path) and oea_workspace_check reports OEA_ERR_WORKSPACE_STATE.  The workspace also carries a small load-balancing state from call to call (a
  * speed estimate per workgroup that steers how the weight rows are shared out); it changes
  * timing only, and the order of the floating-point additions into `out`.
  */
@@ -83,9 +91,9 @@ int oea_route(const float *router_logits, int B, int N, int k, int k0, int32_t *
               void *stream);
 
 /*
- * oea_route for L independent decode positions in one launch (Section 4: each position and layer
- * is routed on its own; the paper's language-modelling evaluation routes all positions of a
- * sequence this way).  Position l uses rows [l*B, (l+1)*B) of the logits and nothing else.
+ * oea_route for L independent decode positions in one launch (Section 4.1, "Methodology": routing
+ * runs only within a decode step, and the paper's cross-entropy evaluation routes all positions of
+ * its sequences in parallel this way).  Position l uses rows [l*B, (l+1)*B) of the logits and nothing else.
  *   router_logits [L,B,N]; token_mask [L,B] uint8 or NULL (0 = padding token);
  *   expert_idx, gate_w [L,B,k]; n_sel [L,B]; active_list [L,N]; n_active [L].
  * Limits as oea_route, 1 <= L <= OEA_MAX_POSITIONS.
@@ -95,7 +103,9 @@ int oea_route_batched(const float *router_logits, const uint8_t *token_mask, int
                       int32_t *active_list, int32_t *n_active, void *stream);
 
 /*
- * General OEA routing (Algorithm 2 of the paper, Section 3.2 "General OEA"): as oea_route, with
+ * General OEA routing (Algorithm 2 of the paper, Section 3.2 "The Proposed Routing Algorithm",
+ * paragraphs "Phase 1: Baseline expert selection" and "Phase 2: Opportunistic piggybacking"): as
+ * oea_route, with
  *   - a top-p cut of the baseline: n_i = min(k0, t_i), where t_i is the smallest t such that the t
  *     best experts of token i hold softmax mass >= p (sorted cumulative sum; p = 1 switches the
  *     cut off, which is how the paper's experiments run it),
@@ -135,7 +145,9 @@ int oea_route_general(const float *router_logits, const uint8_t *token_mask, int
  * whole layer runs as ONE persistent kernel with one workgroup per compute unit, one grid-wide
  * barrier and per-expert completion counters; it expects the device to itself while it runs (a
  * workgroup that cannot be placed delays the others; every wait is bounded, after about a second
- * the call gives up and its output is undefined).  Still larger batches of these shapes run as
+ * the call gives up, its output is undefined and oea_workspace_check reports OEA_ERR_TIMEOUT).
+ * A caller that runs other kernels beside the layer (a second stream) sets
+ * oea_decode_ex.cooperative, which makes co-residency the runtime's guarantee.  Still larger batches of these shapes run as
  * three kernels (router + routing, gate/up stage, down stage) that share the fused kernel's stage
  * code; every other shape, and fp32 storage, runs as three kernels with generic expert kernels.
  * Arithmetic: router logits are accumulated in fp64 and rounded once to fp32; expert mat-vecs
@@ -148,31 +160,12 @@ int moe_decode(const void *x, const void *W_router, const void *W_gate, const vo
                oea_dtype dt, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * Host.  Test aid: which expert-FFN kernels later moe_decode calls of this process use.
- *   0 = automatic: the single fused kernel for the shapes and batch sizes it is built for, else
- *       three kernels (router + routing, gate/up, down) with the best expert kernels that apply
- *   1 = three kernels, generic expert kernels only (any shape and batch size)
- *   2 = three kernels, streaming expert kernels with fixed shares when the token vectors fit in
- *       LDS, else generic ones
- *   3 = three kernels, the fused kernel's stage code as expert kernels where the shape allows
- * Returns OEA_OK, or OEA_ERR_SHAPE for another value.  Not thread-safe against running calls.
- */
-int oea_set_kernel_path(int path);
-
-/*
- * Measurement aid: enqueue a kernel that reads `bytes` bytes (>= 1 MiB) at `buf` once, with the
- * access pattern the expert kernels stream weights with, and discards them.  Timing it over memory
- * that is not in any cache gives the practical read ceiling of the device, the yardstick next to
- * the published HBM peak.  `sink` (4 bytes of device memory, may be NULL) is never written in practice.
- */
-int oea_read_probe(const void *buf, size_t bytes, void *sink, void *stream);
-
-/*
  * Host, synchronises `stream`.  The single-kernel layer waits for other workgroups in a few places;
  * every such wait is bounded, and a workgroup whose wait runs out records that in the workspace
  * and goes on (the call still returns, with undefined output).  This call reports it: OEA_OK if no
  * wait has given up on this workspace since oea_workspace_init, else OEA_ERR_TIMEOUT (the record
- * stays until the workspace is initialised again).  Callers that cannot rule out sharing the
+ * stays until the workspace is initialised again); OEA_ERR_WORKSPACE_STATE if the workspace does
+ * not carry the mark of oea_workspace_init at all.  Callers that cannot rule out sharing the
  * device with other kernels call it after a batch of layers.
  */
 int oea_workspace_check(const void *workspace, size_t workspace_bytes, void *stream);
@@ -188,15 +181,14 @@ typedef struct {
   int32_t *n_sel_out;         /* [B]   */
   int32_t *active_list_out;   /* [N]   */
   int32_t *n_active_out;      /* [1]   */
-  void **h_kernel_events;     /* HOST array of 6 hipEvent_t (created by the caller): recorded on the
-                                 stream before/after the router+routing kernel [0],[1], the gate/up
-                                 kernel [2],[3] and the down kernel [4],[5].  Measurement aid. */
   double top_p;               /* general OEA (Algorithm 2): top-p cut of the baseline; 0 or >= 1 = off */
   int32_t max_p;              /* general OEA: piggyback only among the max_p best ranks; 0 or >= N = off.
                                  With either set, k plays the role of k_max and the layer runs as three
                                  kernels. */
-  uint32_t spin_limit;        /* test aid: polls after which a wait inside the single kernel gives up
-                                 (0 = the default, about a second) */
+  int32_t cooperative;        /* non-zero: the single persistent kernel is launched as a cooperative
+                                 launch, so the runtime guarantees that all its workgroups are resident
+                                 together or refuses the launch (OEA_ERR_HIP) - for callers that share
+                                 the device with other work.  Costs about 18 us per call on MI355X. */
 } oea_decode_ex;
 
 /* moe_decode with the extras above (ex == NULL behaves as moe_decode). */

@@ -17,10 +17,10 @@ OEA_F32, OEA_BF16 = 0, 1
 OEA_OK = 0
 STATUS = {"OEA_ERR_NULL": -1, "OEA_ERR_SHAPE": -2, "OEA_ERR_K": -3, "OEA_ERR_ALIGN": -4,
           "OEA_ERR_WORKSPACE": -5, "OEA_ERR_DTYPE": -6, "OEA_ERR_HIP": -7, "OEA_ERR_TIMEOUT": -8,
-          "OEA_ERR_LIMIT": -9}
+          "OEA_ERR_LIMIT": -9, "OEA_ERR_WORKSPACE_STATE": -10}
 EXPORTS = ("oea_status_string", "oea_workspace_bytes", "oea_workspace_init", "oea_route", "oea_route_batched", "oea_route_general",
-           "moe_decode", "moe_decode_ex", "moe_decode_static", "oea_set_kernel_path", "oea_read_probe",
-           "oea_workspace_check")
+           "moe_decode", "moe_decode_ex", "moe_decode_static", "oea_workspace_check")
+TEST_EXPORTS = ("moe_decode_test", "oea_read_probe")  # include/oea_testing.h
 
 
 class OeaError(RuntimeError):
@@ -34,8 +34,12 @@ class DecodeEx(ctypes.Structure):
                 ("logits_out", ctypes.c_void_p), ("expert_idx_out", ctypes.c_void_p),
                 ("gate_w_out", ctypes.c_void_p), ("n_sel_out", ctypes.c_void_p),
                 ("active_list_out", ctypes.c_void_p), ("n_active_out", ctypes.c_void_p),
-                ("h_kernel_events", ctypes.POINTER(ctypes.c_void_p)),
-                ("top_p", ctypes.c_double), ("max_p", ctypes.c_int32), ("spin_limit", ctypes.c_uint32)]
+                ("top_p", ctypes.c_double), ("max_p", ctypes.c_int32), ("cooperative", ctypes.c_int32)]
+
+
+class TestOpts(ctypes.Structure):  # oea_test_opts of include/oea_testing.h
+    _fields_ = [("kernel_path", ctypes.c_int32), ("spin_limit", ctypes.c_uint32),
+                ("h_kernel_events", ctypes.POINTER(ctypes.c_void_p))]
 
 
 _lib = None
@@ -55,8 +59,6 @@ def lib():
         L.oea_workspace_bytes.argtypes = [ci] * 5
         L.oea_workspace_init.restype = ci
         L.oea_workspace_init.argtypes = [vp, sz, vp]
-        L.oea_set_kernel_path.restype = ci
-        L.oea_set_kernel_path.argtypes = [ci]
         L.oea_route.restype = ci
         L.oea_route.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
         L.oea_route_batched.restype = ci
@@ -71,6 +73,8 @@ def lib():
         L.moe_decode.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp]
         L.moe_decode_ex.restype = ci
         L.moe_decode_ex.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp, ctypes.POINTER(DecodeEx)]
+        L.moe_decode_test.restype = ci
+        L.moe_decode_test.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp, ctypes.POINTER(DecodeEx), ctypes.POINTER(TestOpts)]
         L.moe_decode_static.restype = ci
         L.moe_decode_static.argtypes = [vp] * 6 + [ci] * 7 + [vp, ctypes.POINTER(DecodeEx)]
         _lib = L
@@ -101,11 +105,6 @@ def _dtype_code(t):
     if t.dtype == torch.bfloat16:
         return OEA_BF16
     raise TypeError("x and weights must be float32 or bfloat16, got %s" % t.dtype)
-
-
-def set_kernel_path(path):
-    """0 = automatic, 1 = generic expert kernels only (test aid)."""
-    _check(lib().oea_set_kernel_path(int(path)))
 
 
 def workspace_bytes(B, d, N, I, k):
@@ -213,22 +212,19 @@ def _layer_args(x, w_router, w_gate, w_up, w_down, k, k0, out):
     return args, out, (B, d, N, I)
 
 
-def _extras(shape, k, dev, router_bias, token_mask, taps, kernel_events, top_p, max_p, spin_limit):
+def _extras(shape, k, dev, router_bias, token_mask, taps, top_p, max_p, cooperative=False):
     """The oea_decode_ex struct for the optional inputs and taps (None if none is asked for)."""
     B, d, N, I = shape
-    if not taps and router_bias is None and token_mask is None and kernel_events is None and top_p is None \
-            and max_p is None and spin_limit is None:
+    if not taps and router_bias is None and token_mask is None and top_p is None and max_p is None \
+            and not cooperative:
         return None, None
     ex = DecodeEx()
     tap = None
-    if spin_limit is not None:
-        ex.spin_limit = int(spin_limit)
+    ex.cooperative = 1 if cooperative else 0
     if top_p is not None:
         ex.top_p = float(top_p)
     if max_p is not None:
         ex.max_p = int(max_p)
-    if kernel_events is not None:  # ctypes array of 6 hipEvent_t handles
-        ex.h_kernel_events = ctypes.cast(kernel_events, ctypes.POINTER(ctypes.c_void_p))
     if router_bias is not None:
         assert router_bias.is_cuda and router_bias.dtype == torch.float32 and router_bias.numel() == N
         ex.router_bias = router_bias.data_ptr()
@@ -251,18 +247,35 @@ def _extras(shape, k, dev, router_bias, token_mask, taps, kernel_events, top_p, 
     return ex, tap
 
 
+def test_opts(kernel_path=None, spin_limit=None, kernel_events=None):
+    """oea_test_opts (include/oea_testing.h) or None if nothing is set.  kernel_events: ctypes array of
+    6 hipEvent_t handles."""
+    if kernel_path is None and spin_limit is None and kernel_events is None:
+        return None
+    o = TestOpts()
+    o.kernel_path = int(kernel_path or 0)
+    o.spin_limit = int(spin_limit or 0)
+    if kernel_events is not None:
+        o.h_kernel_events = ctypes.cast(kernel_events, ctypes.POINTER(ctypes.c_void_p))
+    return o
+
+
 def moe_decode(x, w_router, w_gate, w_up, w_down, k, k0, workspace, out=None, stream=None,
-               router_bias=None, token_mask=None, taps=False, kernel_events=None, top_p=None, max_p=None,
-               spin_limit=None):
+               router_bias=None, token_mask=None, taps=False, top_p=None, max_p=None, cooperative=False,
+               kernel_path=None, spin_limit=None, kernel_events=None):
     """One decode-time MoE layer with OEA routing.  Returns out [B,d] float32 (and a dict of routing
-    taps when taps=True)."""
+    taps when taps=True).  kernel_path, spin_limit and kernel_events are the test aids of
+    moe_decode_test."""
     args, out, shape = _layer_args(x, w_router, w_gate, w_up, w_down, k, k0, out)
     args += [_ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)]
-    ex, tap = _extras(shape, k, x.device, router_bias, token_mask, taps, kernel_events, top_p, max_p, spin_limit)
-    if ex is None:
+    ex, tap = _extras(shape, k, x.device, router_bias, token_mask, taps, top_p, max_p, cooperative)
+    opts = test_opts(kernel_path, spin_limit, kernel_events)
+    if opts is not None:
+        _check(lib().moe_decode_test(*args, None if ex is None else ctypes.byref(ex), ctypes.byref(opts)))
+    elif ex is None:
         _check(lib().moe_decode(*args))
-        return out
-    _check(lib().moe_decode_ex(*args, ctypes.byref(ex)))
+    else:
+        _check(lib().moe_decode_ex(*args, ctypes.byref(ex)))
     return (out, tap) if taps else out
 
 
@@ -271,7 +284,7 @@ def moe_decode_static(x, w_router, w_gate, w_up, w_down, k, k0, out=None, stream
     """moe_decode on the scratch built into the library (no workspace argument, nothing allocated by
     the call; pass `out` to keep torch from allocating the result too)."""
     args, out, shape = _layer_args(x, w_router, w_gate, w_up, w_down, k, k0, out)
-    ex, tap = _extras(shape, k, x.device, router_bias, token_mask, taps, None, top_p, max_p, None)
+    ex, tap = _extras(shape, k, x.device, router_bias, token_mask, taps, top_p, max_p)
     _check(lib().moe_decode_static(*args, _stream(stream), None if ex is None else ctypes.byref(ex)))
     return (out, tap) if taps else out
 

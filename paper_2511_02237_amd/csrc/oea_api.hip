@@ -61,6 +61,7 @@ extern "C" const char* oea_status_string(int status) {
     case OEA_ERR_HIP: return "HIP runtime error";
     case OEA_ERR_TIMEOUT: return "a bounded wait inside a kernel gave up";
     case OEA_ERR_LIMIT: return "sizes need more scratch than the allocation-free entry point has built in";
+    case OEA_ERR_WORKSPACE_STATE: return "workspace not prepared by oea_workspace_init (or overwritten since)";
     default: return "unknown status";
   }
 }
@@ -85,15 +86,6 @@ extern "C" size_t oea_workspace_bytes(int B, int d, int N, int I, int k) {
   return ws_layout(B, d, N, I, k, 4).total;  // sized for the wider storage type
 }
 
-static int g_kernel_path = 0;
-
-extern "C" int oea_set_kernel_path(int path) {
-  if (path < 0 || path > 3) return OEA_ERR_SHAPE;
-  g_kernel_path = path;
-  set_force_generic(path == 1);
-  return OEA_OK;
-}
-
 extern "C" int oea_read_probe(const void* buf, size_t bytes, void* sink, void* stream) {
   if (!buf) return OEA_ERR_NULL;
   if (!aligned16(buf)) return OEA_ERR_ALIGN;
@@ -107,7 +99,7 @@ extern "C" int oea_workspace_init(void* workspace, size_t workspace_bytes, void*
   if (!aligned16(workspace)) return OEA_ERR_ALIGN;
   if (workspace_bytes < oea::kCtrlWords * sizeof(uint32_t)) return OEA_ERR_WORKSPACE;
   hipError_t e =
-      launch_fill_zero(static_cast<uint32_t*>(workspace), oea::kCtrlWords, static_cast<hipStream_t>(stream));
+      launch_ws_prepare(static_cast<uint32_t*>(workspace), oea::kCtrlWords, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? OEA_OK : OEA_ERR_HIP;
 }
 
@@ -115,12 +107,14 @@ extern "C" int oea_workspace_check(const void* workspace, size_t workspace_bytes
   if (!workspace) return OEA_ERR_NULL;
   if (!aligned16(workspace)) return OEA_ERR_ALIGN;
   if (workspace_bytes < oea::kCtrlWords * sizeof(uint32_t)) return OEA_ERR_WORKSPACE;
-  uint32_t gave_up = 0;  // control word 3: set by a workgroup whose wait ran out
+  static_assert(oea::kCtrlMagicWord == oea::kCtrlErrWord + 1, "the two words are read with one copy");
+  uint32_t words[2] = {0, 0};  // error flag (set by a workgroup whose wait ran out), magic word
   if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) return OEA_ERR_HIP;
-  if (hipMemcpy(&gave_up, static_cast<const uint32_t*>(workspace) + 3, sizeof(gave_up), hipMemcpyDeviceToHost) !=
-      hipSuccess)
+  if (hipMemcpy(words, static_cast<const uint32_t*>(workspace) + oea::kCtrlErrWord, sizeof(words),
+                hipMemcpyDeviceToHost) != hipSuccess)
     return OEA_ERR_HIP;
-  return gave_up ? OEA_ERR_TIMEOUT : OEA_OK;
+  if (words[1] != oea::kWsMagic) return OEA_ERR_WORKSPACE_STATE;
+  return words[0] ? OEA_ERR_TIMEOUT : OEA_OK;
 }
 
 extern "C" int oea_route(const float* router_logits, int B, int N, int k, int k0, int32_t* expert_idx,
@@ -179,7 +173,10 @@ static int check_decode_args(const void* x, const void* W_router, const void* W_
 // The layer on a checked workspace: carve it, enqueue the kernels and the taps.
 static int decode_enqueue(const void* x, const void* W_router, const void* W_gate, const void* W_up,
                           const void* W_down, float* out, int B, int d, int N, int I, int k, int k0, oea_dtype dt,
-                          void* workspace, void* stream, const oea_decode_ex* ex) {
+                          void* workspace, void* stream, const oea_decode_ex* ex,
+                          const oea_test_opts* opts = nullptr) {
+  const int path = opts ? opts->kernel_path : 0;
+  if (path < 0 || path > 3) return OEA_ERR_SHAPE;
   const WsLayout w = ws_layout(B, d, N, I, k, elem_bytes_of(dt));
   char* ws = static_cast<char*>(workspace);
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -191,7 +188,7 @@ static int decode_enqueue(const void* x, const void* W_router, const void* W_gat
   Grouping g{ro.active_list, ro.n_active, ro.grp_off, ro.grp_tok, ro.grp_gw};
   void* h = ws + w.h;
 
-  hipEvent_t* ev = ex && ex->h_kernel_events ? reinterpret_cast<hipEvent_t*>(ex->h_kernel_events) : nullptr;
+  hipEvent_t* ev = opts && opts->h_kernel_events ? reinterpret_cast<hipEvent_t*>(opts->h_kernel_events) : nullptr;
   auto mark = [&](int i) { return !ev || hipEventRecord(ev[i], s) == hipSuccess; };
 
   // general OEA (Algorithm 2) only if the extras ask for it; k is then k_max
@@ -202,11 +199,11 @@ static int decode_enqueue(const void* x, const void* W_router, const void* W_gat
 
   if (!mark(0)) return OEA_ERR_HIP;
   hipError_t e = hipErrorNotSupported;
-  if (g_kernel_path == 0 && !general)
+  if (path == 0 && !general)
     e = try_launch_fused(x, W_router, W_gate, W_up, W_down, ex ? ex->router_bias : nullptr,
                          ex ? ex->token_mask : nullptr, out, logits, h, ro,
                          reinterpret_cast<uint32_t*>(ws + w.ctrl), B, d, N, I, k, k0, dt, s,
-                         ex ? ex->spin_limit : 0u);
+                         opts ? opts->spin_limit : 0u, ex && ex->cooperative != 0);
   if (e == hipSuccess) {  // one kernel: the inner event pairs collapse onto its end
     for (int i = 1; i < 6; ++i)
       if (!mark(i)) return OEA_ERR_HIP;
@@ -217,14 +214,15 @@ static int decode_enqueue(const void* x, const void* W_router, const void* W_gat
                                 N, k, k0, dt, logits, out, reinterpret_cast<uint32_t*>(ws + w.ctrl), ro,
                                 general ? &ga : nullptr, s);
     if (e != hipSuccess || !mark(1) || !mark(2)) return OEA_ERR_HIP;
-    const bool stage_kernels = g_kernel_path == 0 || g_kernel_path == 3;
+    const bool stage_kernels = path == 0 || path == 3;
+    const bool generic_only = path == 1;
     e = stage_kernels ? try_launch_stage_kernels(0, x, W_gate, W_up, h, nullptr, B, d, N, I, k, dt, g, s)
                       : hipErrorNotSupported;
-    if (e == hipErrorNotSupported) e = launch_expert_gate_up(x, W_gate, W_up, h, B, d, N, I, k, dt, g, s);
+    if (e == hipErrorNotSupported) e = launch_expert_gate_up(x, W_gate, W_up, h, B, d, N, I, k, dt, g, generic_only, s);
     if (e != hipSuccess || !mark(3) || !mark(4)) return OEA_ERR_HIP;
     e = stage_kernels ? try_launch_stage_kernels(1, h, W_down, nullptr, nullptr, out, B, d, N, I, k, dt, g, s)
                       : hipErrorNotSupported;
-    if (e == hipErrorNotSupported) e = launch_expert_down(h, W_down, out, B, d, N, I, k, dt, g, s);
+    if (e == hipErrorNotSupported) e = launch_expert_down(h, W_down, out, B, d, N, I, k, dt, g, generic_only, s);
     if (e != hipSuccess || !mark(5)) return OEA_ERR_HIP;
   }
 
@@ -257,6 +255,18 @@ extern "C" int moe_decode_ex(const void* x, const void* W_router, const void* W_
   return decode_enqueue(x, W_router, W_gate, W_up, W_down, out, B, d, N, I, k, k0, dt, workspace, stream, ex);
 }
 
+extern "C" int moe_decode_test(const void* x, const void* W_router, const void* W_gate, const void* W_up,
+                               const void* W_down, float* out, int B, int d, int N, int I, int k, int k0,
+                               oea_dtype dt, void* workspace, size_t workspace_bytes, void* stream,
+                               const oea_decode_ex* ex, const oea_test_opts* opts) {
+  if (!workspace) return OEA_ERR_NULL;
+  int rc = check_decode_args(x, W_router, W_gate, W_up, W_down, out, B, d, N, I, k, k0, dt);
+  if (rc != OEA_OK) return rc;
+  if (!aligned16(workspace)) return OEA_ERR_ALIGN;
+  if (workspace_bytes < oea_workspace_bytes(B, d, N, I, k)) return OEA_ERR_WORKSPACE;
+  return decode_enqueue(x, W_router, W_gate, W_up, W_down, out, B, d, N, I, k, k0, dt, workspace, stream, ex, opts);
+}
+
 extern "C" int moe_decode(const void* x, const void* W_router, const void* W_gate, const void* W_up,
                           const void* W_down, float* out, int B, int d, int N, int I, int k, int k0,
                           oea_dtype dt, void* workspace, size_t workspace_bytes, void* stream) {
@@ -273,12 +283,11 @@ extern "C" int moe_decode(const void* x, const void* W_router, const void* W_gat
 static __device__ __align__(256) unsigned char scratch[OEA_STATIC_SCRATCH_BYTES];
 
 namespace {
-constexpr int kMaxDevices = 64;
 struct StaticScratch {
   void* ptr = nullptr;    // device address of `scratch` on this device
   bool prepared = false;  // its control words have been cleared by a kernel on some stream
 };
-StaticScratch g_static[kMaxDevices];
+StaticScratch g_static[oea::kMaxDevices];
 std::mutex g_static_mutex;
 }  // namespace
 
@@ -307,7 +316,7 @@ extern "C" int moe_decode_static(const void* x, const void* W_router, const void
       hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
       if (hipStreamIsCapturing(static_cast<hipStream_t>(stream), &cs) == hipSuccess && cs != hipStreamCaptureStatusNone)
         return OEA_ERR_HIP;
-      if (launch_fill_zero(static_cast<uint32_t*>(st.ptr), oea::kCtrlWords, static_cast<hipStream_t>(stream)) !=
+      if (launch_ws_prepare(static_cast<uint32_t*>(st.ptr), oea::kCtrlWords, static_cast<hipStream_t>(stream)) !=
           hipSuccess)
         return OEA_ERR_HIP;
       st.prepared = true;

@@ -21,7 +21,6 @@ namespace {
 
 constexpr size_t kLdsBudget = 128 * 1024;     // generic kernel: LDS bytes for the staged token vectors
 constexpr size_t kStreamLdsMax = 152 * 1024;  // streaming kernel: most LDS one workgroup may ask for
-bool g_force_generic = false;                 // test hook: route every call to the generic kernel
 
 struct FfnParams {
   const void* wa;    // stage 0: W_gate [N,rows,L]; stage 1: W_down [N,rows,L]
@@ -334,29 +333,17 @@ __global__ __launch_bounds__(kFfnThreads) void read_probe_kernel(const uint4* __
   if (acc == 0x9e3779b9u && sink) *sink = acc;  // keeps the loads alive; practically never taken
 }
 
-int g_num_cus = 0;
-
 int num_cus() {
-  if (g_num_cus == 0) {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-      g_num_cus = prop.multiProcessorCount;
-    if (g_num_cus <= 0) g_num_cus = 256;
-  }
-  return g_num_cus;
+  int dev = 0, cus = 0;
+  return current_device(&dev, &cus) && cus > 0 ? cus : 256;
 }
 
 template <typename WT, int STAGE, int LPR, int NCH, int RG>
 hipError_t launch_one(const FfnParams& p, size_t lds_bytes, hipStream_t s) {
   auto kern = expert_kernel<WT, STAGE, LPR, NCH, RG>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static PerDevice attr_done;
+  hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)kLdsBudget, attr_done);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(num_cus()), dim3(kFfnThreads), lds_bytes, s, p);
   return hipGetLastError();
 }
@@ -374,13 +361,9 @@ hipError_t launch_lpr(const FfnParams& p, size_t lds_bytes, hipStream_t s) {
 template <typename WT, int STAGE, int LPR, int NCH, int RG, bool FULL>
 hipError_t launch_stream_one(const FfnParams& p, size_t lds_bytes, hipStream_t s) {
   auto kern = expert_stream_kernel<WT, STAGE, LPR, NCH, RG, FULL>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStreamLdsMax);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static PerDevice attr_done;
+  hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)kStreamLdsMax, attr_done);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(num_cus()), dim3(kFfnThreads), lds_bytes, s, p);
   return hipGetLastError();
 }
@@ -424,8 +407,8 @@ hipError_t try_launch_stream(int stage, FfnParams p, int B, int k, hipStream_t s
 }
 
 template <typename WT>
-hipError_t launch_stage(int stage, FfnParams p, int B, int k, hipStream_t s) {
-  if (!g_force_generic) {
+hipError_t launch_stage(int stage, FfnParams p, int B, int k, bool generic_only, hipStream_t s) {
+  if (!generic_only) {
     hipError_t e = try_launch_stream<WT>(stage, p, B, k, s);
     if (e != hipErrorNotSupported) return e;
   }
@@ -447,7 +430,21 @@ hipError_t launch_stage(int stage, FfnParams p, int B, int k, hipStream_t s) {
 
 }  // namespace
 
-void set_force_generic(bool on) { g_force_generic = on; }
+bool current_device(int* dev, int* cus) {
+  static PerDevice cached;  // compute units + 1, 0 = not looked up yet
+  int d = -1;
+  if (hipGetDevice(&d) != hipSuccess || d < 0 || d >= kMaxDevices) return false;
+  int c = cached.v[d].load(std::memory_order_relaxed);
+  if (c == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, d) != hipSuccess || n < 0) return false;
+    c = n + 1;
+    cached.v[d].store(c, std::memory_order_relaxed);
+  }
+  *dev = d;
+  *cus = c - 1;
+  return true;
+}
 
 hipError_t launch_read_probe(const void* buf, size_t bytes, uint32_t* sink, hipStream_t s) {
   hipLaunchKernelGGL(read_probe_kernel, dim3(num_cus()), dim3(kFfnThreads), 0, s, static_cast<const uint4*>(buf),
@@ -456,7 +453,8 @@ hipError_t launch_read_probe(const void* buf, size_t bytes, uint32_t* sink, hipS
 }
 
 hipError_t launch_expert_gate_up(const void* x, const void* w_gate, const void* w_up, void* h, int B,
-                                 int d, int N, int I, int k, oea_dtype dt, Grouping g, hipStream_t s) {
+                                 int d, int N, int I, int k, oea_dtype dt, Grouping g, bool generic_only,
+                                 hipStream_t s) {
   FfnParams p{};
   p.B = B;
   p.pairs_max = B * k;
@@ -469,11 +467,12 @@ hipError_t launch_expert_gate_up(const void* x, const void* w_gate, const void* 
   p.L = d;
   p.N = N;
   p.g = g;
-  return dt == OEA_F32 ? launch_stage<float>(0, p, B, k, s) : launch_stage<uint16_t>(0, p, B, k, s);
+  return dt == OEA_F32 ? launch_stage<float>(0, p, B, k, generic_only, s)
+                       : launch_stage<uint16_t>(0, p, B, k, generic_only, s);
 }
 
 hipError_t launch_expert_down(const void* h, const void* w_down, float* out, int B, int d, int N, int I,
-                              int k, oea_dtype dt, Grouping g, hipStream_t s) {
+                              int k, oea_dtype dt, Grouping g, bool generic_only, hipStream_t s) {
   FfnParams p{};
   p.B = B;
   p.pairs_max = B * k;
@@ -486,7 +485,8 @@ hipError_t launch_expert_down(const void* h, const void* w_down, float* out, int
   p.L = I;
   p.N = N;
   p.g = g;
-  return dt == OEA_F32 ? launch_stage<float>(1, p, B, k, s) : launch_stage<uint16_t>(1, p, B, k, s);
+  return dt == OEA_F32 ? launch_stage<float>(1, p, B, k, generic_only, s)
+                       : launch_stage<uint16_t>(1, p, B, k, generic_only, s);
 }
 
 }  // namespace oea

@@ -112,7 +112,7 @@ __device__ __forceinline__ void grid_wait(uint32_t* ctrl, uint32_t next, uint32_
     while (int(__hip_atomic_load(ctrl + 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - next) < 0) {
       __builtin_amdgcn_s_sleep(2);
       if (++spins > spin_limit) {
-        atomicExch(ctrl + 3, 1u);
+        atomicExch(ctrl + kCtrlErrWord, 1u);
         break;
       }
     }
@@ -431,6 +431,8 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   uint4* const l_vec = lds4 + 1 + fused_meta_words(B, N, k) / 4;
 
   OEA_TL(0);
+  // every thread reads the same word (one request per wavefront); tested before the grid barrier
+  const uint32_t magic = __hip_atomic_load(p.ctrl + kCtrlMagicWord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   uint32_t gen0 = 0;  // thread 0: barrier generation at the start of this call
   if (tid == 0 || tid == 64) gen0 = grid_generation(p.ctrl);  // thread 64: parity of the call for the speed weights
   const bool balanced = G <= kBalMaxWg;
@@ -533,6 +535,9 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   }
 
   OEA_TL(1);
+  // A workspace that oea_workspace_init has not prepared holds arbitrary barrier words: nobody
+  // arrives, nobody waits, the kernel ends here in every workgroup (they all read the same word).
+  if (magic != kWsMagic) return;
   grid_arrive(p.ctrl, gen0 + 1);  // logits and cleared out words are in memory
   if (balanced && wave == 1)  // while thread 0 waits at the barrier
     balance_shares(p.ctrl, uint32_t(__builtin_amdgcn_readfirstlane(int(gen0))), G, wg == 0, l_frac, lane, bal_in);
@@ -609,7 +614,7 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
             while (__hip_atomic_load(done_count(ctrl, a0 + sgm), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < uint32_t(I)) {
               __builtin_amdgcn_s_sleep(2);
               if (++spins > spin_limit) {
-                atomicExch(ctrl + 3, 1u);
+                atomicExch(ctrl + kCtrlErrWord, 1u);
                 break;
               }
             }
@@ -694,6 +699,7 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedPara
   uint4* const l_vec = lds4 + 1 + fused_meta_words(B, N, k) / 4;
   const int d16 = d / EPL, I16 = I / EPL;
 
+  const uint32_t magic = __hip_atomic_load(ctrl + kCtrlMagicWord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   uint32_t gen0 = 0;
   if (tid == 0 || tid == 64) gen0 = grid_generation(ctrl);
   const bool balanced = G <= kBalMaxWg;
@@ -741,6 +747,7 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedPara
       }
     }
   }
+  if (magic != kWsMagic) return;  // unprepared workspace: see moe_fused_kernel
   grid_arrive(ctrl, gen0 + 1);
   if (balanced && wave == 1)
     balance_shares(ctrl, uint32_t(__builtin_amdgcn_readfirstlane(int(gen0))), G, wg == 0, l_frac, lane, bal_in);
@@ -855,7 +862,7 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedPara
                   while (__hip_atomic_load(done_count(ctrl, a0 + sgm), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < uint32_t(I)) {
                     __builtin_amdgcn_s_sleep(2);
                     if (++spins > spin_limit) {
-                      atomicExch(ctrl + 3, 1u);
+                      atomicExch(ctrl + kCtrlErrWord, 1u);
                       break;
                     }
                   }
@@ -894,8 +901,6 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedPara
                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 }
-
-int g_fused_cus = -1;  // CUs of the device (0: query failed), -1 before the query
 
 // ---------------------------------------------------------------------------------------------
 // One expert stage as a kernel of its own, for batches the fused kernel does not take (B > 32):
@@ -972,9 +977,8 @@ __global__ __launch_bounds__(kFfnThreads) void expert_stage_kernel(StageParams p
 }
 
 template <typename WT, int STAGE, int LPR, int NCH, int RG>
-hipError_t launch_stage_one(StageParams p, hipStream_t s) {
+hipError_t launch_stage_one(StageParams p, int grid, hipStream_t s) {
   auto kern = expert_stage_kernel<WT, STAGE, LPR, NCH, RG>;
-  const int grid = g_fused_cus;
   // LDS plan: lists, then as many vectors as fit beside a result buffer of 1024 floats per wavefront
   p.cap_list = kMaxSeg * p.B < p.pairs_max ? kMaxSeg * p.B : p.pairs_max;
   const size_t fixed = 16 + ((2 * (size_t)p.N + 8 + 2 * (size_t)p.cap_list + 3) / 4) * 16;
@@ -985,52 +989,56 @@ hipError_t launch_stage_one(StageParams p, hipStream_t s) {
   if (cap > (size_t)p.cap_list) cap = p.cap_list;
   p.cap_vec = (int)cap;
   const size_t lds = fixed + cap * p.L * sizeof(WT) + res;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLdsMax);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static PerDevice attr_set;
+  hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)kFusedLdsMax, attr_set);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kFfnThreads), lds, s, p);
   return hipGetLastError();
 }
 
 
-template <typename WT, int LPR0, int NCH0, int LPR1, int NCH1, int NV>
-hipError_t launch_fused_one(const FusedParams& p, size_t lds_bytes, hipStream_t s) {
-  auto kern = moe_fused_kernel<WT, LPR0, NCH0, LPR1, NCH1, NV>;
-  static int checked = 0;  // 1 = usable, -1 = not
-  if (checked == 0) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLdsMax);
-    if (e != hipSuccess) return e;
+// Launch of a persistent layer kernel: one workgroup per compute unit, all resident at once.  The
+// occupancy query (once per kernel and device) shows that a workgroup fits on a compute unit; that
+// the compute units are FREE when the kernel starts is the caller's part (see oea.h).
+// cooperative: launch through hipLaunchCooperativeKernel, with which the runtime itself guarantees
+// that the whole grid is resident or refuses the launch (measured: 18 us more per launch, so it is
+// an option for callers that share the device, not the default).
+template <typename Kern>
+hipError_t launch_persistent(Kern kern, const FusedParams& p, int grid, size_t lds_bytes, PerDevice& attr,
+                             PerDevice& fits, bool cooperative, hipStream_t s) {
+  int dev = 0;
+  hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)kFusedLdsMax, attr, &dev);
+  if (e != hipSuccess) return e;
+  int ok = fits.v[dev].load(std::memory_order_relaxed);  // 1 = a workgroup fits on a compute unit, -1 = not
+  if (ok == 0) {
     int per_cu = 0;
     e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, kFfnThreads, kFusedLdsMax);
     if (e != hipSuccess) return e;
-    checked = per_cu >= 1 ? 1 : -1;  // every CU can hold one workgroup: the whole grid is resident
+    ok = per_cu >= 1 ? 1 : -1;
+    fits.v[dev].store(ok, std::memory_order_relaxed);
   }
-  if (checked < 0) return hipErrorNotSupported;
-  hipLaunchKernelGGL(kern, dim3(g_fused_cus), dim3(kFfnThreads), lds_bytes, s, p);
+  if (ok < 0) return hipErrorNotSupported;
+  if (cooperative) {
+    FusedParams pc = p;
+    void* args[] = {&pc};
+    return hipLaunchCooperativeKernel(reinterpret_cast<const void*>(kern), dim3(grid), dim3(kFfnThreads), args,
+                                      (unsigned)lds_bytes, s);
+  }
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kFfnThreads), lds_bytes, s, p);
   return hipGetLastError();
 }
 
 template <typename WT, int LPR0, int NCH0, int LPR1, int NCH1, int NV>
-hipError_t launch_fused_gather_one(const FusedParams& p, size_t lds_bytes, hipStream_t s) {
-  auto kern = moe_fused_gather_kernel<WT, LPR0, NCH0, LPR1, NCH1, NV>;
-  static int checked = 0;  // 1 = usable, -1 = not
-  if (checked == 0) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLdsMax);
-    if (e != hipSuccess) return e;
-    int per_cu = 0;
-    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, kFfnThreads, kFusedLdsMax);
-    if (e != hipSuccess) return e;
-    checked = per_cu >= 1 ? 1 : -1;
-  }
-  if (checked < 0) return hipErrorNotSupported;
-  hipLaunchKernelGGL(kern, dim3(g_fused_cus), dim3(kFfnThreads), lds_bytes, s, p);
-  return hipGetLastError();
+hipError_t launch_fused_one(const FusedParams& p, int grid, size_t lds_bytes, bool coop, hipStream_t s) {
+  static PerDevice attr, fits;
+  return launch_persistent(moe_fused_kernel<WT, LPR0, NCH0, LPR1, NCH1, NV>, p, grid, lds_bytes, attr, fits, coop, s);
+}
+
+template <typename WT, int LPR0, int NCH0, int LPR1, int NCH1, int NV>
+hipError_t launch_fused_gather_one(const FusedParams& p, int grid, size_t lds_bytes, bool coop, hipStream_t s) {
+  static PerDevice attr, fits;
+  return launch_persistent(moe_fused_gather_kernel<WT, LPR0, NCH0, LPR1, NCH1, NV>, p, grid, lds_bytes, attr, fits,
+                           coop, s);
 }
 
 }  // namespace
@@ -1039,17 +1047,12 @@ hipError_t launch_fused_gather_one(const FusedParams& p, size_t lds_bytes, hipSt
 hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_gate, const void* w_up,
                             const void* w_down, const float* bias, const uint8_t* token_mask, float* out,
                             float* logits, void* h, RouteOut ro, uint32_t* ctrl, int B, int d, int N, int I,
-                            int k, int k0, oea_dtype dt, hipStream_t s, uint32_t spin_limit) {
+                            int k, int k0, oea_dtype dt, hipStream_t s, uint32_t spin_limit, bool cooperative) {
   if (dt != OEA_BF16 || N > 128 || B > 128 || k > 16) return hipErrorNotSupported;
   const bool shape30 = d == 2048 && I == 768, shape235 = d == 4096 && I == 1536;
   if (!shape30 && !shape235) return hipErrorNotSupported;
-  if (g_fused_cus < 0) {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hipErrorUnknown;
-    g_fused_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 0;
-  }
-  const int grid = g_fused_cus;
+  int dev = 0, grid = 0;
+  if (!current_device(&dev, &grid)) return hipErrorUnknown;
   if (grid < 1) return hipErrorNotSupported;
   // most experts one workgroup's cost share can touch: share / cheapest expert, plus the two it may cut
   const int beta_hi = kBetaUp > kBetaDown ? kBetaUp : kBetaDown, beta_lo = kBetaUp < kBetaDown ? kBetaUp : kBetaDown;
@@ -1119,11 +1122,11 @@ hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_g
   p.ecap1 = ecap1;
   p.spin_limit = spin_limit ? spin_limit : 4u << 20;  // polls of >= 100 ns each: gives up after about a second
   if (gather) {
-    if (shape30) return launch_fused_gather_one<uint16_t, 32, 8, 16, 6, 2>(p, lds_bytes, s);
-    return launch_fused_gather_one<uint16_t, 64, 8, 32, 6, 2>(p, lds_bytes, s);
+    if (shape30) return launch_fused_gather_one<uint16_t, 32, 8, 16, 6, 2>(p, grid, lds_bytes, cooperative, s);
+    return launch_fused_gather_one<uint16_t, 64, 8, 32, 6, 2>(p, grid, lds_bytes, cooperative, s);
   }
-  if (shape30) return launch_fused_one<uint16_t, 32, 8, 16, 6, 2>(p, lds_bytes, s);
-  return launch_fused_one<uint16_t, 64, 8, 32, 6, 2>(p, lds_bytes, s);
+  if (shape30) return launch_fused_one<uint16_t, 32, 8, 16, 6, 2>(p, grid, lds_bytes, cooperative, s);
+  return launch_fused_one<uint16_t, 64, 8, 32, 6, 2>(p, grid, lds_bytes, cooperative, s);
 }
 
 // The two expert stages as separate kernels built from the fused kernel's stage code (batches the
@@ -1134,13 +1137,8 @@ hipError_t try_launch_stage_kernels(int stage, const void* vec, const void* wa, 
   if (dt != OEA_BF16 || N > 128) return hipErrorNotSupported;
   const bool shape30 = d == 2048 && I == 768, shape235 = d == 4096 && I == 1536;
   if (!shape30 && !shape235) return hipErrorNotSupported;
-  if (g_fused_cus < 0) {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hipErrorUnknown;
-    g_fused_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 0;
-  }
-  const int grid = g_fused_cus;
+  int dev = 0, grid = 0;
+  if (!current_device(&dev, &grid)) return hipErrorUnknown;
   if (grid < 1) return hipErrorNotSupported;
   // a workgroup's cost share must not span more than kMaxSeg experts (see try_launch_fused)
   const int beta_hi = kBetaUp > kBetaDown ? kBetaUp : kBetaDown, beta_lo = kBetaUp < kBetaDown ? kBetaUp : kBetaDown;
@@ -1159,8 +1157,10 @@ hipError_t try_launch_stage_kernels(int stage, const void* vec, const void* wa, 
   p.B = B;
   p.pairs_max = B * k;
   if (shape30)
-    return stage == 0 ? launch_stage_one<uint16_t, 0, 32, 8, 1>(p, s) : launch_stage_one<uint16_t, 1, 16, 6, 2>(p, s);
-  return stage == 0 ? launch_stage_one<uint16_t, 0, 64, 8, 1>(p, s) : launch_stage_one<uint16_t, 1, 32, 6, 2>(p, s);
+    return stage == 0 ? launch_stage_one<uint16_t, 0, 32, 8, 1>(p, grid, s)
+                      : launch_stage_one<uint16_t, 1, 16, 6, 2>(p, grid, s);
+  return stage == 0 ? launch_stage_one<uint16_t, 0, 64, 8, 1>(p, grid, s)
+                    : launch_stage_one<uint16_t, 1, 32, 6, 2>(p, grid, s);
 }
 
 }  // namespace oea

@@ -4,16 +4,47 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "oea.h"
+#include "oea_testing.h"
 
 namespace oea {
+
+// Control words at the start of a workspace (see WsLayout::ctrl).  oea_workspace_init writes the
+// magic word; the layer kernels look at it before they wait for anybody, so a workspace that was
+// never prepared (or was overwritten) makes them return at once instead of spinning.
+constexpr int kCtrlErrWord = 3;    // set by a workgroup whose bounded wait ran out
+constexpr int kCtrlMagicWord = 4;  // kWsMagic on a prepared workspace
+constexpr uint32_t kWsMagic = 0x4F454131u;
+
+// State that is looked up or set once per DEVICE (a process may drive several): indexed by the
+// HIP device id of the calling thread's current device.
+constexpr int kMaxDevices = 64;
+struct PerDevice {
+  std::atomic<int> v[kMaxDevices];  // zero-initialised for objects of static storage duration
+};
+// Current device and its number of compute units (cached per device).  Returns false if HIP fails.
+bool current_device(int* dev, int* cus);
+// hipFuncSetAttribute(max dynamic LDS) for `kern` on the current device, once per device (`done`
+// belongs to that kernel); *dev_out receives the device id.
+inline hipError_t ensure_dynamic_lds(const void* kern, int bytes, PerDevice& done, int* dev_out = nullptr) {
+  int dev = 0, cus = 0;
+  if (!current_device(&dev, &cus)) return hipErrorInvalidDevice;
+  if (dev_out) *dev_out = dev;
+  if (done.v[dev].load(std::memory_order_relaxed) >= bytes) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) done.v[dev].store(bytes, std::memory_order_relaxed);
+  return e;
+}
 
 // Carving of the caller's workspace.  All offsets are multiples of 256 bytes.
 struct WsLayout {
   size_t ctrl;         // uint32[1024 + 8192 + 768].  [9216..) is the fused kernel's load-balancing state (speed
-                       // weights of the workgroups, adapted from call to call); the rest is zero between calls: [0] arrival counter of the router kernel,
-                       // [3] error flag, [32], [64] and [256 + 32 i] grid-barrier words of the fused kernel, [1024..) its
-                       // per-expert completion counters, one 128-byte line each (as many lines again are unused)
+                       // weights of the workgroups, adapted from call to call); [4] holds kWsMagic; the rest is zero
+                       // between calls: [0] arrival counter of the router kernel, [3] error flag, [32], [64] and
+                       // [256 + 32 i] grid-barrier words of the fused kernel, [1024..) its per-expert completion
+                       // counters, one 128-byte line each (as many lines again are unused)
   size_t logits;       // float [B,N]
   size_t expert_idx;   // int32 [B,k]
   size_t gate_w;       // float [B,k]
@@ -57,7 +88,8 @@ struct RouteGeneralArgs {
 };
 
 // launchers (each returns the hipError_t of the launch)
-hipError_t launch_fill_zero(uint32_t* p, size_t n_words, hipStream_t s);
+// zero the control words and write the magic word (a kernel, not a memset: captures stay valid)
+hipError_t launch_ws_prepare(uint32_t* ctrl, size_t n_words, hipStream_t s);
 // L independent positions: logits [L,B,N]; every output has a leading dimension L
 hipError_t launch_route(const float* logits, const uint8_t* token_mask, int L, int B, int N, int k, int k0,
                         RouteOut o, hipStream_t s);
@@ -67,16 +99,19 @@ hipError_t launch_router_and_route(const void* x, const void* w_router, const fl
                                    RouteOut o, const RouteGeneralArgs* general, hipStream_t s);
 hipError_t launch_route_general(const float* logits, const uint8_t* token_mask, int B, int N, int k0,
                                 const RouteGeneralArgs& ga, int32_t* n_base, RouteOut o, hipStream_t s);
+// generic_only: skip the streaming kernels with fixed shares (test aid)
 hipError_t launch_expert_gate_up(const void* x, const void* w_gate, const void* w_up, void* h, int B,
-                                 int d, int N, int I, int k, oea_dtype dt, Grouping g, hipStream_t s);
+                                 int d, int N, int I, int k, oea_dtype dt, Grouping g, bool generic_only,
+                                 hipStream_t s);
 hipError_t launch_expert_down(const void* h, const void* w_down, float* out, int B, int d, int N, int I,
-                              int k, oea_dtype dt, Grouping g, hipStream_t s);
+                              int k, oea_dtype dt, Grouping g, bool generic_only, hipStream_t s);
 
 // whole layer in one persistent kernel; hipErrorNotSupported if the shape is not one it is built for
 hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_gate, const void* w_up,
                             const void* w_down, const float* bias, const uint8_t* token_mask, float* out,
                             float* logits, void* h, RouteOut ro, uint32_t* ctrl, int B, int d, int N, int I,
-                            int k, int k0, oea_dtype dt, hipStream_t s, uint32_t spin_limit = 0);
+                            int k, int k0, oea_dtype dt, hipStream_t s, uint32_t spin_limit = 0,
+                            bool cooperative = false);
 
 // one expert stage (0 gate/up, 1 down) with the fused kernel's stage code, for larger batches
 hipError_t try_launch_stage_kernels(int stage, const void* vec, const void* wa, const void* wb, void* h_out,
@@ -85,6 +120,5 @@ hipError_t try_launch_stage_kernels(int stage, const void* vec, const void* wa, 
 
 hipError_t launch_read_probe(const void* buf, size_t bytes, uint32_t* sink, hipStream_t s);
 size_t route_lds_bytes(int B, int N);
-void set_force_generic(bool on);
 
 }  // namespace oea

@@ -62,6 +62,8 @@ __global__ __launch_bounds__(kRouteThreads) void router_route_kernel(
   constexpr int EPL = 16 / int(sizeof(WT));
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int e = blockIdx.x;
+  // `counter` is the first control word of the workspace; every thread reads the same magic word
+  const uint32_t magic = counter[kCtrlMagicWord];
 
   {  // clear this workgroup's slice of out[B,d] (d is a multiple of 8, so float4 granules)
     const size_t total4 = (size_t)B * d / 4;
@@ -69,6 +71,13 @@ __global__ __launch_bounds__(kRouteThreads) void router_route_kernel(
     const size_t lo = per * e, hi = lo + per < total4 ? lo + per : total4;
     float4* o4 = reinterpret_cast<float4*>(out_to_zero);
     for (size_t i = lo + tid; i < hi; i += kRouteThreads) o4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+
+  // A workspace that was never prepared holds an arbitrary arrival count: no workgroup would know
+  // that it is the last.  The layer then ends with out = 0 and an empty routing (no active expert).
+  if (magic != kWsMagic) {
+    if (e == 0 && tid == 0) *o.n_active = 0;
+    return;
   }
 
   // TB tokens at a time per wavefront: the router row chunk is loaded once for all of them and their
@@ -134,9 +143,9 @@ __global__ __launch_bounds__(kRouteThreads) void router_route_kernel(
     route_block<NV, kRouteThreads, 0>(logits, token_mask, B, N, k, k0, o, lds);
 }
 
-__global__ void fill_zero_kernel(uint32_t* p, size_t n) {
+__global__ void ws_prepare_kernel(uint32_t* p, size_t n) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = 0u;
+  if (i < n) p[i] = i == (size_t)kCtrlMagicWord ? kWsMagic : 0u;
 }
 
 int nv_for(int N) {
@@ -148,9 +157,9 @@ int nv_for(int N) {
 
 size_t route_lds_bytes(int B, int N) { return sizeof(uint32_t) * (route_lds_words(B, N) + (size_t)B); }
 
-hipError_t launch_fill_zero(uint32_t* p, size_t n_words, hipStream_t s) {
-  if (n_words == 0) return hipSuccess;
-  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((n_words + 255) / 256)), dim3(256), 0, s, p, n_words);
+hipError_t launch_ws_prepare(uint32_t* ctrl, size_t n_words, hipStream_t s) {
+  if (n_words <= (size_t)kCtrlMagicWord) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(ws_prepare_kernel, dim3((unsigned)((n_words + 255) / 256)), dim3(256), 0, s, ctrl, n_words);
   return hipGetLastError();
 }
 

@@ -7,6 +7,7 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "oea.h")
+TEST_HEADER = os.path.join(ROOT, "include", "oea_testing.h")
 LIB = os.path.join(ROOT, "paper_2511_02237_amd", "liboea.so")
 
 
@@ -30,11 +31,12 @@ def L():
     lib.moe_decode.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp]
     lib.moe_decode_ex.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp, vp]
     lib.moe_decode_static.argtypes = [vp] * 6 + [ci] * 7 + [vp, vp]
+    lib.moe_decode_test.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp, vp, vp]
     return lib
 
 
-def declared_functions():
-    text = open(HEADER).read()
+def declared_functions(header=HEADER):
+    text = open(header).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(\w+)\s*\([^;{}]*\)\s*;", text)))
 
@@ -43,17 +45,20 @@ def test_every_declared_symbol_is_exported(L):
     names = declared_functions()
     assert {"oea_route", "oea_route_general", "moe_decode", "moe_decode_ex", "oea_workspace_bytes", "oea_workspace_init",
             "oea_status_string"} <= set(names)
-    for n in names:
+    for n in names + declared_functions(TEST_HEADER):
         assert hasattr(L, n), n
+    # the product header carries no test or measurement aid
+    assert not {"oea_set_kernel_path", "oea_read_probe", "moe_decode_test"} & set(names)
+    assert "spin_limit" not in open(HEADER).read() and "h_kernel_events" not in open(HEADER).read()
 
 
 def test_status_strings(L):
     seen = set()
-    for code in range(0, -10, -1):
+    for code in range(0, -11, -1):
         s = L.oea_status_string(code).decode()
         assert s and s != "unknown status"
         seen.add(s)
-    assert len(seen) == 10
+    assert len(seen) == 11
     assert L.oea_status_string(-99).decode() == "unknown status"
 
 
@@ -127,8 +132,16 @@ def test_decode_argument_checks(L):
     assert call(a14=1024) == -5
     need = L.oea_workspace_bytes(16, 2048, 128, 768, 8)
     assert call(a14=need - 1) == -5
-    # moe_decode_ex shares the checks
+    # moe_decode_ex and moe_decode_test share the checks
     assert L.moe_decode_ex(*(ok[:14] + [16, None, None])) == -5
+    assert L.moe_decode_test(*(ok[:14] + [16, None, None, None])) == -5
+    assert L.moe_decode_test(*([None] + ok[1:] + [None, None])) == -1
+    import ctypes as C
+
+    class Opts(C.Structure):
+        _fields_ = [("kernel_path", C.c_int32), ("spin_limit", C.c_uint32), ("h_kernel_events", C.c_void_p)]
+    bad = Opts(kernel_path=4)
+    assert L.moe_decode_test(*(ok + [None, C.addressof(bad)])) == -2  # refused before any enqueue
 
 
 def test_decode_static_argument_checks(L):
@@ -174,6 +187,7 @@ def test_read_probe_argument_checks(L):
 def test_binding_module_names_match_the_abi():
     from paper_2511_02237_amd import binding
     assert set(binding.EXPORTS) == set(declared_functions())
+    assert set(binding.TEST_EXPORTS) == set(declared_functions(TEST_HEADER))
     for n in ("oea_route", "moe_decode", "workspace_bytes", "new_workspace", "status_string"):
         assert hasattr(binding, n)
 

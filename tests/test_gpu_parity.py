@@ -95,17 +95,19 @@ def test_route_non_finite_logits_stay_in_range(torch, B_):
     assert (got["n_sel"] >= 0).all() and (got["n_sel"] <= 8).all()
 
 
-def run_layer(torch, B_, L, k0, ws=None, bias=None, mask=None):
+def run_layer(torch, B_, L, k0, ws=None, bias=None, mask=None, path=None):
     dev = {f: B_.to_device(getattr(L, f)) for f in ("x", "w_router", "w_gate", "w_up", "w_down")}
-    return run_layer_dev(torch, B_, L, dev, k0, ws, bias, mask)
+    return run_layer_dev(torch, B_, L, dev, k0, ws, bias, mask, path)
 
 
-def run_layer_dev(torch, B_, L, dev, k0, ws=None, bias=None, mask=None):
+def run_layer_dev(torch, B_, L, dev, k0, ws=None, bias=None, mask=None, path=None):
+    """path: kernel path of oea_test_opts (None = the product entry point, automatic choice)."""
     if ws is None:
         ws = B_.new_workspace(L.B, L.d, L.N, L.I, L.k)
     out, tap = B_.moe_decode(dev["x"], dev["w_router"], dev["w_gate"], dev["w_up"], dev["w_down"], L.k, k0, ws,
                              router_bias=None if bias is None else torch.from_numpy(bias).cuda(),
-                             token_mask=None if mask is None else torch.from_numpy(mask).cuda(), taps=True)
+                             token_mask=None if mask is None else torch.from_numpy(mask).cuda(), taps=True,
+                             kernel_path=path)
     torch.cuda.synchronize()
     return out.cpu().numpy(), {n: v.cpu().numpy() for n, v in tap.items()}
 
@@ -173,20 +175,16 @@ def test_ragged_shapes(torch, B_, oracle):
 def test_generic_kernel_path(torch, B_, oracle):
     """The generic expert kernels (used when the staged token vectors do not fit in LDS) on shapes the
     automatic choice would give to the streaming kernels."""
-    B_.set_kernel_path(1)
-    try:
-        for name, seed in (("toy", 600), ("mid_bf16", 601), ("mid_f32", 602)):
-            L = W.make_layer(name, seed)
-            for k0 in L.k0s:
-                out, tap = run_layer(torch, B_, L, k0)
-                check_layer(oracle, L, k0, out, tap, "generic %s k0=%d" % (name, k0))
-        for (d, I, N, B, k, dtype) in [(72, 24, 5, 3, 3, "bf16"), (1032, 520, 6, 3, 2, "bf16"), (2056, 8, 4, 2, 2, "bf16"),
-                                       (2048, 64, 4, 80, 2, "bf16")]:
-            L = W.make_layer("toy", 603, d=d, I=I, N=N, B=B, k=k, dtype=dtype)
-            out, tap = run_layer(torch, B_, L, 1)
-            check_layer(oracle, L, 1, out, tap, "generic ragged d=%d I=%d" % (d, I))
-    finally:
-        B_.set_kernel_path(0)
+    for name, seed in (("toy", 600), ("mid_bf16", 601), ("mid_f32", 602)):
+        L = W.make_layer(name, seed)
+        for k0 in L.k0s:
+            out, tap = run_layer(torch, B_, L, k0, path=1)
+            check_layer(oracle, L, k0, out, tap, "generic %s k0=%d" % (name, k0))
+    for (d, I, N, B, k, dtype) in [(72, 24, 5, 3, 3, "bf16"), (1032, 520, 6, 3, 2, "bf16"), (2056, 8, 4, 2, 2, "bf16"),
+                                   (2048, 64, 4, 80, 2, "bf16")]:
+        L = W.make_layer("toy", 603, d=d, I=I, N=N, B=B, k=k, dtype=dtype)
+        out, tap = run_layer(torch, B_, L, 1, path=1)
+        check_layer(oracle, L, 1, out, tap, "generic ragged d=%d I=%d" % (d, I))
 
 
 def test_bias_and_padding_mask(torch, B_, oracle):
@@ -267,14 +265,10 @@ def test_full_size_30b_every_k0_and_odd_batches(torch, B_, oracle):
 def test_full_size_30b_shape_three_kernel_paths(torch, B_, oracle, path):
     """Same layer through the three-kernel paths (streaming / generic expert kernels)."""
     L, dev = big_layer(B_, "qwen3_30b", 2000)
-    B_.set_kernel_path(path)
-    try:
-        for k0 in (3, 8):
-            out, tap = run_layer_dev(torch, B_, L, dev, k0)
-            err, ref = check_layer(oracle, L, k0, out, tap, "path %d k0=%d" % (path, k0))
-            say("path", path, "k0", k0, "T=%d err=%.2e" % (ref["n_active"], err))
-    finally:
-        B_.set_kernel_path(0)
+    for k0 in (3, 8):
+        out, tap = run_layer_dev(torch, B_, L, dev, k0, path=path)
+        err, ref = check_layer(oracle, L, k0, out, tap, "path %d k0=%d" % (path, k0))
+        say("path", path, "k0", k0, "T=%d err=%.2e" % (ref["n_active"], err))
 
 
 def test_fused_kernel_repeatable_and_masked(torch, B_, oracle):
@@ -325,15 +319,11 @@ def test_full_size_235b_shape(torch, B_, oracle):
     L = W.make_layer("qwen3_235b", 3000)
     dev = {f: B_.to_device(getattr(L, f)) for f in ("x", "w_router", "w_gate", "w_up", "w_down")}
     for path in (0, 2):
-        B_.set_kernel_path(path)
-        try:
-            for k0 in (3, 8):
-                ctx = "qwen3_235b path=%d k0=%d" % (path, k0)
-                out, tap = run_layer_dev(torch, B_, L, dev, k0)
-                err, ref = check_layer(oracle, L, k0, out, tap, ctx)
-                say(ctx, "T=%d err=%.2e" % (ref["n_active"], err))
-        finally:
-            B_.set_kernel_path(0)
+        for k0 in (3, 8):
+            ctx = "qwen3_235b path=%d k0=%d" % (path, k0)
+            out, tap = run_layer_dev(torch, B_, L, dev, k0, path=path)
+            err, ref = check_layer(oracle, L, k0, out, tap, ctx)
+            say(ctx, "T=%d err=%.2e" % (ref["n_active"], err))
     # a larger batch on the same weights: the single kernel with per-workgroup staging (vectors of
     # 8 KB leave room for about a dozen per workgroup, so pieces occur)
     L48 = W.make_layer("qwen3_235b", 3001, B=48, N=1, I=8)  # only its x is used
@@ -471,14 +461,10 @@ def test_stage_kernels_at_b16(torch, B_, oracle):
     """Kernel path 3 runs the stage kernels also where the fused kernel would apply."""
     L = W.make_layer("qwen3_30b", 77)
     dev = {f: B_.to_device(getattr(L, f)) for f in ("x", "w_router", "w_gate", "w_up", "w_down")}
-    B_.set_kernel_path(3)
-    try:
-        for k0 in (1, 3, 8):
-            out, tap = run_layer_dev(torch, B_, L, dev, k0)
-            err, ref = check_layer(oracle, L, k0, out, tap, "stage kernels B=16 k0=%d" % k0)
-            say("stage kernels B=16 k0=%d T=%d err=%.2e" % (k0, ref["n_active"], err))
-    finally:
-        B_.set_kernel_path(0)
+    for k0 in (1, 3, 8):
+        out, tap = run_layer_dev(torch, B_, L, dev, k0, path=3)
+        err, ref = check_layer(oracle, L, k0, out, tap, "stage kernels B=16 k0=%d" % k0)
+        say("stage kernels B=16 k0=%d T=%d err=%.2e" % (k0, ref["n_active"], err))
 
 
 def test_many_tokens_per_expert(torch, B_, oracle):
@@ -489,18 +475,14 @@ def test_many_tokens_per_expert(torch, B_, oracle):
     x[1::2] = L0.x[1:2]  # two distinct tokens, alternating
     L = W.Layer(**{**L0.__dict__, "x": np.ascontiguousarray(x)})
     dev = {f: B_.to_device(getattr(L, f)) for f in ("x", "w_router", "w_gate", "w_up", "w_down")}
-    try:
-        for path in (0, 3):  # the single kernel for larger batches, and the separate stage kernels
-            B_.set_kernel_path(path)
-            for k0 in (2, 8):
-                out, tap = run_layer_dev(torch, B_, L, dev, k0)
-                err, ref = check_layer(oracle, L, k0, out, tap, "B=64 duplicated tokens k0=%d path %d" % (k0, path))
-                cnt = np.bincount(ref["expert_idx"][ref["expert_idx"] >= 0], minlength=L.N)
-                say("B=64 duplicated tokens k0=%d path %d: T=%d, most pairs on one expert %d, err=%.2e"
-                    % (k0, path, ref["n_active"], cnt.max(), err))
-                assert cnt.max() >= 32
-    finally:
-        B_.set_kernel_path(0)
+    for path in (0, 3):  # the single kernel for larger batches, and the separate stage kernels
+        for k0 in (2, 8):
+            out, tap = run_layer_dev(torch, B_, L, dev, k0, path=path)
+            err, ref = check_layer(oracle, L, k0, out, tap, "B=64 duplicated tokens k0=%d path %d" % (k0, path))
+            cnt = np.bincount(ref["expert_idx"][ref["expert_idx"] >= 0], minlength=L.N)
+            say("B=64 duplicated tokens k0=%d path %d: T=%d, most pairs on one expert %d, err=%.2e"
+                % (k0, path, ref["n_active"], cnt.max(), err))
+            assert cnt.max() >= 32
 
 
 # ---- capture into a HIP graph
@@ -542,6 +524,52 @@ def test_graph_capture_and_replay(torch, B_, oracle):
             err = np.abs(got.cpu().numpy() - want).max() / np.abs(want).max()
             assert err <= 1e-5, "replay %d %s: %.2e" % (rep, name, err)
     say("graph replays match the eager result")
+
+
+def test_unprepared_workspace_is_reported_at_once(torch, B_, oracle):
+    """A layer on a workspace that oea_workspace_init never saw (or that was overwritten since) does not
+    spin: its kernels return early and oea_workspace_check names the cause.  Both the single-kernel
+    path and the three-kernel path; afterwards the prepared workspace works."""
+    import time
+    for name, B in (("qwen3_30b", 4), ("mid_bf16", None)):
+        L = W.make_layer(name, 95, B=B)
+        dev = {f: B_.to_device(getattr(L, f)) for f in ("x", "w_router", "w_gate", "w_up", "w_down")}
+        n = B_.workspace_bytes(L.B, L.d, L.N, L.I, L.k)
+        ws = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda")  # never prepared: arbitrary control words
+        args = (dev["x"], dev["w_router"], dev["w_gate"], dev["w_up"], dev["w_down"], L.k, 2, ws)
+        say("%s: layer on an unprepared workspace" % name)
+        t0 = time.perf_counter()
+        B_.moe_decode(*args)
+        with pytest.raises(B_.OeaError) as err:
+            B_.workspace_check(ws)
+        assert err.value.code == B_.STATUS["OEA_ERR_WORKSPACE_STATE"]
+        assert time.perf_counter() - t0 < 0.5, "the kernels must not wait out their poll limit"
+        # prepared, used, then overwritten by the caller
+        B_.workspace_init(ws)
+        good = B_.moe_decode(*args).cpu().numpy()
+        B_.workspace_check(ws)
+        ref = oracle.moe_decode(L.x, L.w_router, L.w_gate, L.w_up, L.w_down, L.k, 2)
+        assert np.abs(good - ref["out"]).max() / np.abs(ref["out"]).max() <= TOL[L.dtype]
+        ws[:64].fill_(0xAB)
+        B_.moe_decode(*args)
+        with pytest.raises(B_.OeaError) as err:
+            B_.workspace_check(ws)
+        assert err.value.code == B_.STATUS["OEA_ERR_WORKSPACE_STATE"]
+
+
+def test_cooperative_launch_option(torch, B_, oracle):
+    """oea_decode_ex.cooperative: the single kernel through a cooperative launch (co-residency is then
+    the runtime's guarantee); same results."""
+    L = W.make_layer("qwen3_30b", 96, B=6)
+    dev = {f: B_.to_device(getattr(L, f)) for f in ("x", "w_router", "w_gate", "w_up", "w_down")}
+    ws = B_.new_workspace(L.B, L.d, L.N, L.I, L.k)
+    for k0 in (2, 8):
+        out, tap = B_.moe_decode(dev["x"], dev["w_router"], dev["w_gate"], dev["w_up"], dev["w_down"], L.k, k0, ws,
+                                 taps=True, cooperative=True)
+        torch.cuda.synchronize()
+        check_layer(oracle, L, k0, out.cpu().numpy(), {n: v.cpu().numpy() for n, v in tap.items()},
+                    "cooperative k0=%d" % k0)
+    B_.workspace_check(ws)
 
 
 def test_read_probe_runs_and_leaves_memory_alone(torch, B_):
