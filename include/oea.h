@@ -42,7 +42,8 @@ typedef enum {
                                    oea_workspace_init (or has been overwritten since) */
 } oea_status;
 
-/* storage type of x, W_router, W_gate, W_up, W_down (all the same) */
+/* storage type of x, W_router, W_gate, W_up, W_down (all the same).  Entry points take it as a
+ * plain int `dt` and answer any other value with OEA_ERR_DTYPE. */
 typedef enum { OEA_F32 = 0, OEA_BF16 = 1 } oea_dtype;
 
 #define OEA_MAX_N 512  /* experts */
@@ -157,7 +158,7 @@ int oea_route_general(const float *router_logits, const uint8_t *token_mask, int
  */
 int moe_decode(const void *x, const void *W_router, const void *W_gate, const void *W_up,
                const void *W_down, float *out, int B, int d, int N, int I, int k, int k0,
-               oea_dtype dt, void *workspace, size_t workspace_bytes, void *stream);
+               int dt, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Host, synchronises `stream`.  The single-kernel layer waits for other workgroups in a few places;
@@ -194,7 +195,7 @@ typedef struct {
 /* moe_decode with the extras above (ex == NULL behaves as moe_decode). */
 int moe_decode_ex(const void *x, const void *W_router, const void *W_gate, const void *W_up,
                   const void *W_down, float *out, int B, int d, int N, int I, int k, int k0,
-                  oea_dtype dt, void *workspace, size_t workspace_bytes, void *stream,
+                  int dt, void *workspace, size_t workspace_bytes, void *stream,
                   const oea_decode_ex *ex);
 
 /*
@@ -215,7 +216,7 @@ int moe_decode_ex(const void *x, const void *W_router, const void *W_gate, const
  */
 int moe_decode_static(const void *x, const void *W_router, const void *W_gate, const void *W_up,
                       const void *W_down, float *out, int B, int d, int N, int I, int k, int k0,
-                      oea_dtype dt, void *stream, const oea_decode_ex *ex);
+                      int dt, void *stream, const oea_decode_ex *ex);
 
 #ifdef __cplusplus
 }

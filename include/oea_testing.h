@@ -38,7 +38,7 @@ typedef struct {
  */
 int moe_decode_test(const void *x, const void *W_router, const void *W_gate, const void *W_up,
                     const void *W_down, float *out, int B, int d, int N, int I, int k, int k0,
-                    oea_dtype dt, void *workspace, size_t workspace_bytes, void *stream,
+                    int dt, void *workspace, size_t workspace_bytes, void *stream,
                     const oea_decode_ex *ex, const oea_test_opts *opts);
 
 /*

@@ -18,6 +18,21 @@ def build(force: bool = True) -> str:
     return LIB
 
 
+SAN_EXE = os.path.join(HERE, "oracle_sanitize")
+
+
+def build_sanitized() -> str:
+    """The oracle and its driver (sanitize_main.c) as one executable under AddressSanitizer and
+    UndefinedBehaviorSanitizer; a report aborts the run (-fno-sanitize-recover)."""
+    cmd = ["gcc", "-std=c11", "-O1", "-g", "-fopenmp", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+           "-fno-omit-frame-pointer", "-Wall", "-Wextra", "-o", SAN_EXE, SRC, os.path.join(HERE, "sanitize_main.c"),
+           "-lm"]
+    subprocess.check_call(cmd)
+    return SAN_EXE
+
+
 if __name__ == "__main__":
     print(build(force=True))
+    if sys.argv[1:2] == ["--sanitize"]:
+        print(build_sanitized())
     sys.exit(0)

@@ -160,9 +160,9 @@ extern "C" int oea_route_general(const float* router_logits, const uint8_t* toke
 // Argument checks shared by the layer entry points (everything but the workspace).
 static int check_decode_args(const void* x, const void* W_router, const void* W_gate, const void* W_up,
                              const void* W_down, const float* out, int B, int d, int N, int I, int k, int k0,
-                             oea_dtype dt) {
+                             int dt) {
   if (!x || !W_router || !W_gate || !W_up || !W_down || !out) return OEA_ERR_NULL;
-  int rc = check_decode_sizes(B, d, N, I, k, k0, (int)dt);
+  int rc = check_decode_sizes(B, d, N, I, k, k0, dt);
   if (rc != OEA_OK) return rc;
   if (!aligned16(x) || !aligned16(W_router) || !aligned16(W_gate) || !aligned16(W_up) || !aligned16(W_down) ||
       !aligned16(out))
@@ -172,9 +172,10 @@ static int check_decode_args(const void* x, const void* W_router, const void* W_
 
 // The layer on a checked workspace: carve it, enqueue the kernels and the taps.
 static int decode_enqueue(const void* x, const void* W_router, const void* W_gate, const void* W_up,
-                          const void* W_down, float* out, int B, int d, int N, int I, int k, int k0, oea_dtype dt,
+                          const void* W_down, float* out, int B, int d, int N, int I, int k, int k0, int dt_checked,
                           void* workspace, void* stream, const oea_decode_ex* ex,
                           const oea_test_opts* opts = nullptr) {
+  const oea_dtype dt = dt_checked == OEA_F32 ? OEA_F32 : OEA_BF16;  // check_decode_args has seen it
   const int path = opts ? opts->kernel_path : 0;
   if (path < 0 || path > 3) return OEA_ERR_SHAPE;
   const WsLayout w = ws_layout(B, d, N, I, k, elem_bytes_of(dt));
@@ -245,7 +246,7 @@ static int decode_enqueue(const void* x, const void* W_router, const void* W_gat
 
 extern "C" int moe_decode_ex(const void* x, const void* W_router, const void* W_gate, const void* W_up,
                              const void* W_down, float* out, int B, int d, int N, int I, int k, int k0,
-                             oea_dtype dt, void* workspace, size_t workspace_bytes, void* stream,
+                             int dt, void* workspace, size_t workspace_bytes, void* stream,
                              const oea_decode_ex* ex) {
   if (!workspace) return OEA_ERR_NULL;
   int rc = check_decode_args(x, W_router, W_gate, W_up, W_down, out, B, d, N, I, k, k0, dt);
@@ -257,7 +258,7 @@ extern "C" int moe_decode_ex(const void* x, const void* W_router, const void* W_
 
 extern "C" int moe_decode_test(const void* x, const void* W_router, const void* W_gate, const void* W_up,
                                const void* W_down, float* out, int B, int d, int N, int I, int k, int k0,
-                               oea_dtype dt, void* workspace, size_t workspace_bytes, void* stream,
+                               int dt, void* workspace, size_t workspace_bytes, void* stream,
                                const oea_decode_ex* ex, const oea_test_opts* opts) {
   if (!workspace) return OEA_ERR_NULL;
   int rc = check_decode_args(x, W_router, W_gate, W_up, W_down, out, B, d, N, I, k, k0, dt);
@@ -269,7 +270,7 @@ extern "C" int moe_decode_test(const void* x, const void* W_router, const void* 
 
 extern "C" int moe_decode(const void* x, const void* W_router, const void* W_gate, const void* W_up,
                           const void* W_down, float* out, int B, int d, int N, int I, int k, int k0,
-                          oea_dtype dt, void* workspace, size_t workspace_bytes, void* stream) {
+                          int dt, void* workspace, size_t workspace_bytes, void* stream) {
   return moe_decode_ex(x, W_router, W_gate, W_up, W_down, out, B, d, N, I, k, k0, dt, workspace,
                        workspace_bytes, stream, nullptr);
 }
@@ -293,7 +294,7 @@ std::mutex g_static_mutex;
 
 extern "C" int moe_decode_static(const void* x, const void* W_router, const void* W_gate, const void* W_up,
                                  const void* W_down, float* out, int B, int d, int N, int I, int k, int k0,
-                                 oea_dtype dt, void* stream, const oea_decode_ex* ex) {
+                                 int dt, void* stream, const oea_decode_ex* ex) {
   int rc = check_decode_args(x, W_router, W_gate, W_up, W_down, out, B, d, N, I, k, k0, dt);
   if (rc != OEA_OK) return rc;
   const size_t need = oea_workspace_bytes(B, d, N, I, k);

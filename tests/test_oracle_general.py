@@ -97,3 +97,71 @@ def test_hand_example_alg2(oracle):
     # token 1 ranking 1,2,3,0: walks rank 3 only -> expert 3 not in union; rank 4 (expert 0) is beyond maxP
     assert res["expert_idx"].tolist() == [[0, 1, 2], [1, 2, -1]]
     assert res["n_sel"].tolist() == [3, 2]
+
+
+# ---- brute force on tiny inputs against a set-based statement of Algorithm 2
+
+def alg2_by_sets(rank, mass, k0, p, k_max, max_p):
+    """Algorithm 2 written as set algebra, with no loop over ranks that stops early.
+    rank[i] = experts of token i from best to worst; mass[i][j] = softmax mass of the expert of rank j.
+      t_i   = least t with mass[i][0] + ... + mass[i][t-1] >= p        (p = 1: no cut)
+      n_i   = min(k0, t_i),  base_i = {rank[i][0..n_i-1]},  U = union of the base_i
+      C_i   = members of U outside base_i whose rank index is below max_p
+      S_i   = base_i + those members of C_i that have fewer than k_max - n_i members of C_i ranked above them
+    """
+    B, N = len(rank), len(rank[0])
+    n = []
+    for i in range(B):
+        if p >= 1.0:
+            t = N
+        else:
+            t = min(t for t in range(1, N + 1) if sum(mass[i][:t]) >= p)
+        n.append(min(k0, t))
+    base = [set(rank[i][:n[i]]) for i in range(B)]
+    U = set().union(*base)
+    S = []
+    for i in range(B):
+        pos = {e: j for j, e in enumerate(rank[i])}
+        C = {e for e in U - base[i] if pos[e] < max_p}
+        extra = {e for e in C if len({f for f in C if pos[f] < pos[e]}) < k_max - n[i]}
+        S.append(sorted(base[i] | extra, key=lambda e: pos[e]))
+    return n, sorted(U), S
+
+
+@pytest.mark.parametrize("N,B", [(4, 2), (3, 2), (4, 1), (2, 2)])
+def test_brute_force_all_rankings_alg2(oracle, N, B):
+    import itertools
+    # logits by rank; different spreads per token so that the top-p cut bites differently
+    levels = [np.array([2.0, 1.1, 0.3, -0.6])[:N], np.array([0.9, 0.5, 0.2, -0.1])[:N]]
+    masses = [np.exp(v) / np.exp(v).sum() for v in levels]
+    # thresholds strictly between the cumulative masses of both tokens (never on a knife edge), and 1 (no cut)
+    cums = sorted(set(np.round(np.concatenate([np.cumsum(m)[:-1] for m in masses]), 12).tolist()))
+    ps = [cums[0] * 0.5] + [(a + b) / 2 for a, b in zip(cums[:-1], cums[1:])] + [(cums[-1] + 1.0) / 2, 1.0]
+    for pv in ps[:-1]:
+        assert min(abs(pv - c) for c in cums) > 1e-3
+    perms = list(itertools.permutations(range(N)))
+    n_cases = 0
+    for ranks in itertools.product(perms, repeat=B):
+        lg = np.zeros((B, N), np.float32)
+        for i in range(B):
+            for j, e in enumerate(ranks[i]):
+                lg[i, e] = levels[i % 2][j]
+        mass = [masses[i % 2].tolist() for i in range(B)]
+        for k0 in range(1, N + 1):
+            for k_max in range(1, N + 1):
+                for max_p in range(1, N + 1):
+                    for pv in ps:
+                        res = oracle.route_general(lg, k0, pv, k_max, max_p)
+                        n, U, S = alg2_by_sets(ranks, mass, k0, pv, k_max, max_p)
+                        ctx = (ranks, k0, k_max, max_p, pv)
+                        assert res["n_base"].tolist() == n, ctx
+                        assert res["active_list"][:res["n_active"]].tolist() == U, ctx
+                        kw = max(k0, k_max)
+                        for i in range(B):
+                            assert res["n_sel"][i] == len(S[i]), ctx
+                            assert res["expert_idx"][i, :len(S[i])].tolist() == S[i], ctx
+                            assert (res["expert_idx"][i, len(S[i]):kw] == -1).all(), ctx
+                            w = np.array([mass[i][ranks[i].index(e)] for e in S[i]])
+                            assert np.allclose(res["gate_w"][i, :len(S[i])], w / w.sum(), atol=1e-12), ctx
+                        n_cases += 1
+    assert n_cases == len(perms) ** B * N ** 3 * len(ps)
