@@ -247,6 +247,22 @@ __device__ __forceinline__ void balance_shares(uint32_t* ctrl, uint32_t parity, 
   if (lane == 0) l_frac[G] = 1.f;
 }
 
+// A workgroup whose experts' pairs exceed the vectors its LDS holds (cap) walks them in pieces.  The
+// piece that starts at pair c0 ends at a boundary between experts whenever one lies within reach:
+// the rows of an expert are then streamed for one piece only (fused_stage hands out no tiles for a
+// segment without pairs in the piece); only a single expert with more than cap pairs has its rows
+// streamed once per piece.  e1 <= e2: ends of the first and second expert in the pair list [0, nvec).
+__device__ __forceinline__ int piece_end(int c0, int nvec, int cap, int e1, int e2) {
+  int c1 = c0 + cap < nvec ? c0 + cap : nvec;
+  if (c1 < nvec) {
+    if (e2 > c0 && e2 <= c1)
+      c1 = e2;
+    else if (e1 > c0 && e1 <= c1)
+      c1 = e1;
+  }
+  return c1;
+}
+
 // One mat-vec stage of the fused kernel.  Same tile loop as expert_stream_kernel; the routing
 // metadata comes from LDS, and `mid` runs once the first two weight tiles are in flight (it holds
 // the wait for the hidden vectors and their staging for the down stage).  Every workgroup calls mid.
@@ -311,9 +327,11 @@ __device__ __forceinline__ void fused_stage(const WT* wa, const WT* wb, WT* h_ou
   const int n_res = result_entries(sv);
   const bool use_buf = n_res <= ecap * kFfnWaves;
 
-  // tile i of the workgroup: the tiles of segment 0, then of segment 1, ...; none crosses an expert boundary
-  const int nt0 = (seg_n(sv, 0) + TROWS - 1) / TROWS, nt1 = (seg_n(sv, 1) + TROWS - 1) / TROWS;
-  const int nt2 = (seg_n(sv, 2) + TROWS - 1) / TROWS;
+  // tile i of the workgroup: the tiles of segment 0, then of segment 1, ...; none crosses an expert boundary.
+  // A segment none of whose pairs belongs to this piece has no tiles: its rows are not streamed.
+  const int nt0 = n0 > 0 ? (seg_n(sv, 0) + TROWS - 1) / TROWS : 0;
+  const int nt1 = n1 > 0 ? (seg_n(sv, 1) + TROWS - 1) / TROWS : 0;
+  const int nt2 = n2 > 0 ? (seg_n(sv, 2) + TROWS - 1) / TROWS : 0;
   // The wavefronts that start right away take their first two tiles by number (tile w, then tile
   // nw + w): with few tiles everybody gets one before anybody gets two.  The counter hands out the
   // tiles behind those (i < 0: the next tile from the counter).
@@ -699,6 +717,7 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedPara
   uint4* const l_vec = lds4 + 1 + fused_meta_words(B, N, k) / 4;
   const int d16 = d / EPL, I16 = I / EPL;
 
+  OEA_TL(0);
   const uint32_t magic = __hip_atomic_load(ctrl + kCtrlMagicWord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   uint32_t gen0 = 0;
   if (tid == 0 || tid == 64) gen0 = grid_generation(ctrl);
@@ -747,11 +766,13 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedPara
       }
     }
   }
+  OEA_TL(1);
   if (magic != kWsMagic) return;  // unprepared workspace: see moe_fused_kernel
   grid_arrive(ctrl, gen0 + 1);
   if (balanced && wave == 1)
     balance_shares(ctrl, uint32_t(__builtin_amdgcn_readfirstlane(int(gen0))), G, wg == 0, l_frac, lane, bal_in);
   grid_wait(ctrl, gen0 + 1, p.spin_limit);
+  OEA_TL(2);
 
   if (tid == 0) l_nact[1] = l_nact[2] = 0;
   const RouteOut lo{l_idx, l_gatew, l_nsel, l_active, l_nact, l_off, l_tok, l_gw};
@@ -781,25 +802,36 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedPara
   const int RB0 = uniform(int(l_route[2])), RB1 = uniform(int(l_route[3]));
 
   // pairs of the experts a row range touches: [first pair, count)
-  auto pairs_of = [&](int R0, int R1, int rows, int& off0, int& nvec) __attribute__((always_inline)) {
+  // ... and where the first and the second expert end in that list (for piece_end)
+  auto pairs_of = [&](int R0, int R1, int rows, int& off0, int& nvec, int& e1, int& e2) __attribute__((always_inline)) {
     off0 = 0;
-    nvec = 0;
+    nvec = e1 = e2 = 0;
     if (R0 >= R1) return;
     const int a0 = R0 / rows, a1 = (R1 - 1) / rows;
     off0 = uniform(l_off[a0]);
     nvec = uniform(l_off[a1 + 1]) - off0;
     if (off0 < 0 || nvec < 0 || off0 + nvec > P) nvec = 0;  // never true for a valid routing
+    e1 = uniform(l_off[a0 + 1]) - off0;
+    e2 = a1 > a0 ? uniform(l_off[a0 + 2]) - off0 : nvec;
+    e1 = e1 < 0 ? 0 : (e1 > nvec ? nvec : e1);
+    e2 = e2 < e1 ? e1 : (e2 > nvec ? nvec : e2);
   };
   const unsigned long long tA0 = wall_clock64();
+  OEA_TL(7);
+  OEA_TL_VAL(16, RA0);
+  OEA_TL_VAL(17, RA1);
+  OEA_TL_VAL(18, RB0);
+  OEA_TL_VAL(19, RB1);
 
   // ---- phase A: gate/up, in pieces of at most cap0 pairs
   {
-    int off0, nvec;
-    pairs_of(RA0, RA1, I, off0, nvec);
+    int off0, nvec, end1, end2;
+    pairs_of(RA0, RA1, I, off0, nvec, end1, end2);
     const int cap0 = p.cap_vec;
     float* const ebuf = reinterpret_cast<float*>(l_vec + (size_t)cap0 * d16);
-    for (int c0 = 0; c0 == 0 || c0 < nvec; c0 += cap0) {
-      const int c1 = c0 + cap0 < nvec ? c0 + cap0 : nvec;
+    int c0 = 0, c1 = 0;
+    do {  // at least once: a workgroup without rows still takes part in the barriers inside
+      c1 = piece_end(c0, nvec, cap0, end1, end2);
       if (c0 > 0) {  // the previous piece is flushed; hand the tiles out again
         __syncthreads();
         if (tid == 0) l_nact[1] = 0;
@@ -829,22 +861,26 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedPara
             __syncthreads();
           },
           c0, c1);
-    }
+      c0 = c1;
+    } while (c0 < nvec);
   }
   const unsigned long long tA1 = wall_clock64();
+  OEA_TL(8);
   signal_hidden_done(ctrl, RA0, RA1, I);
+  OEA_TL(9);
 
   // ---- phase B: down, in pieces of at most cap1 pairs
   unsigned long long tB0 = 0;
   {
-    int off0, nvec;
-    pairs_of(RB0, RB1, d, off0, nvec);
+    int off0, nvec, end1, end2;
+    pairs_of(RB0, RB1, d, off0, nvec, end1, end2);
     const int cap1 = p.cap_vec1;
     float* const ebuf = reinterpret_cast<float*>(l_vec + (size_t)cap1 * I16);
     const WT* const hsrc = static_cast<const WT*>(p.h);
     const uint32_t spin_limit = p.spin_limit;
-    for (int c0 = 0; c0 == 0 || c0 < nvec; c0 += cap1) {
-      const int c1 = c0 + cap1 < nvec ? c0 + cap1 : nvec;
+    int c0 = 0, c1 = 0;
+    do {
+      c1 = piece_end(c0, nvec, cap1, end1, end2);
       if (c0 > 0) {
         __syncthreads();
         if (tid == 0) l_nact[2] = 0;
@@ -887,10 +923,14 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedPara
               }
             }
             __syncthreads();
-            if (c0 == 0) tB0 = wall_clock64();
+            if (c0 == 0) {
+              tB0 = wall_clock64();
+              OEA_TL(12);
+            }
           },
           c0, c1);
-    }
+      c0 = c1;
+    } while (c0 < nvec);
   }
   if (balanced && tid == 0) {
     const unsigned long long tB1 = wall_clock64();
@@ -900,6 +940,8 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedPara
     __hip_atomic_store(reinterpret_cast<float*>(ctrl + kBalBase) + 2 * kBalMaxWg + wg, measured ? share / ticks : 0.f,
                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
+  OEA_TL(13);
+  OEA_TL_DRAINED(14);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -959,8 +1001,11 @@ __global__ __launch_bounds__(kFfnThreads) void expert_stage_kernel(StageParams p
     l_gw[i] = p.g.grp_gw[off0 + i];
   }
   const uint4* const vsrc = reinterpret_cast<const uint4*>(p.vec);
-  for (int c0 = 0; c0 < nvec; c0 += p.cap_vec) {
-    const int c1 = c0 + p.cap_vec < nvec ? c0 + p.cap_vec : nvec;
+  int end1 = l_off[a0 + 1] - off0, end2 = a1 > a0 ? l_off[a0 + 2] - off0 : nvec;
+  end1 = end1 < 0 ? 0 : (end1 > nvec ? nvec : end1);
+  end2 = end2 < end1 ? end1 : (end2 > nvec ? nvec : end2);
+  for (int c0 = 0, c1 = 0; c0 < nvec; c0 = c1) {
+    c1 = piece_end(c0, nvec, p.cap_vec, end1, end2);
     __syncthreads();  // the lists are written; the previous piece is done with the vector area
     if (tid == 0) *l_next = 0;
     for (int i16 = tid; i16 < (c1 - c0) * L16; i16 += kFfnThreads) {

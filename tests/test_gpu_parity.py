@@ -57,6 +57,8 @@ def assert_routing_equal(got, ref, ctx):
 ROUTE_CASES = [(B, N, k, k0, kind, seed)
                for (B, N, k) in [(4, 16, 4), (16, 128, 8), (3, 7, 5), (33, 64, 6), (1, 128, 8), (128, 128, 8),
                                  (16, 100, 8), (7, 200, 12), (5, 512, 32), (200, 130, 8), (16, 1, 1),
+                                 # several token groups with the keys kept in registers between the phases
+                                 (70, 64, 6), (100, 128, 8), (127, 128, 8), (256, 128, 8),
                                  (1024, 128, 8), (1024, 512, 32)]  # the last two: the size limits of the entry point
                for k0 in sorted({1, max(1, k // 2), k})
                for kind in W.LOGIT_KINDS
@@ -138,13 +140,14 @@ def check_layer(oracle, L, k0, out, tap, ctx, bias=None, mask=None):
 
 @pytest.mark.parametrize("name", ["toy", "mid_bf16", "mid_f32"])
 def test_small_layers_all_k0(torch, B_, oracle, name):
-    for seed in range(4):
+    for seed in range(32):
         L = W.make_layer(name, 100 + seed)
         for k0 in L.k0s:
             ctx = "%s seed=%d k0=%d" % (name, seed, k0)
             out, tap = run_layer(torch, B_, L, k0)
             err, _ = check_layer(oracle, L, k0, out, tap, ctx)
-            say(ctx, "T=%d err=%.2e" % (int(tap["n_active"][0]), err))
+            if seed < 2:
+                say(ctx, "T=%d err=%.2e" % (int(tap["n_active"][0]), err))
 
 
 @pytest.mark.parametrize("B", [1, 2, 5, 16, 33, 64, 300, 1024])  # 1024: the batch limit of the entry point
@@ -242,6 +245,31 @@ def test_full_size_30b_shape(torch, B_, oracle, name, seeds):
             say(ctx, "T=%d sum_n_sel=%d err=%.2e" % (ref["n_active"], int(ref["n_sel"].sum()), err))
 
 
+def with_inputs_of(L, B_, dev, name, seed, B=None):
+    """The layer L with the token batch and the router of another seed (its expert weights kept: they do
+    not enter the routing, and a full-size draw of them takes longer than everything else here)."""
+    other = W.make_layer(name, seed, B=B, I=8)  # cheap: only x, the router and the bias are used
+    Ln = W.Layer(**{**L.__dict__, "B": other.B, "x": other.x, "w_router": other.w_router,
+                    "router_bias": other.router_bias})
+    devn = dict(dev, x=B_.to_device(Ln.x), w_router=B_.to_device(Ln.w_router))
+    return Ln, devn
+
+
+def test_full_size_30b_eight_input_seeds(torch, B_, oracle):
+    """The benchmark configuration on eight seeds of token batch and router: two draws of the expert
+    weights, four draws of (x, W_router) on each; k0 = 3 and 8, every output element."""
+    for wseed in (2000, 2001):
+        L, dev = big_layer(B_, "qwen3_30b", wseed)
+        ws = B_.new_workspace(L.B, L.d, L.N, L.I, L.k)
+        for s in range(4):
+            Ln, devn = with_inputs_of(L, B_, dev, "qwen3_30b", 2500 + 10 * (wseed - 2000) + s)
+            for k0 in (3, 8):
+                ctx = "qwen3_30b weights %d inputs %d k0=%d" % (wseed, s, k0)
+                out, tap = run_layer_dev(torch, B_, Ln, devn, k0, ws=ws)
+                err, ref = check_layer(oracle, Ln, k0, out, tap, ctx)
+                say(ctx, "T=%d err=%.2e" % (ref["n_active"], err))
+
+
 def test_full_size_30b_every_k0_and_odd_batches(torch, B_, oracle):
     """Single-kernel path at the benchmark shape: every k0 from 1 to k at B=16, and batches of 3 and 7
     tokens cut from the same layer (a workgroup then owns rows of experts with a single pair)."""
@@ -304,26 +332,46 @@ def test_full_size_30b_batch_sweep(torch, B_, oracle):
     dev_w = {f: B_.to_device(getattr(L0, f)) for f in ("w_router", "w_gate", "w_up", "w_down")}
     # up to 32: single kernel with x resident; 64, 128: single kernel with per-workgroup staging;
     # 160: router kernel and the two stage kernels
-    for B in (1, 2, 8, 32, 64, 128, 160):
+    for B in (1, 2, 4, 8, 16, 32, 64, 128, 160):
         L = W.Layer(**{**L0.__dict__, "B": B, "x": np.ascontiguousarray(L0.x[:B])})
         dev = dict(dev_w, x=B_.to_device(L.x))
-        for k0 in ((3, 8) if B <= 32 else (3,)):
+        for k0 in (3, 5, 8):
             ctx = "30b-shape B=%d k0=%d" % (B, k0)
             out, tap = run_layer_dev(torch, B_, L, dev, k0)
             err, ref = check_layer(oracle, L, k0, out, tap, ctx)
             say(ctx, "T=%d err=%.2e" % (ref["n_active"], err))
+    # ragged batches through the kernel with per-workgroup staging: a last token group that is not full,
+    # padded tokens, a router bias, Phase 2 with and without rounds
+    rng = np.random.Generator(np.random.PCG64(77))
+    bias = (rng.standard_normal(L0.N) * 0.7).astype(np.float32)
+    for B in (33, 50, 100, 127):
+        L = W.Layer(**{**L0.__dict__, "B": B, "x": np.ascontiguousarray(L0.x[160 - B:])})
+        dev = dict(dev_w, x=B_.to_device(L.x))
+        mask = (rng.integers(0, 5, size=B) != 0).astype(np.uint8)
+        for k0 in (3, 8):
+            ctx = "30b-shape ragged B=%d k0=%d, mask and bias" % (B, k0)
+            out, tap = run_layer_dev(torch, B_, L, dev, k0, bias=bias, mask=mask)
+            err, ref = check_layer(oracle, L, k0, out, tap, ctx, bias=bias, mask=mask)
+            assert (out[mask == 0] == 0).all()
+            say(ctx, "T=%d live=%d err=%.2e" % (ref["n_active"], int(mask.sum()), err))
 
 
 def test_full_size_235b_shape(torch, B_, oracle):
     _BIG.clear()
     L = W.make_layer("qwen3_235b", 3000)
     dev = {f: B_.to_device(getattr(L, f)) for f in ("x", "w_router", "w_gate", "w_up", "w_down")}
-    for path in (0, 2):
-        for k0 in (3, 8):
-            ctx = "qwen3_235b path=%d k0=%d" % (path, k0)
-            out, tap = run_layer_dev(torch, B_, L, dev, k0, path=path)
-            err, ref = check_layer(oracle, L, k0, out, tap, ctx)
+    for k0 in range(1, L.k + 1):  # every k0, on two seeds of token batch and router
+        for s in (0, 1):
+            Ln, devn = (L, dev) if s == 0 else with_inputs_of(L, B_, dev, "qwen3_235b", 3100)
+            ctx = "qwen3_235b inputs %d k0=%d" % (s, k0)
+            out, tap = run_layer_dev(torch, B_, Ln, devn, k0)
+            err, ref = check_layer(oracle, Ln, k0, out, tap, ctx)
             say(ctx, "T=%d err=%.2e" % (ref["n_active"], err))
+    for k0 in (3, 8):  # the three-kernel path with the streaming expert kernels
+        ctx = "qwen3_235b path=2 k0=%d" % k0
+        out, tap = run_layer_dev(torch, B_, L, dev, k0, path=2)
+        err, ref = check_layer(oracle, L, k0, out, tap, ctx)
+        say(ctx, "T=%d err=%.2e" % (ref["n_active"], err))
     # a larger batch on the same weights: the single kernel with per-workgroup staging (vectors of
     # 8 KB leave room for about a dozen per workgroup, so pieces occur)
     L48 = W.make_layer("qwen3_235b", 3001, B=48, N=1, I=8)  # only its x is used
