@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--weight-sets", type=int, default=0, help="rotating expert-weight sets (0 = auto)")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="budget of the oracle timing")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--deterministic", action="store_true",
+                    help="time the layer with oea_decode_ex.deterministic (slot-ordered combine in a last kernel)")
     ap.add_argument("--no-other", action="store_true",
                     help="skip the other_workloads block (235B shape, skewed routing, other batch sizes)")
     ap.add_argument("--kernel-path", type=int, default=0, help="0 automatic (fused kernel), 1 generic, 2 three kernels")
@@ -371,7 +373,7 @@ def run(args):
     if cfg.get("skew"):
         xs_np = xs_np[:1]  # the skewed recipe ties x to the bias drawn with it
     xs = [binding.to_device(x, dev) for x in xs_np]
-    ws = binding.new_workspace(B, d, N, I, k, device=dev)
+    ws = binding.new_workspace(B, d, N, I, k, device=dev, deterministic=args.deterministic)
     out = torch.empty((B, d), dtype=torch.float32, device=dev)
     torch.cuda.synchronize()
     if args.verbose:
@@ -387,9 +389,10 @@ def run(args):
              ctypes.c_void_p(wset[2].data_ptr()), ctypes.c_void_p(out.data_ptr()), B, d, N, I, k, k0,
              binding.OEA_BF16, ctypes.c_void_p(ws.data_ptr()), ws_bytes, sptr]
         opts = opts if opts is not None else topts
-        if opts is None and bias is None:
+        if opts is None and bias is None and not args.deterministic:
             return lambda: lib.moe_decode(*a)
         exs = binding.DecodeEx()
+        exs.deterministic = 1 if args.deterministic else 0
         if bias is not None:
             exs.router_bias = bias.data_ptr()
         ref = ctypes.byref(exs)
@@ -403,7 +406,7 @@ def run(args):
     for ti, x in enumerate(xs):
         for k0 in k0s:
             _, tap = binding.moe_decode(x, w_router, *sets[0], k, k0, ws, out=out, router_bias=bias, taps=True,
-                                        kernel_path=args.kernel_path or None)
+                                        kernel_path=args.kernel_path or None, deterministic=args.deterministic)
             torch.cuda.synchronize()
             stats[(ti, k0)] = (int(tap["n_active"].item()), int(tap["n_sel"].sum().item()))
 
@@ -413,7 +416,7 @@ def run(args):
         import oracle
         ref = oracle.moe_decode(L.x, L.w_router, L.w_gate, L.w_up, L.w_down, k, args.k0, router_bias=L.router_bias)
         o, tap = binding.moe_decode(xs[0], w_router, *sets[0], k, args.k0, ws, router_bias=bias, taps=True,
-                                    kernel_path=args.kernel_path or None)
+                                    kernel_path=args.kernel_path or None, deterministic=args.deterministic)
         torch.cuda.synchronize()
         assert np.array_equal(tap["expert_idx"].cpu().numpy(), ref["expert_idx"]), "routing differs from the oracle"
         parity = float(np.abs(o.cpu().numpy() - ref["out"]).max() / np.abs(ref["out"]).max())
@@ -634,7 +637,7 @@ def run(args):
 
     # ---- the other configurations, and the two-term fit over everything timed in this run
     others, fit2 = None, None
-    if args.workload == "qwen3_30b" and args.kernel_path == 0 and not args.no_other:
+    if args.workload == "qwen3_30b" and args.kernel_path == 0 and not args.no_other and not args.deterministic:
         others = other_workloads(args, hip, sptr, stream, sets)
         cells = [(v["unique_experts"], v["pairs"], v["latency_us"]) for v in table.values()] + \
                 [(r_["unique_experts"], r_["pairs"], r_["latency_us"]) for r_ in others if r_["workload"] == "qwen3_30b"]
@@ -655,7 +658,8 @@ def run(args):
                 higher_is_better=False, scaling="weak", vs_baseline=None, dtype="bf16", data="synthetic",
                 config=dict(workload="%s B=%d d=%d N=%d I=%d k=%d, OEA k0=%d (k0=%d is plain top-k)"
                                      % (args.workload, B, d, N, I, k, args.k0, k),
-                            trials=len(xs), weight_sets=R, k0=args.k0, launch=args.launch),
+                            trials=len(xs), weight_sets=R, k0=args.k0, launch=args.launch,
+                            combine="deterministic (slot order, last kernel)" if args.deterministic else "fp32 atomics"),
                 topk_latency_us=topk_value,
                 latency_ratio_vs_topk=round(value / topk_value, 4),
                 unique_expert_ratio_vs_topk=round(table[str(args.k0)]["unique_experts"] / table[str(k)]["unique_experts"], 4),

@@ -59,6 +59,9 @@ const char *oea_status_string(int status);
 /* Host, pure.  Bytes of device workspace moe_decode needs for these sizes (0 on bad sizes). */
 size_t oea_workspace_bytes(int B, int d, int N, int I, int k);
 
+/* Host, pure.  The same for calls with oea_decode_ex.deterministic set (adds B*k*d floats). */
+size_t oea_workspace_bytes_deterministic(int B, int d, int N, int I, int k);
+
 /*
  * Prepare a workspace: enqueues a kernel that zeroes its control words and marks it as prepared.
  * Call once after allocating (or re-using for something else) a workspace, before the first
@@ -138,7 +141,9 @@ int oea_route_general(const float *router_logits, const uint8_t *token_mask, int
  *   W_gate   [N,I,d]  dt      per expert [I,d]: row j produces hidden unit j
  *   W_up     [N,I,d]  dt
  *   W_down   [N,d,I]  dt      per expert [d,I]: row c produces output coordinate c
- *   out      [B,d]    fp32    overwritten
+ *   out      [B,d]    fp32    overwritten.  The weighted sum over a token's experts is accumulated with
+ *                             fp32 atomics in arrival order (results of two calls can differ in the last
+ *                             places) unless oea_decode_ex.deterministic asks for a fixed order
  *   workspace         device scratch of >= oea_workspace_bytes(B,d,N,I,k) bytes, 16-byte aligned,
  *                     prepared once by oea_workspace_init.  Two calls that share a workspace must
  *                     be ordered on the same stream.
@@ -186,6 +191,11 @@ typedef struct {
   int32_t max_p;              /* general OEA: piggyback only among the max_p best ranks; 0 or >= N = off.
                                  With either set, k plays the role of k_max and the layer runs as three
                                  kernels. */
+  int32_t deterministic;      /* non-zero: Eq. 1's sum over the selected experts is taken in slot order by
+                                 one thread per output element (a last small kernel), instead of with
+                                 floating-point atomics in arrival order: `out` is then bit-identical from
+                                 call to call.  Needs oea_workspace_bytes_deterministic(...) bytes of
+                                 workspace; costs one more kernel launch (about 4 us at B=16). */
   int32_t cooperative;        /* non-zero: the single persistent kernel is launched as a cooperative
                                  launch, so the runtime guarantees that all its workgroups are resident
                                  together or refuses the launch (OEA_ERR_HIP) - for callers that share

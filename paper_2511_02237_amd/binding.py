@@ -18,7 +18,7 @@ OEA_OK = 0
 STATUS = {"OEA_ERR_NULL": -1, "OEA_ERR_SHAPE": -2, "OEA_ERR_K": -3, "OEA_ERR_ALIGN": -4,
           "OEA_ERR_WORKSPACE": -5, "OEA_ERR_DTYPE": -6, "OEA_ERR_HIP": -7, "OEA_ERR_TIMEOUT": -8,
           "OEA_ERR_LIMIT": -9, "OEA_ERR_WORKSPACE_STATE": -10}
-EXPORTS = ("oea_status_string", "oea_workspace_bytes", "oea_workspace_init", "oea_route", "oea_route_batched", "oea_route_general",
+EXPORTS = ("oea_status_string", "oea_workspace_bytes", "oea_workspace_bytes_deterministic", "oea_workspace_init", "oea_route", "oea_route_batched", "oea_route_general",
            "moe_decode", "moe_decode_ex", "moe_decode_static", "oea_workspace_check")
 TEST_EXPORTS = ("moe_decode_test", "oea_read_probe")  # include/oea_testing.h
 
@@ -34,7 +34,8 @@ class DecodeEx(ctypes.Structure):
                 ("logits_out", ctypes.c_void_p), ("expert_idx_out", ctypes.c_void_p),
                 ("gate_w_out", ctypes.c_void_p), ("n_sel_out", ctypes.c_void_p),
                 ("active_list_out", ctypes.c_void_p), ("n_active_out", ctypes.c_void_p),
-                ("top_p", ctypes.c_double), ("max_p", ctypes.c_int32), ("cooperative", ctypes.c_int32)]
+                ("top_p", ctypes.c_double), ("max_p", ctypes.c_int32), ("deterministic", ctypes.c_int32),
+                ("cooperative", ctypes.c_int32)]
 
 
 class TestOpts(ctypes.Structure):  # oea_test_opts of include/oea_testing.h
@@ -57,6 +58,8 @@ def lib():
         L.oea_status_string.argtypes = [ci]
         L.oea_workspace_bytes.restype = sz
         L.oea_workspace_bytes.argtypes = [ci] * 5
+        L.oea_workspace_bytes_deterministic.restype = sz
+        L.oea_workspace_bytes_deterministic.argtypes = [ci] * 5
         L.oea_workspace_init.restype = ci
         L.oea_workspace_init.argtypes = [vp, sz, vp]
         L.oea_route.restype = ci
@@ -107,13 +110,14 @@ def _dtype_code(t):
     raise TypeError("x and weights must be float32 or bfloat16, got %s" % t.dtype)
 
 
-def workspace_bytes(B, d, N, I, k):
-    return int(lib().oea_workspace_bytes(B, d, N, I, k))
+def workspace_bytes(B, d, N, I, k, deterministic=False):
+    f = lib().oea_workspace_bytes_deterministic if deterministic else lib().oea_workspace_bytes
+    return int(f(B, d, N, I, k))
 
 
-def new_workspace(B, d, N, I, k, device="cuda", stream=None):
+def new_workspace(B, d, N, I, k, device="cuda", stream=None, deterministic=False):
     """Allocate (torch) and prepare (library) a workspace for moe_decode."""
-    n = workspace_bytes(B, d, N, I, k)
+    n = workspace_bytes(B, d, N, I, k, deterministic)
     if n == 0:
         raise OeaError(STATUS["OEA_ERR_SHAPE"], status_string(STATUS["OEA_ERR_SHAPE"]))
     ws = torch.empty(n, dtype=torch.uint8, device=device)
@@ -212,15 +216,16 @@ def _layer_args(x, w_router, w_gate, w_up, w_down, k, k0, out):
     return args, out, (B, d, N, I)
 
 
-def _extras(shape, k, dev, router_bias, token_mask, taps, top_p, max_p, cooperative=False):
+def _extras(shape, k, dev, router_bias, token_mask, taps, top_p, max_p, cooperative=False, deterministic=False):
     """The oea_decode_ex struct for the optional inputs and taps (None if none is asked for)."""
     B, d, N, I = shape
     if not taps and router_bias is None and token_mask is None and top_p is None and max_p is None \
-            and not cooperative:
+            and not cooperative and not deterministic:
         return None, None
     ex = DecodeEx()
     tap = None
     ex.cooperative = 1 if cooperative else 0
+    ex.deterministic = 1 if deterministic else 0
     if top_p is not None:
         ex.top_p = float(top_p)
     if max_p is not None:
@@ -262,13 +267,13 @@ def test_opts(kernel_path=None, spin_limit=None, kernel_events=None):
 
 def moe_decode(x, w_router, w_gate, w_up, w_down, k, k0, workspace, out=None, stream=None,
                router_bias=None, token_mask=None, taps=False, top_p=None, max_p=None, cooperative=False,
-               kernel_path=None, spin_limit=None, kernel_events=None):
+               deterministic=False, kernel_path=None, spin_limit=None, kernel_events=None):
     """One decode-time MoE layer with OEA routing.  Returns out [B,d] float32 (and a dict of routing
     taps when taps=True).  kernel_path, spin_limit and kernel_events are the test aids of
     moe_decode_test."""
     args, out, shape = _layer_args(x, w_router, w_gate, w_up, w_down, k, k0, out)
     args += [_ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)]
-    ex, tap = _extras(shape, k, x.device, router_bias, token_mask, taps, top_p, max_p, cooperative)
+    ex, tap = _extras(shape, k, x.device, router_bias, token_mask, taps, top_p, max_p, cooperative, deterministic)
     opts = test_opts(kernel_path, spin_limit, kernel_events)
     if opts is not None:
         _check(lib().moe_decode_test(*args, None if ex is None else ctypes.byref(ex), ctypes.byref(opts)))
@@ -280,11 +285,11 @@ def moe_decode(x, w_router, w_gate, w_up, w_down, k, k0, workspace, out=None, st
 
 
 def moe_decode_static(x, w_router, w_gate, w_up, w_down, k, k0, out=None, stream=None, router_bias=None,
-                      token_mask=None, taps=False, top_p=None, max_p=None):
+                      token_mask=None, taps=False, top_p=None, max_p=None, deterministic=False):
     """moe_decode on the scratch built into the library (no workspace argument, nothing allocated by
     the call; pass `out` to keep torch from allocating the result too)."""
     args, out, shape = _layer_args(x, w_router, w_gate, w_up, w_down, k, k0, out)
-    ex, tap = _extras(shape, k, x.device, router_bias, token_mask, taps, top_p, max_p)
+    ex, tap = _extras(shape, k, x.device, router_bias, token_mask, taps, top_p, max_p, False, deterministic)
     _check(lib().moe_decode_static(*args, _stream(stream), None if ex is None else ctypes.byref(ex)))
     return (out, tap) if taps else out
 

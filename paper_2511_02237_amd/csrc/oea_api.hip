@@ -13,7 +13,6 @@ static size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
 static constexpr size_t kCtrlWords = 1024 + 2 * 128 * 32 + 3 * 256;  // see WsLayout::ctrl
 
 WsLayout ws_layout(int B, int d, int N, int I, int k, int elem_bytes) {
-  (void)d;
   WsLayout w{};
   size_t off = 0;
   auto take = [&](size_t bytes) {
@@ -33,7 +32,10 @@ WsLayout ws_layout(int B, int d, int N, int I, int k, int elem_bytes) {
   w.grp_tok = take(P * sizeof(int32_t));
   w.grp_gw = take(P * sizeof(float));
   w.h = take(P * (size_t)I * elem_bytes);
+  w.grp_pos = take(P * sizeof(int32_t));
   w.total = off;
+  w.y = take(P * (size_t)d * sizeof(float));
+  w.total_with_y = off;
   return w;
 }
 
@@ -84,6 +86,11 @@ extern "C" size_t oea_workspace_bytes(int B, int d, int N, int I, int k) {
       d > OEA_MAX_D || I > OEA_MAX_D)
     return 0;
   return ws_layout(B, d, N, I, k, 4).total;  // sized for the wider storage type
+}
+
+extern "C" size_t oea_workspace_bytes_deterministic(int B, int d, int N, int I, int k) {
+  if (oea_workspace_bytes(B, d, N, I, k) == 0) return 0;
+  return ws_layout(B, d, N, I, k, 4).total_with_y;
 }
 
 extern "C" int oea_read_probe(const void* buf, size_t bytes, void* sink, void* stream) {
@@ -170,6 +177,11 @@ static int check_decode_args(const void* x, const void* W_router, const void* W_
   return OEA_OK;
 }
 
+// workspace bytes a call needs: more with the deterministic combine
+static size_t workspace_need(int B, int d, int N, int I, int k, const oea_decode_ex* ex) {
+  return ex && ex->deterministic ? oea_workspace_bytes_deterministic(B, d, N, I, k) : oea_workspace_bytes(B, d, N, I, k);
+}
+
 // The layer on a checked workspace: carve it, enqueue the kernels and the taps.
 static int decode_enqueue(const void* x, const void* W_router, const void* W_gate, const void* W_up,
                           const void* W_down, float* out, int B, int d, int N, int I, int k, int k0, int dt_checked,
@@ -185,7 +197,12 @@ static int decode_enqueue(const void* x, const void* W_router, const void* W_gat
   RouteOut ro{reinterpret_cast<int32_t*>(ws + w.expert_idx), reinterpret_cast<float*>(ws + w.gate_w),
               reinterpret_cast<int32_t*>(ws + w.n_sel),      reinterpret_cast<int32_t*>(ws + w.active_list),
               reinterpret_cast<int32_t*>(ws + w.n_active),   reinterpret_cast<int32_t*>(ws + w.grp_off),
-              reinterpret_cast<int32_t*>(ws + w.grp_tok),    reinterpret_cast<float*>(ws + w.grp_gw)};
+              reinterpret_cast<int32_t*>(ws + w.grp_tok),    reinterpret_cast<float*>(ws + w.grp_gw),
+              reinterpret_cast<int32_t*>(ws + w.grp_pos)};
+  // deterministic combine: the down stage adds each pair's weighted result into a row of its own
+  // (zeroed first; a single add per element, so the order of the adds cannot matter), and a last
+  // kernel sums the rows of every token in slot order
+  float* const y = ex && ex->deterministic ? reinterpret_cast<float*>(ws + w.y) : nullptr;
   Grouping g{ro.active_list, ro.n_active, ro.grp_off, ro.grp_tok, ro.grp_gw};
   void* h = ws + w.h;
 
@@ -204,7 +221,7 @@ static int decode_enqueue(const void* x, const void* W_router, const void* W_gat
     e = try_launch_fused(x, W_router, W_gate, W_up, W_down, ex ? ex->router_bias : nullptr,
                          ex ? ex->token_mask : nullptr, out, logits, h, ro,
                          reinterpret_cast<uint32_t*>(ws + w.ctrl), B, d, N, I, k, k0, dt, s,
-                         opts ? opts->spin_limit : 0u, ex && ex->cooperative != 0);
+                         opts ? opts->spin_limit : 0u, ex && ex->cooperative != 0, y);
   if (e == hipSuccess) {  // one kernel: the inner event pairs collapse onto its end
     for (int i = 1; i < 6; ++i)
       if (!mark(i)) return OEA_ERR_HIP;
@@ -212,20 +229,23 @@ static int decode_enqueue(const void* x, const void* W_router, const void* W_gat
     return OEA_ERR_HIP;
   } else {
     e = launch_router_and_route(x, W_router, ex ? ex->router_bias : nullptr, ex ? ex->token_mask : nullptr, B, d,
-                                N, k, k0, dt, logits, out, reinterpret_cast<uint32_t*>(ws + w.ctrl), ro,
-                                general ? &ga : nullptr, s);
+                                N, k, k0, dt, logits, y ? y : out, y ? (size_t)B * k * d : (size_t)B * d,
+                                reinterpret_cast<uint32_t*>(ws + w.ctrl), ro, general ? &ga : nullptr, s);
     if (e != hipSuccess || !mark(1) || !mark(2)) return OEA_ERR_HIP;
     const bool stage_kernels = path == 0 || path == 3;
     const bool generic_only = path == 1;
-    e = stage_kernels ? try_launch_stage_kernels(0, x, W_gate, W_up, h, nullptr, B, d, N, I, k, dt, g, s)
+    e = stage_kernels ? try_launch_stage_kernels(0, x, W_gate, W_up, h, nullptr, B, d, N, I, k, dt, g, false, s)
                       : hipErrorNotSupported;
     if (e == hipErrorNotSupported) e = launch_expert_gate_up(x, W_gate, W_up, h, B, d, N, I, k, dt, g, generic_only, s);
     if (e != hipSuccess || !mark(3) || !mark(4)) return OEA_ERR_HIP;
-    e = stage_kernels ? try_launch_stage_kernels(1, h, W_down, nullptr, nullptr, out, B, d, N, I, k, dt, g, s)
+    e = stage_kernels ? try_launch_stage_kernels(1, h, W_down, nullptr, nullptr, y ? y : out, B, d, N, I, k, dt, g,
+                                                 y != nullptr, s)
                       : hipErrorNotSupported;
-    if (e == hipErrorNotSupported) e = launch_expert_down(h, W_down, out, B, d, N, I, k, dt, g, generic_only, s);
+    if (e == hipErrorNotSupported)
+      e = launch_expert_down(h, W_down, y ? y : out, B, d, N, I, k, dt, g, generic_only, y != nullptr, s);
     if (e != hipSuccess || !mark(5)) return OEA_ERR_HIP;
   }
+  if (y && launch_combine(y, ro.grp_pos, ro.n_sel, out, B, d, k, s) != hipSuccess) return OEA_ERR_HIP;
 
   if (ex) {  // taps: device-to-device copies in stream order
     const size_t P = (size_t)B * k;
@@ -252,7 +272,7 @@ extern "C" int moe_decode_ex(const void* x, const void* W_router, const void* W_
   int rc = check_decode_args(x, W_router, W_gate, W_up, W_down, out, B, d, N, I, k, k0, dt);
   if (rc != OEA_OK) return rc;
   if (!aligned16(workspace)) return OEA_ERR_ALIGN;
-  if (workspace_bytes < oea_workspace_bytes(B, d, N, I, k)) return OEA_ERR_WORKSPACE;
+  if (workspace_bytes < workspace_need(B, d, N, I, k, ex)) return OEA_ERR_WORKSPACE;
   return decode_enqueue(x, W_router, W_gate, W_up, W_down, out, B, d, N, I, k, k0, dt, workspace, stream, ex);
 }
 
@@ -264,7 +284,7 @@ extern "C" int moe_decode_test(const void* x, const void* W_router, const void* 
   int rc = check_decode_args(x, W_router, W_gate, W_up, W_down, out, B, d, N, I, k, k0, dt);
   if (rc != OEA_OK) return rc;
   if (!aligned16(workspace)) return OEA_ERR_ALIGN;
-  if (workspace_bytes < oea_workspace_bytes(B, d, N, I, k)) return OEA_ERR_WORKSPACE;
+  if (workspace_bytes < workspace_need(B, d, N, I, k, ex)) return OEA_ERR_WORKSPACE;
   return decode_enqueue(x, W_router, W_gate, W_up, W_down, out, B, d, N, I, k, k0, dt, workspace, stream, ex, opts);
 }
 
@@ -297,7 +317,7 @@ extern "C" int moe_decode_static(const void* x, const void* W_router, const void
                                  int dt, void* stream, const oea_decode_ex* ex) {
   int rc = check_decode_args(x, W_router, W_gate, W_up, W_down, out, B, d, N, I, k, k0, dt);
   if (rc != OEA_OK) return rc;
-  const size_t need = oea_workspace_bytes(B, d, N, I, k);
+  const size_t need = workspace_need(B, d, N, I, k, ex);
   if (need == 0 || need > (size_t)OEA_STATIC_SCRATCH_BYTES) return OEA_ERR_LIMIT;  // before any HIP call
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return OEA_ERR_HIP;

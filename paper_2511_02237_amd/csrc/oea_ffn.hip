@@ -33,6 +33,7 @@ struct FfnParams {
   int N;
   int B;
   int pairs_max;     // B*k: size of the grouping arrays
+  int per_pair;      // stage 1: `out` has one row per PAIR (deterministic combine): pair p adds into row p
   int tok_cap;       // generic kernel: token vectors that fit in LDS at once
   int cap_vec;       // streaming kernel: capacity of the staged (expert, token) pair list
   Grouping g;
@@ -148,8 +149,8 @@ __global__ __launch_bounds__(kFfnThreads) void expert_kernel(FfnParams p) {
             } else {
               const float y = row_sum<LPR>(acc[0][rg]);
               if (lsub == 0 && row < my_hi) {
-                const int t = p.g.grp_tok[pidx];
-                if ((unsigned)t < (unsigned)p.B)
+                const int t = p.per_pair ? pidx : p.g.grp_tok[pidx];
+                if ((unsigned)t < (unsigned)(p.per_pair ? p.pairs_max : p.B))
                   unsafeAtomicAdd(p.out + (size_t)t * rows + row, p.g.grp_gw[pidx] * y);
               }
             }
@@ -240,7 +241,9 @@ __global__ __launch_bounds__(kFfnThreads) void expert_stream_kernel(FfnParams p)
   const uint4* const vsrc = reinterpret_cast<const uint4*>(STAGE == 0 || nvec == 0 ? vec : vec + (size_t)off0 * L);
   const int i_first = nvec == 0 ? 0 : (tid < nvec ? tid : nvec - 1);
   const int src_first = off0 + i_first < p.pairs_max ? off0 + i_first : 0;
-  const int tok_first = p.g.grp_tok[src_first];
+  // the row of `out` a pair adds into: its token, or (per_pair) the pair itself
+  const int row_limit = STAGE == 1 && p.per_pair ? p.pairs_max : p.B;
+  const int tok_first = STAGE == 1 && p.per_pair ? src_first : p.g.grp_tok[src_first];
   const float gw_first = p.g.grp_gw[src_first];
   if (STAGE == 1) {
 #pragma unroll
@@ -278,7 +281,7 @@ __global__ __launch_bounds__(kFfnThreads) void expert_stream_kernel(FfnParams p)
   {
     int* const dump_i = reinterpret_cast<int*>(lds4);
     float* const dump_f = reinterpret_cast<float*>(lds4) + 1;
-    *(tid < nvec ? l_tok + tid : dump_i) = tok_first < 0 ? 0 : (tok_first >= p.B ? p.B - 1 : tok_first);
+    *(tid < nvec ? l_tok + tid : dump_i) = tok_first < 0 ? 0 : (tok_first >= row_limit ? row_limit - 1 : tok_first);
     *(tid < nvec ? l_gw + tid : dump_f) = gw_first;
 #pragma unroll
     for (int j = 0; j < kStageBatch; ++j) {
@@ -287,8 +290,8 @@ __global__ __launch_bounds__(kFfnThreads) void expert_stream_kernel(FfnParams p)
     }
   }
   for (int i = tid + kFfnThreads; i < nvec; i += kFfnThreads) {  // only for very large batches
-    int t = p.g.grp_tok[off0 + i];
-    l_tok[i] = t < 0 ? 0 : (t >= p.B ? p.B - 1 : t);
+    int t = STAGE == 1 && p.per_pair ? off0 + i : p.g.grp_tok[off0 + i];
+    l_tok[i] = t < 0 ? 0 : (t >= row_limit ? row_limit - 1 : t);
     l_gw[i] = p.g.grp_gw[off0 + i];
   }
   for (int i16 = kStageBatch * kFfnThreads + tid; i16 < n16; i16 += kFfnThreads) l_vec[i16] = vsrc[i16];
@@ -446,6 +449,39 @@ bool current_device(int* dev, int* cus) {
   return true;
 }
 
+namespace {
+// Deterministic combine (Eq. 1 with the sum over the selected experts taken in slot order): one
+// thread per four output coordinates of a token.  y holds gate weight x expert output per pair.
+__global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ y, const int32_t* __restrict__ grp_pos,
+                                                      const int32_t* __restrict__ n_sel, float* __restrict__ out,
+                                                      int B, int d, int k, int pairs) {
+  const int t = blockIdx.x;
+  int n = n_sel[t];
+  n = n < 0 ? 0 : (n > k ? k : n);
+  for (int c4 = blockIdx.y * 256 + threadIdx.x; c4 < d / 4; c4 += gridDim.y * 256) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s = 0; s < n; ++s) {
+      const int pos = grp_pos[t * k + s];
+      if ((unsigned)pos >= (unsigned)pairs) continue;  // never true after a valid routing
+      const float4 v = reinterpret_cast<const float4*>(y + (size_t)pos * d)[c4];
+      acc.x += v.x;
+      acc.y += v.y;
+      acc.z += v.z;
+      acc.w += v.w;
+    }
+    reinterpret_cast<float4*>(out + (size_t)t * d)[c4] = acc;
+  }
+}
+}  // namespace
+
+hipError_t launch_combine(const float* y, const int32_t* grp_pos, const int32_t* n_sel, float* out, int B, int d,
+                          int k, hipStream_t s) {
+  const int chunks = (d / 4 + 255) / 256;
+  hipLaunchKernelGGL(combine_kernel, dim3(B, chunks > 8 ? 8 : chunks), dim3(256), 0, s, y, grp_pos, n_sel, out, B, d, k,
+                     B * k);
+  return hipGetLastError();
+}
+
 hipError_t launch_read_probe(const void* buf, size_t bytes, uint32_t* sink, hipStream_t s) {
   hipLaunchKernelGGL(read_probe_kernel, dim3(num_cus()), dim3(kFfnThreads), 0, s, static_cast<const uint4*>(buf),
                      bytes / 16, sink);
@@ -472,7 +508,7 @@ hipError_t launch_expert_gate_up(const void* x, const void* w_gate, const void* 
 }
 
 hipError_t launch_expert_down(const void* h, const void* w_down, float* out, int B, int d, int N, int I,
-                              int k, oea_dtype dt, Grouping g, bool generic_only, hipStream_t s) {
+                              int k, oea_dtype dt, Grouping g, bool generic_only, bool per_pair, hipStream_t s) {
   FfnParams p{};
   p.B = B;
   p.pairs_max = B * k;
@@ -485,6 +521,7 @@ hipError_t launch_expert_down(const void* h, const void* w_down, float* out, int
   p.L = I;
   p.N = N;
   p.g = g;
+  p.per_pair = per_pair ? 1 : 0;
   return dt == OEA_F32 ? launch_stage<float>(1, p, B, k, generic_only, s)
                        : launch_stage<uint16_t>(1, p, B, k, generic_only, s);
 }

@@ -44,6 +44,8 @@ struct FusedParams {
   const float* bias;
   const uint8_t* token_mask;
   float* out;
+  float* acc;      // what the down stage adds into: out [B,d], or (deterministic combine) y [B*k, d], one row per pair
+  int acc_rows;    // its rows: B or B*k
   float* logits;   // [B,N] workspace
   void* h;         // [B*k, I] workspace
   RouteOut ro;     // global copies of the routing result, written by workgroup 0
@@ -489,11 +491,11 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
 
   {  // clear this workgroup's slice of out[B,d] (d is a multiple of 8: float4 granules)
     // written through to memory: phase B adds to these words with device-scope atomics from every XCD
-    const int total = B * d;
+    const int total = p.acc_rows * d;
     const int per = (total + G - 1) / G;
     const int lo = per * wg, hi = lo + per < total ? lo + per : total;
     for (int i = lo + tid; i < hi; i += kFfnThreads)
-      __hip_atomic_store(p.out + i, 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(p.acc + i, 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 
   // per-expert completion counters of the gate/up stage: cleared here, before the first grid barrier
@@ -565,7 +567,8 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   // ---- phase R2: routing, replicated per workgroup, result in LDS.  Every row of 16 lanes reads
   // its token's logits straight from memory (device-coherent loads: written by other workgroups).
   if (tid == 0) l_nact[1] = l_nact[2] = 0;  // tile counters of the two stages (a barrier follows in the routing)
-  const RouteOut lo{l_idx, l_gatew, l_nsel, l_active, l_nact, l_off, l_tok, l_gw};
+  // (the positions of the pairs in the grouped order go straight to memory, from workgroup 0 only)
+  const RouteOut lo{l_idx, l_gatew, l_nsel, l_active, l_nact, l_off, l_tok, l_gw, wg == 0 ? p.ro.grp_pos : nullptr};
   uint32_t* const ctrl = p.ctrl;
   const float* const frac = balanced ? l_frac : nullptr;
   uint32_t* const l_cut = l_route + 48;  // [4] inside the routing scratch's block-scan words, unused at N <= 128
@@ -614,6 +617,12 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   OEA_TL(8);
   signal_hidden_done(p.ctrl, RA0, RA1, I);
   OEA_TL(9);
+  // Row of p.acc a pair adds into: its token, or with one row per pair the pair itself (the list of
+  // selected experts in LDS has been published and is not read any more: it becomes that identity)
+  const bool per_pair = p.acc_rows != B;
+  if (per_pair)
+    for (int i = tid; i < P; i += kFfnThreads) l_idx[i] = i;  // ordered before its use by the barriers in mid_b
+  const int* const l_rowof = per_pair ? l_idx : l_tok;
   // ---- phase B: down.  mid = barrier (h complete everywhere), then this workgroup's h rows -> LDS
   const WT* const hsrc = static_cast<const WT*>(p.h);
   const int I16 = I / EPL;
@@ -669,8 +678,8 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
         tB0 = wall_clock64();
       };
   fused_stage<WT, 1, LPR1, NCH1, 2>(
-      static_cast<const WT*>(p.w_down), static_cast<const WT*>(nullptr), static_cast<WT*>(nullptr), p.out, d, I, RB0,
-      RB1, N, P, p.cap_vec, l_active, l_off, l_tok, l_gw, l_vec,
+      static_cast<const WT*>(p.w_down), static_cast<const WT*>(nullptr), static_cast<WT*>(nullptr), p.acc, d, I, RB0,
+      RB1, N, P, p.cap_vec, l_active, l_off, l_rowof, l_gw, l_vec,
       reinterpret_cast<float*>(l_vec + (size_t)cap_vec * I16), p.ecap1, reinterpret_cast<uint32_t*>(l_nact + 2), mid_b,
       0, 0x7fffffff, n_defer);
   if (balanced && tid == 0) {  // this workgroup's speed in this call: cost share per clock tick of streaming
@@ -725,11 +734,11 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedPara
   BalanceIn bal_in{};
   if (balanced && wave == 1) bal_in = balance_load(ctrl, uint32_t(__builtin_amdgcn_readfirstlane(int(gen0))), G, lane);
   {  // clear this workgroup's slice of out[B,d]
-    const int total = B * d;
+    const int total = p.acc_rows * d;
     const int per = (total + G - 1) / G;
     const int lo = per * wg, hi = lo + per < total ? lo + per : total;
     for (int i = lo + tid; i < hi; i += kFfnThreads)
-      __hip_atomic_store(p.out + i, 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(p.acc + i, 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   if (wg == 0 && tid < N) {
     __hip_atomic_store(done_count(ctrl, tid), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -775,7 +784,8 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedPara
   OEA_TL(2);
 
   if (tid == 0) l_nact[1] = l_nact[2] = 0;
-  const RouteOut lo{l_idx, l_gatew, l_nsel, l_active, l_nact, l_off, l_tok, l_gw};
+  // (the positions of the pairs in the grouped order go straight to memory, from workgroup 0 only)
+  const RouteOut lo{l_idx, l_gatew, l_nsel, l_active, l_nact, l_off, l_tok, l_gw, wg == 0 ? p.ro.grp_pos : nullptr};
   route_rows_groups<4 * NV, kFfnThreads, 4, true>(p.logits, p.token_mask, B, N, k, p.k0, lo, l_route);  // B <= 128
   __syncthreads();
   if (wg == 0) {  // publish the routing result
@@ -868,6 +878,10 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedPara
   OEA_TL(8);
   signal_hidden_done(ctrl, RA0, RA1, I);
   OEA_TL(9);
+  const bool per_pair = p.acc_rows != B;  // see moe_fused_kernel
+  if (per_pair)
+    for (int i = tid; i < P; i += kFfnThreads) l_idx[i] = i;
+  const int* const l_rowof = per_pair ? l_idx : l_tok;
 
   // ---- phase B: down, in pieces of at most cap1 pairs
   unsigned long long tB0 = 0;
@@ -887,8 +901,8 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedPara
         __syncthreads();
       }
       fused_stage<WT, 1, LPR1, NCH1, 2, true>(
-          static_cast<const WT*>(p.w_down), static_cast<const WT*>(nullptr), static_cast<WT*>(nullptr), p.out, d, I,
-          RB0, RB1, N, P, cap1, l_active, l_off, l_tok, l_gw, l_vec, ebuf, p.ecap1,
+          static_cast<const WT*>(p.w_down), static_cast<const WT*>(nullptr), static_cast<WT*>(nullptr), p.acc, d, I,
+          RB0, RB1, N, P, cap1, l_active, l_off, l_rowof, l_gw, l_vec, ebuf, p.ecap1,
           reinterpret_cast<uint32_t*>(l_nact + 2),
           [&](int a0, int nseg) {
             if (c0 == 0) {  // wait, bounded, until the hidden vectors of this workgroup's experts are complete
@@ -961,6 +975,7 @@ struct StageParams {
   int cap_vec;   // vectors of length L the LDS vector area holds
   int cap_list;  // entries of the staged pair lists
   int ecap;      // floats of result buffer per wavefront
+  int per_pair;  // stage 1: `out` has one row per pair (deterministic combine)
 };
 
 template <typename WT, int STAGE, int LPR, int NCH, int RG>
@@ -996,8 +1011,10 @@ __global__ __launch_bounds__(kFfnThreads) void expert_stage_kernel(StageParams p
   if (nvec > p.cap_list) nvec = p.cap_list;  // cap_list >= kMaxSeg * B covers every valid routing
   // pair lists of this workgroup's experts; addressed by the global pair number below
   for (int i = tid; i < nvec; i += kFfnThreads) {
-    const int t = p.g.grp_tok[off0 + i];
-    l_tok[i] = t < 0 ? 0 : (t >= p.B ? p.B - 1 : t);
+    const bool rowof_pair = STAGE == 1 && p.per_pair;
+    const int t = rowof_pair ? off0 + i : p.g.grp_tok[off0 + i];
+    const int lim = rowof_pair ? p.pairs_max : p.B;
+    l_tok[i] = t < 0 ? 0 : (t >= lim ? lim - 1 : t);
     l_gw[i] = p.g.grp_gw[off0 + i];
   }
   const uint4* const vsrc = reinterpret_cast<const uint4*>(p.vec);
@@ -1092,7 +1109,8 @@ hipError_t launch_fused_gather_one(const FusedParams& p, int grid, size_t lds_by
 hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_gate, const void* w_up,
                             const void* w_down, const float* bias, const uint8_t* token_mask, float* out,
                             float* logits, void* h, RouteOut ro, uint32_t* ctrl, int B, int d, int N, int I,
-                            int k, int k0, oea_dtype dt, hipStream_t s, uint32_t spin_limit, bool cooperative) {
+                            int k, int k0, oea_dtype dt, hipStream_t s, uint32_t spin_limit, bool cooperative,
+                            float* y_per_pair) {
   if (dt != OEA_BF16 || N > 128 || B > 128 || k > 16) return hipErrorNotSupported;
   const bool shape30 = d == 2048 && I == 768, shape235 = d == 4096 && I == 1536;
   if (!shape30 && !shape235) return hipErrorNotSupported;
@@ -1151,6 +1169,8 @@ hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_g
   p.bias = bias;
   p.token_mask = token_mask;
   p.out = out;
+  p.acc = y_per_pair ? y_per_pair : out;
+  p.acc_rows = y_per_pair ? B * k : B;
   p.logits = logits;
   p.h = h;
   p.ro = ro;
@@ -1178,7 +1198,7 @@ hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_g
 // fused kernel does not take); hipErrorNotSupported for shapes they are not built for.
 hipError_t try_launch_stage_kernels(int stage, const void* vec, const void* wa, const void* wb, void* h_out,
                                     float* out, int B, int d, int N, int I, int k, oea_dtype dt, Grouping g,
-                                    hipStream_t s) {
+                                    bool per_pair, hipStream_t s) {
   if (dt != OEA_BF16 || N > 128) return hipErrorNotSupported;
   const bool shape30 = d == 2048 && I == 768, shape235 = d == 4096 && I == 1536;
   if (!shape30 && !shape235) return hipErrorNotSupported;
@@ -1201,6 +1221,7 @@ hipError_t try_launch_stage_kernels(int stage, const void* vec, const void* wa, 
   p.N = N;
   p.B = B;
   p.pairs_max = B * k;
+  p.per_pair = per_pair ? 1 : 0;
   if (shape30)
     return stage == 0 ? launch_stage_one<uint16_t, 0, 32, 8, 1>(p, grid, s)
                       : launch_stage_one<uint16_t, 1, 16, 6, 2>(p, grid, s);

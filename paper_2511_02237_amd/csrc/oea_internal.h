@@ -55,7 +55,10 @@ struct WsLayout {
   size_t grp_tok;      // int32 [B*k]  token of each (expert, token) pair, grouped by expert
   size_t grp_gw;       // float [B*k]  gate weight of that pair
   size_t h;            // storage type [B*k, I]  hidden activations of each pair
-  size_t total;
+  size_t grp_pos;      // int32 [B*k]  position of (token, slot) in the grouped pair order, -1 for an unused slot
+  size_t total;        // bytes without the area below (what oea_workspace_bytes reports)
+  size_t y;            // float [B*k, d]  deterministic combine only: weighted down-projection of each pair
+  size_t total_with_y; // what oea_workspace_bytes_deterministic reports
 };
 
 WsLayout ws_layout(int B, int d, int N, int I, int k, int elem_bytes);
@@ -78,6 +81,7 @@ struct RouteOut {
   int32_t* grp_off;  // may be nullptr (routing-only entry point)
   int32_t* grp_tok;  // may be nullptr
   float* grp_gw;     // may be nullptr
+  int32_t* grp_pos;  // may be nullptr: [B*k] position of each (token, slot) in the grouped order
 };
 
 // parameters of the general OEA routing (Algorithm 2) beyond k0: top-p threshold, cap, rank window
@@ -95,7 +99,7 @@ hipError_t launch_route(const float* logits, const uint8_t* token_mask, int L, i
                         RouteOut o, hipStream_t s);
 hipError_t launch_router_and_route(const void* x, const void* w_router, const float* bias,
                                    const uint8_t* token_mask, int B, int d, int N, int k, int k0,
-                                   oea_dtype dt, float* logits, float* out_to_zero, uint32_t* counter,
+                                   oea_dtype dt, float* logits, float* to_zero, size_t n_zero, uint32_t* counter,
                                    RouteOut o, const RouteGeneralArgs* general, hipStream_t s);
 hipError_t launch_route_general(const float* logits, const uint8_t* token_mask, int B, int N, int k0,
                                 const RouteGeneralArgs& ga, int32_t* n_base, RouteOut o, hipStream_t s);
@@ -103,20 +107,24 @@ hipError_t launch_route_general(const float* logits, const uint8_t* token_mask, 
 hipError_t launch_expert_gate_up(const void* x, const void* w_gate, const void* w_up, void* h, int B,
                                  int d, int N, int I, int k, oea_dtype dt, Grouping g, bool generic_only,
                                  hipStream_t s);
+// per_pair: `out` is the [B*k, d] buffer of the deterministic combine; pair p adds its weighted result to row p
 hipError_t launch_expert_down(const void* h, const void* w_down, float* out, int B, int d, int N, int I,
-                              int k, oea_dtype dt, Grouping g, bool generic_only, hipStream_t s);
+                              int k, oea_dtype dt, Grouping g, bool generic_only, bool per_pair, hipStream_t s);
+// out[t, :] = sum over the slots of token t, in slot order, of y[grp_pos[t, slot], :]  (Eq. 1 in a fixed order)
+hipError_t launch_combine(const float* y, const int32_t* grp_pos, const int32_t* n_sel, float* out, int B, int d,
+                          int k, hipStream_t s);
 
 // whole layer in one persistent kernel; hipErrorNotSupported if the shape is not one it is built for
 hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_gate, const void* w_up,
                             const void* w_down, const float* bias, const uint8_t* token_mask, float* out,
                             float* logits, void* h, RouteOut ro, uint32_t* ctrl, int B, int d, int N, int I,
                             int k, int k0, oea_dtype dt, hipStream_t s, uint32_t spin_limit = 0,
-                            bool cooperative = false);
+                            bool cooperative = false, float* y_per_pair = nullptr);
 
 // one expert stage (0 gate/up, 1 down) with the fused kernel's stage code, for larger batches
 hipError_t try_launch_stage_kernels(int stage, const void* vec, const void* wa, const void* wb, void* h_out,
                                     float* out, int B, int d, int N, int I, int k, oea_dtype dt, Grouping g,
-                                    hipStream_t s);
+                                    bool per_pair, hipStream_t s);
 
 hipError_t launch_read_probe(const void* buf, size_t bytes, uint32_t* sink, hipStream_t s);
 size_t route_lds_bytes(int B, int N);

@@ -57,7 +57,7 @@ template <typename WT, int NV>
 __global__ __launch_bounds__(kRouteThreads) void router_route_kernel(
     const WT* __restrict__ x, const WT* __restrict__ w_router, const float* __restrict__ bias,
     const uint8_t* token_mask, int B, int d, int N, int k, int k0, float* logits, float* out_to_zero,
-    uint32_t* counter, RouteOut o, RouteGeneral g, int general) {
+    size_t n_zero, uint32_t* counter, RouteOut o, RouteGeneral g, int general) {
   extern __shared__ uint32_t lds[];
   constexpr int EPL = 16 / int(sizeof(WT));
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -65,8 +65,9 @@ __global__ __launch_bounds__(kRouteThreads) void router_route_kernel(
   // `counter` is the first control word of the workspace; every thread reads the same magic word
   const uint32_t magic = counter[kCtrlMagicWord];
 
-  {  // clear this workgroup's slice of out[B,d] (d is a multiple of 8, so float4 granules)
-    const size_t total4 = (size_t)B * d / 4;
+  {  // clear this workgroup's slice of what the down projection adds into: out[B,d], or the per-pair
+     // buffer of the deterministic combine (n_zero floats, a multiple of 8: float4 granules)
+    const size_t total4 = n_zero / 4;
     const size_t per = (total4 + gridDim.x - 1) / gridDim.x;
     const size_t lo = per * e, hi = lo + per < total4 ? lo + per : total4;
     float4* o4 = reinterpret_cast<float4*>(out_to_zero);
@@ -192,7 +193,7 @@ hipError_t launch_route(const float* logits, const uint8_t* token_mask, int L, i
 
 template <typename WT>
 static hipError_t launch_rr(const void* x, const void* w_router, const float* bias, const uint8_t* token_mask,
-                            int B, int d, int N, int k, int k0, float* logits, float* out_to_zero,
+                            int B, int d, int N, int k, int k0, float* logits, float* out_to_zero, size_t n_zero,
                             uint32_t* counter, RouteOut o, const RouteGeneralArgs* ga, hipStream_t s) {
   RouteGeneral g{1.0, k, N, nullptr};
   const int general = ga && (ga->p < 1.0 || ga->max_p < N) ? 1 : 0;
@@ -208,7 +209,7 @@ static hipError_t launch_rr(const void* x, const void* w_router, const float* bi
     }                                                                                                      \
     hipLaunchKernelGGL((router_route_kernel<WT, NV>), dim3(N), dim3(kRouteThreads), lds, s,                \
                        static_cast<const WT*>(x), static_cast<const WT*>(w_router), bias, token_mask, B, d, \
-                       N, k, k0, logits, out_to_zero, counter, o, g, general);                             \
+                       N, k, k0, logits, out_to_zero, n_zero, counter, o, g, general);                     \
   } break;
     OEA_CASE(1)
     OEA_CASE(2)
@@ -221,11 +222,11 @@ static hipError_t launch_rr(const void* x, const void* w_router, const float* bi
 
 hipError_t launch_router_and_route(const void* x, const void* w_router, const float* bias,
                                    const uint8_t* token_mask, int B, int d, int N, int k, int k0,
-                                   oea_dtype dt, float* logits, float* out_to_zero, uint32_t* counter,
+                                   oea_dtype dt, float* logits, float* to_zero, size_t n_zero, uint32_t* counter,
                                    RouteOut o, const RouteGeneralArgs* ga, hipStream_t s) {
   if (dt == OEA_F32)
-    return launch_rr<float>(x, w_router, bias, token_mask, B, d, N, k, k0, logits, out_to_zero, counter, o, ga, s);
-  return launch_rr<uint16_t>(x, w_router, bias, token_mask, B, d, N, k, k0, logits, out_to_zero, counter, o, ga, s);
+    return launch_rr<float>(x, w_router, bias, token_mask, B, d, N, k, k0, logits, to_zero, n_zero, counter, o, ga, s);
+  return launch_rr<uint16_t>(x, w_router, bias, token_mask, B, d, N, k, k0, logits, to_zero, n_zero, counter, o, ga, s);
 }
 
 hipError_t launch_route_general(const float* logits, const uint8_t* token_mask, int B, int N, int k0,

@@ -203,13 +203,17 @@ __device__ __forceinline__ void route_group(int B, int N, int k, RouteOut o, uin
   // ---- one thread per (token, slot) pair; inside an expert, pairs are in token order
   for (int p = tid; p < B * k; p += NT) {
     const int ex = o.expert_idx[p];
-    if (ex < 0) continue;
+    if (ex < 0) {
+      if (o.grp_pos) o.grp_pos[p] = -1;
+      continue;
+    }
     const int t = p / k;
     int rank = __popc(colmask[ex * NWB + (t >> 5)] & ((1u << (t & 31)) - 1u));
     for (int w = 0; w < (t >> 5); ++w) rank += __popc(colmask[ex * NWB + w]);
     const int dst = int(eoff[ex]) + rank;
     o.grp_tok[dst] = t;
     o.grp_gw[dst] = o.gate_w[p];
+    if (o.grp_pos) o.grp_pos[p] = dst;
   }
 }
 

@@ -15,7 +15,8 @@ static hipError_t reached(const char* what) {
 hipError_t launch_ws_prepare(uint32_t*, size_t, hipStream_t) { return reached("ws_prepare"); }
 hipError_t launch_route(const float*, const uint8_t*, int, int, int, int, int, RouteOut, hipStream_t) { return reached("route"); }
 hipError_t launch_router_and_route(const void*, const void*, const float*, const uint8_t*, int, int, int, int, int,
-                                   oea_dtype, float*, float*, uint32_t*, RouteOut, const RouteGeneralArgs*, hipStream_t) {
+                                   oea_dtype, float*, float*, size_t, uint32_t*, RouteOut, const RouteGeneralArgs*,
+                                   hipStream_t) {
   return reached("router_and_route");
 }
 hipError_t launch_route_general(const float*, const uint8_t*, int, int, int, const RouteGeneralArgs&, int32_t*, RouteOut,
@@ -27,17 +28,20 @@ hipError_t launch_expert_gate_up(const void*, const void*, const void*, void*, i
   return reached("gate_up");
 }
 hipError_t launch_expert_down(const void*, const void*, float*, int, int, int, int, int, oea_dtype, Grouping, bool,
-                              hipStream_t) {
+                              bool, hipStream_t) {
   return reached("down");
 }
 hipError_t try_launch_fused(const void*, const void*, const void*, const void*, const void*, const float*,
                             const uint8_t*, float*, float*, void*, RouteOut, uint32_t*, int, int, int, int, int, int,
-                            oea_dtype, hipStream_t, uint32_t, bool) {
+                            oea_dtype, hipStream_t, uint32_t, bool, float*) {
   return reached("fused");
 }
 hipError_t try_launch_stage_kernels(int, const void*, const void*, const void*, void*, float*, int, int, int, int, int,
-                                    oea_dtype, Grouping, hipStream_t) {
+                                    oea_dtype, Grouping, bool, hipStream_t) {
   return reached("stage_kernels");
+}
+hipError_t launch_combine(const float*, const int32_t*, const int32_t*, float*, int, int, int, hipStream_t) {
+  return reached("combine");
 }
 hipError_t launch_read_probe(const void*, size_t, uint32_t*, hipStream_t) { return reached("read_probe"); }
 }  // namespace oea
@@ -91,6 +95,15 @@ int main() {
   oea_decode_ex ex;
   std::memset(&ex, 0, sizeof ex);
   EXPECT(moe_decode_ex(P, P, P, P, P, F, 16, 2048, 128, 768, 8, 3, OEA_BF16, P, 1024, nullptr, &ex), OEA_ERR_WORKSPACE);
+  ex.deterministic = 1;  // needs the larger workspace
+  EXPECT(moe_decode_ex(P, P, P, P, P, F, 16, 2048, 128, 768, 8, 3, OEA_BF16, P, oea_workspace_bytes(16, 2048, 128, 768, 8),
+                       nullptr, &ex),
+         OEA_ERR_WORKSPACE);
+  if (oea_workspace_bytes_deterministic(16, 2048, 128, 768, 8) !=
+      oea_workspace_bytes(16, 2048, 128, 768, 8) + (size_t)16 * 8 * 2048 * 4)
+    ++failures;
+  EXPECT(moe_decode_static(P, P, P, P, P, F, 128, 4096, 128, 1536, 8, 3, OEA_BF16, nullptr, &ex), OEA_ERR_LIMIT);
+  ex.deterministic = 0;
   oea_test_opts opts;
   std::memset(&opts, 0, sizeof opts);
   opts.kernel_path = 7;

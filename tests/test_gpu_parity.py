@@ -605,6 +605,51 @@ def test_unprepared_workspace_is_reported_at_once(torch, B_, oracle):
         assert err.value.code == B_.STATUS["OEA_ERR_WORKSPACE_STATE"]
 
 
+def test_deterministic_combine_is_bit_reproducible(torch, B_, oracle):
+    """oea_decode_ex.deterministic: the sum over a token's experts (Eq. 1) is taken in slot order, so
+    `out` is the same bits on every call, on every kernel path; it still matches the oracle."""
+    L30 = W.make_layer("qwen3_30b", 97, B=160)
+    dev30 = {f: B_.to_device(getattr(L30, f)) for f in ("w_router", "w_gate", "w_up", "w_down")}
+    cases = []
+    for B in (16, 5, 64, 160):  # single kernel (two batch ranges), then router kernel + stage kernels
+        Ls = W.Layer(**{**L30.__dict__, "B": B, "x": np.ascontiguousarray(L30.x[:B])})
+        cases.append(("30b-shape B=%d" % B, Ls, dict(dev30, x=B_.to_device(Ls.x)), None, 3))
+    Lm = W.make_layer("mid_bf16", 98)
+    devm = {f: B_.to_device(getattr(Lm, f)) for f in ("x", "w_router", "w_gate", "w_up", "w_down")}
+    Lf = W.make_layer("mid_f32", 99)
+    devf = {f: B_.to_device(getattr(Lf, f)) for f in ("x", "w_router", "w_gate", "w_up", "w_down")}
+    cases += [("mid_bf16 streaming kernels", Lm, devm, 2, 3), ("mid_bf16 generic kernels", Lm, devm, 1, 3),
+              ("mid_f32", Lf, devf, None, 2)]
+    for name, L, dev, path, k0 in cases:
+        ws = B_.new_workspace(L.B, L.d, L.N, L.I, L.k, deterministic=True)
+        first = None
+        for it in range(20 if L.B <= 16 else 6):
+            out, tap = B_.moe_decode(dev["x"], dev["w_router"], dev["w_gate"], dev["w_up"], dev["w_down"], L.k, k0, ws,
+                                     taps=True, deterministic=True, kernel_path=path)
+            torch.cuda.synchronize()
+            o = out.cpu().numpy()
+            if first is None:
+                first = o
+                err, ref = check_layer(oracle, L, k0, o, {n: v.cpu().numpy() for n, v in tap.items()}, "deterministic " + name)
+                say("deterministic %s: T=%d err=%.2e" % (name, ref["n_active"], err))
+            else:
+                assert np.array_equal(o.view(np.uint32), first.view(np.uint32)), "%s: call %d differs" % (name, it)
+        B_.workspace_check(ws)
+    # the smaller workspace is refused when the flag is set
+    L, dev = cases[0][1], cases[0][2]
+    with pytest.raises(B_.OeaError) as e:
+        B_.moe_decode(dev["x"], dev["w_router"], dev["w_gate"], dev["w_up"], dev["w_down"], L.k, 3,
+                      B_.new_workspace(L.B, L.d, L.N, L.I, L.k), deterministic=True)
+    assert e.value.code == B_.STATUS["OEA_ERR_WORKSPACE"]
+    # padded tokens come out as zero rows
+    mask = np.ones(L.B, np.uint8)
+    mask[[2, 9]] = 0
+    ws = B_.new_workspace(L.B, L.d, L.N, L.I, L.k, deterministic=True)
+    out = B_.moe_decode(dev["x"], dev["w_router"], dev["w_gate"], dev["w_up"], dev["w_down"], L.k, 3, ws,
+                        token_mask=torch.from_numpy(mask).cuda(), deterministic=True).cpu().numpy()
+    assert (out[[2, 9]] == 0).all() and np.abs(out[0]).max() > 0
+
+
 def test_cooperative_launch_option(torch, B_, oracle):
     """oea_decode_ex.cooperative: the single kernel through a cooperative launch (co-residency is then
     the runtime's guarantee); same results."""

@@ -25,7 +25,8 @@ class Ex(ctypes.Structure):  # oea_decode_ex of include/oea.h
                 ("logits_out", ctypes.c_void_p), ("expert_idx_out", ctypes.c_void_p),
                 ("gate_w_out", ctypes.c_void_p), ("n_sel_out", ctypes.c_void_p),
                 ("active_list_out", ctypes.c_void_p), ("n_active_out", ctypes.c_void_p),
-                ("top_p", ctypes.c_double), ("max_p", ctypes.c_int32), ("cooperative", ctypes.c_int32)]
+                ("top_p", ctypes.c_double), ("max_p", ctypes.c_int32), ("deterministic", ctypes.c_int32),
+                ("cooperative", ctypes.c_int32)]
 
 
 def say(*a):
