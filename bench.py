@@ -53,6 +53,9 @@ def parse():
     ap.add_argument("--route-positions", type=int, default=0,
                     help="instead of the layer: time oea_route_batched over this many decode positions of the workload's "
                          "B, N, k at --k0 (the routing step alone, as a simulation over a trace would call it)")
+    ap.add_argument("--route-general", action="store_true",
+                    help="instead of the layer: time oea_route_general (Algorithm 2) at p in {0.5, 1} and maxP in {8, N} "
+                         "beside oea_route (Algorithm 1) on the workload's B, N, k at --k0, one batch per launch")
     ap.add_argument("--timeline", type=int, default=0, metavar="CALLS",
                     help="instead of the report: per-workgroup phase stamps of the single-kernel layer, averaged over "
                          "this many calls; needs the measurement build of the library (python -m "
@@ -117,6 +120,8 @@ def main():
         return route_throughput(args)
     if args.timeline:
         return timeline(args)
+    if args.route_general:
+        return route_general_latency(args)
     print(json.dumps(run(args)))
 
 
@@ -205,6 +210,7 @@ def timeline(args):
             continue
         t = buf.reshape(n_slots, n_wg).astype(np.int64)
         rel = (t[:len(TIMELINE_SLOTS)] - t[0].min()) / 100.0  # us
+        rel[(t[:len(TIMELINE_SLOTS)] < t[0].min()).any(axis=1)] = np.nan  # not stamped by this kernel (an older launch's value)
         acc_med = acc_med + np.median(rel, axis=1)
         acc_max = acc_max + rel.max(axis=1)
         acc_min = acc_min + rel.min(axis=1)
@@ -212,12 +218,52 @@ def timeline(args):
     n = args.timeline
     rows = [dict(slot=i, phase=TIMELINE_SLOTS[i], first_wg_us=round(float(acc_min[i] / n), 2),
                  median_wg_us=round(float(acc_med[i] / n), 2), slowest_wg_us=round(float(acc_max[i] / n), 2))
-            for i in range(len(TIMELINE_SLOTS))]
+            for i in range(len(TIMELINE_SLOTS)) if np.isfinite(acc_med[i])]
     print(json.dumps(dict(workload="%s B=%d k0=%d" % (args.workload, B, args.k0), calls=n,
                           mean_unique_experts=round(float(np.mean(Ts)), 2), timeline=rows)))
     for r in rows:
         print("| %2d | %-42s | %7.2f | %7.2f | %7.2f |" % (r["slot"], r["phase"], r["first_wg_us"], r["median_wg_us"],
                                                        r["slowest_wg_us"]), file=sys.stderr)
+
+
+def route_general_latency(args):
+    """Routing alone, one decode batch per launch: Algorithm 1 (oea_route) and Algorithm 2
+    (oea_route_general: top-p cut of the baseline, k^max, rank window maxP) on seeded Gaussian logits.
+    Back-to-back launches on one stream; the figure is launch period, i.e. kernel plus dispatch gap."""
+    import torch
+
+    from paper_2511_02237_amd import binding, workloads
+    assert args.gpus == 1 and torch.cuda.is_available()
+    cfg = workloads.CONFIGS[args.workload]
+    N, k, B = cfg["N"], cfg["k"], args.batch
+    lg = torch.from_numpy(workloads.make_logits(B, N, 4242, "gaussian")).cuda()
+    rows = []
+
+    hip = Hip()
+    e0, e1 = hip.event(), hip.event()
+    sptr = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+    def timed(name, fn):
+        res = fn(None)  # the output tensors are allocated once and reused
+        for _ in range(args.warmup):
+            fn(res)
+        torch.cuda.synchronize()
+        hip.record(e0, sptr)
+        for _ in range(args.steps):
+            fn(res)
+        hip.record(e1, sptr)
+        torch.cuda.synchronize()
+        us = hip.elapsed_ms(e0, e1) / args.steps * 1e3
+        rows.append(dict(routing=name, us_per_call=round(us, 2), unique_experts=int(res["n_active"].item()),
+                         mean_experts_per_token=round(float(res["n_sel"].float().mean().item()), 2)))
+
+    timed("Algorithm 1: k0=%d, k=%d" % (args.k0, k), lambda o: binding.oea_route(lg, k, args.k0, out=o))
+    for p_, maxp in ((1.0, N), (0.5, N), (1.0, 8), (0.5, 8)):
+        timed("Algorithm 2: k0=%d, p=%g, k_max=%d, maxP=%d" % (args.k0, p_, k, maxp),
+              lambda o, p_=p_, maxp=maxp: binding.oea_route_general(lg, args.k0, p_, k, maxp, out=o))
+    print(json.dumps(dict(metric="OEA routing latency per decode batch (us), B=%d N=%d" % (B, N), unit="us", n_gpus=1,
+                          steps=args.steps, warmup=args.warmup, dtype="f32", data="synthetic",
+                          config=dict(workload="%s routing, one batch per launch" % args.workload), rows=rows)))
 
 
 def sweep(args):
@@ -346,8 +392,9 @@ def run(args):
     d, N, I, k = cfg["d"], cfg["N"], cfg["I"], cfg["k"]
     B = args.batch
     k0s = [int(v) for v in args.k0s.split(",")] if args.k0s else list(range(1, k + 1))
-    if args.k0 not in k0s:
-        k0s.append(args.k0)
+    for must in (args.k0, k):  # the headline k0 and plain top-k are always timed
+        if must not in k0s:
+            k0s.append(must)
     expert_bytes = 3 * d * I * 2
     # enough sets that a full rotation exceeds the infinity cache several times over
     R = args.weight_sets or max(8, int(np.ceil(4 * 256e6 / (N * expert_bytes))) + 1)
@@ -513,6 +560,11 @@ def run(args):
     per_call_us = {str(k0): per_call(k0, R) for k0 in sorted({args.k0, k})}
     cache_warm_us = {str(k0): per_call(k0, 1) for k0 in sorted({args.k0, k})}
 
+    # ---- the other configurations (before the headline passes, which stay the last launches of the layer)
+    others = None
+    if args.workload == "qwen3_30b" and args.kernel_path == 0 and not args.no_other and not args.deterministic:
+        others = other_workloads(args, hip, sptr, stream, sets)
+
     # ---- the headline timing: back-to-back calls in which the TOKEN BATCH changes from call to call as
     # well as the weight set (a server never sees the same batch twice, so the per-workgroup speed
     # weights cannot settle on one routing pattern).  `warmup` untimed calls, then exactly `steps`
@@ -636,9 +688,8 @@ def run(args):
                           "token batch 0 / weight set 0 of the timed workload" % (reps, args.k0))
 
     # ---- the other configurations, and the two-term fit over everything timed in this run
-    others, fit2 = None, None
-    if args.workload == "qwen3_30b" and args.kernel_path == 0 and not args.no_other and not args.deterministic:
-        others = other_workloads(args, hip, sptr, stream, sets)
+    fit2 = None
+    if others is not None:
         cells = [(v["unique_experts"], v["pairs"], v["latency_us"]) for v in table.values()] + \
                 [(r_["unique_experts"], r_["pairs"], r_["latency_us"]) for r_ in others if r_["workload"] == "qwen3_30b"]
         A2 = np.array([[1.0, c[0], c[1]] for c in cells])

@@ -177,7 +177,7 @@ def oea_route_batched(router_logits, k, k0, token_mask=None, stream=None):
     return out
 
 
-def oea_route_general(router_logits, k0, p, k_max, max_p, token_mask=None, stream=None):
+def oea_route_general(router_logits, k0, p, k_max, max_p, token_mask=None, stream=None, out=None):
     """General OEA routing (Algorithm 2).  Returns dict(expert_idx [B,kw], gate_w, n_sel, n_base,
     active_list, n_active) on device, kw = max(k0, k_max)."""
     assert router_logits.is_cuda and router_logits.dtype == torch.float32 and router_logits.is_contiguous()
@@ -186,12 +186,13 @@ def oea_route_general(router_logits, k0, p, k_max, max_p, token_mask=None, strea
     kw = max(int(k0), int(k_max))
     if token_mask is not None:
         assert token_mask.is_cuda and token_mask.dtype == torch.uint8 and token_mask.numel() == B
-    out = dict(expert_idx=torch.empty((B, kw), dtype=torch.int32, device=dev),
-               gate_w=torch.empty((B, kw), dtype=torch.float32, device=dev),
-               n_sel=torch.empty((B,), dtype=torch.int32, device=dev),
-               n_base=torch.empty((B,), dtype=torch.int32, device=dev),
-               active_list=torch.empty((N,), dtype=torch.int32, device=dev),
-               n_active=torch.empty((1,), dtype=torch.int32, device=dev))
+    if out is None:
+        out = dict(expert_idx=torch.empty((B, kw), dtype=torch.int32, device=dev),
+                   gate_w=torch.empty((B, kw), dtype=torch.float32, device=dev),
+                   n_sel=torch.empty((B,), dtype=torch.int32, device=dev),
+                   n_base=torch.empty((B,), dtype=torch.int32, device=dev),
+                   active_list=torch.empty((N,), dtype=torch.int32, device=dev),
+                   n_active=torch.empty((1,), dtype=torch.int32, device=dev))
     _check(lib().oea_route_general(_ptr(router_logits), _ptr(token_mask), B, N, int(k0), float(p), int(k_max),
                                    int(max_p), _ptr(out["expert_idx"]), _ptr(out["gate_w"]), _ptr(out["n_sel"]),
                                    _ptr(out["n_base"]), _ptr(out["active_list"]), _ptr(out["n_active"]),
