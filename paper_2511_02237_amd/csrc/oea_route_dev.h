@@ -109,13 +109,15 @@ __device__ __forceinline__ int wave_incl_scan_i32(int v, int lane) {
 // Tail of the first half: the members of the union bit mask U (lds[0..15]) in ascending order ->
 // o.active_list, their number -> *o.n_active.  Called by all NT threads after a barrier that
 // completes U; the results are complete after the caller's next barrier.
+// Expert e is handled by thread ebase + e (ebase a multiple of 64): with ebase > 0 the wavefronts
+// below it have nothing to do here and go on at once.
 template <int NT>
-__device__ __forceinline__ void route_active(int N, RouteOut o, uint32_t* lds) {
-  const int tid = threadIdx.x;
+__device__ __forceinline__ void route_active(int N, RouteOut o, uint32_t* lds, int ebase = 0) {
+  const int e = int(threadIdx.x) - ebase;
+  if (e < 0) return;
   const uint32_t* U = lds;
   // position of expert e among the members = members below it, counted from the mask words
   // themselves (at most 16 of them): no scan across the wavefronts, no barrier
-  const int e = tid;
   const int nw = (N + 31) >> 5;
   int T = 0, pos = 0;
   for (int w = 0; w < nw; ++w) {
@@ -128,7 +130,7 @@ __device__ __forceinline__ void route_active(int N, RouteOut o, uint32_t* lds) {
   pos += __popc(mine & ((1u << (e & 31)) - 1u));
   if (in_u) o.active_list[pos] = e;
   if (e < N && e >= T) o.active_list[e] = -1;
-  if (tid == 0) *o.n_active = T;
+  if (e == 0) *o.n_active = T;
 }
 
 
@@ -141,8 +143,33 @@ __device__ __forceinline__ void route_active(int N, RouteOut o, uint32_t* lds) {
 struct NoHook {
   __device__ __forceinline__ void operator()() const {}
 };
+// What the offsets need from the union mask alone (complete since the end of Phase 1): computed
+// before the barrier that ends Phase 2, by the threads that will compute the offsets after it.
+struct GroupPre {
+  int e;      // this thread's expert (threadIdx.x - ebase); < 0: none
+  int T;      // members of U
+  int pos;    // members below e
+  bool in_u;  // e is a member
+};
+template <int NT>
+__device__ __forceinline__ GroupPre route_group_pre(int N, const uint32_t* lds, int ebase) {
+  GroupPre g{int(threadIdx.x) - ebase, 0, 0, false};
+  if (g.e < 0) return g;
+  const uint32_t* U = lds;
+  const int nw = (N + 31) >> 5;
+  for (int w = 0; w < nw; ++w) {
+    const int c = __popc(U[w]);
+    g.T += c;
+    g.pos += w < (g.e >> 5) ? c : 0;
+  }
+  const uint32_t mine = g.e < N ? U[g.e >> 5] : 0u;
+  g.in_u = (mine >> (g.e & 31)) & 1u;
+  g.pos += __popc(mine & ((1u << (g.e & 31)) - 1u));
+  return g;
+}
 template <int NT, typename Hook = NoHook>
-__device__ __forceinline__ void route_group(int B, int N, int k, RouteOut o, uint32_t* lds, Hook after_offsets = Hook()) {
+__device__ __forceinline__ void route_group_with(int B, int N, int k, RouteOut o, uint32_t* lds, const GroupPre g,
+                                                 Hook after_offsets = Hook()) {
   constexpr int NW = NT / 64;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int NWB = (B + 31) >> 5;
@@ -152,35 +179,30 @@ __device__ __forceinline__ void route_group(int B, int N, int k, RouteOut o, uin
   uint32_t* eoff = colmask + N * NWB;
   if (!o.grp_off) return;
   // ---- pairs per expert, CSR offsets by position in the active list
-  const int e = tid;
-  const int nw = (N + 31) >> 5;
-  int T = 0, pos = 0;  // members of U, members below e (from the mask words, as in route_active)
-  for (int w = 0; w < nw; ++w) {
-    const int c = __popc(U[w]);
-    T += c;
-    pos += w < (e >> 5) ? c : 0;
-  }
-  const uint32_t mine = e < N ? U[e >> 5] : 0u;
-  const bool in_u = (mine >> (e & 31)) & 1u;
-  pos += __popc(mine & ((1u << (e & 31)) - 1u));
-  int cnt = 0;
-  if (in_u)
-    for (int w = 0; w < NWB; ++w) cnt += __popc(colmask[e * NWB + w]);
-  const int incl = wave_incl_scan_i32(cnt, lane);  // inclusive scan of cnt inside the wave
-  int excl;
+  const int e = g.e, T = g.T, pos = g.pos;
+  const bool in_u = g.in_u;
+  int cnt = 0, excl = 0;
   if (N <= 128) {
-    // the experts sit in the first two wavefronts: the second one counts the pairs of the first
-    // 64 experts itself instead of waiting for them at a barrier
-    int before = 0;
-    if (wave == 1) {
-      int c0 = 0;
-      if ((U[lane >> 5] >> (lane & 31)) & 1u)
-        for (int w = 0; w < NWB; ++w) c0 += __popc(colmask[lane * NWB + w]);
-      before = __builtin_amdgcn_readlane(wave_incl_scan_i32(c0, lane), 63);
+    if (e >= 0) {  // uniform over a wavefront (the thread base is a multiple of 64)
+      if (in_u)
+        for (int w = 0; w < NWB; ++w) cnt += __popc(colmask[e * NWB + w]);
+      const int incl = wave_incl_scan_i32(cnt, lane);  // inclusive scan of cnt inside the wave
+      // the experts sit in two wavefronts: the second one counts the pairs of the first 64 experts
+      // itself instead of waiting for them at a barrier
+      int before = 0;
+      if ((e >> 6) == 1) {
+        int c0 = 0;
+        if ((U[lane >> 5] >> (lane & 31)) & 1u)
+          for (int w = 0; w < NWB; ++w) c0 += __popc(colmask[lane * NWB + w]);
+        before = __builtin_amdgcn_readlane(wave_incl_scan_i32(c0, lane), 63);
+      }
+      excl = before + incl - cnt;
+      if (e == N - 1) o.grp_off[T] = excl + cnt;  // all pairs
     }
-    excl = before + incl - cnt;
-    if (e == N - 1) o.grp_off[T] = excl + cnt;  // all pairs
-  } else {
+  } else {  // thread base 0 (see route_union_rows): e == tid
+    if (in_u)
+      for (int w = 0; w < NWB; ++w) cnt += __popc(colmask[e * NWB + w]);
+    const int incl = wave_incl_scan_i32(cnt, lane);
     if (lane == 63) scan[16 + wave] = uint32_t(incl);
     __syncthreads();
     int cnt_base = 0, P = 0;
@@ -215,6 +237,10 @@ __device__ __forceinline__ void route_group(int B, int N, int k, RouteOut o, uin
     o.grp_gw[dst] = o.gate_w[p];
     if (o.grp_pos) o.grp_pos[p] = dst;
   }
+}
+template <int NT, typename Hook = NoHook>
+__device__ __forceinline__ void route_group(int B, int N, int k, RouteOut o, uint32_t* lds, Hook after_offsets = Hook()) {
+  route_group_with<NT>(B, N, k, o, lds, route_group_pre<NT>(N, lds, 0), after_offsets);
 }
 
 
@@ -431,23 +457,110 @@ struct RowCarry {
   int n;             // picks so far (every lane of the row)
   int t;             // the row's token, -1 if none
   bool any;          // wave-uniform: some row of this wavefront holds a token
+  int ebase;         // workgroup-uniform: thread ebase + e does the per-expert bookkeeping of expert e
 };
+
+// The data path of one round for eight keys per lane, as one block of machine code: m = the row's
+// best key, win = the lowest expert id holding it, and that expert's key cleared.  Same steps as the
+// generic code in row_pick; what differs is the order of the instructions.  On gfx950 a select may
+// not read a lane mask that a compare wrote less than two instructions earlier, and the compiler
+// pairs every compare with its select (two idle issue slots per pair, an idle slot costs as much as
+// an instruction: 32 of a round's 98 slots).  Here the eight compares of a step write eight masks
+// first and the selects follow.  The idle slots that remain (s_nop 1) are the two a DPP operand
+// needs after the instruction that wrote it.
+__device__ __forceinline__ void row_pick_core8(uint32_t (&key)[8], const uint32_t (&id)[8], uint32_t& m,
+                                               uint32_t& win) {
+  uint32_t t, u;
+  unsigned long long s0, s1, s2, s3, s4, s5, s6, s7;
+  asm("v_max3_u32 %[t], %[k0], %[k1], %[k2]\n"
+      "v_max3_u32 %[u], %[k3], %[k4], %[k5]\n"
+      "v_max3_u32 %[t], %[t], %[k6], %[k7]\n"
+      "v_max_u32 %[t], %[t], %[u]\n"
+      "s_nop 1\n"
+      "v_max_u32_dpp %[t], %[t], %[t] quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf bound_ctrl:1\n"
+      "s_nop 1\n"
+      "v_max_u32_dpp %[t], %[t], %[t] quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf bound_ctrl:1\n"
+      "s_nop 1\n"
+      "v_max_u32_dpp %[t], %[t], %[t] row_half_mirror row_mask:0xf bank_mask:0xf bound_ctrl:1\n"
+      "s_nop 1\n"
+      "v_max_u32_dpp %[m], %[t], %[t] row_mirror row_mask:0xf bank_mask:0xf bound_ctrl:1\n"
+      // lowest id among this lane's keys equal to m (0xffff: none), then the lowest of the row
+      "v_cmp_eq_u32 %[s7], %[k7], %[m]\n"
+      "v_cmp_eq_u32 %[s6], %[k6], %[m]\n"
+      "v_cmp_eq_u32 %[s5], %[k5], %[m]\n"
+      "v_cmp_eq_u32 %[s4], %[k4], %[m]\n"
+      "v_cmp_eq_u32 %[s3], %[k3], %[m]\n"
+      "v_cmp_eq_u32 %[s2], %[k2], %[m]\n"
+      "v_cmp_eq_u32 %[s1], %[k1], %[m]\n"
+      "v_cmp_eq_u32 %[s0], %[k0], %[m]\n"
+      "v_mov_b32 %[u], 0xffff\n"
+      "v_cndmask_b32 %[u], %[u], %[i7], %[s7]\n"
+      "v_cndmask_b32 %[u], %[u], %[i6], %[s6]\n"
+      "v_cndmask_b32 %[u], %[u], %[i5], %[s5]\n"
+      "v_cndmask_b32 %[u], %[u], %[i4], %[s4]\n"
+      "v_cndmask_b32 %[u], %[u], %[i3], %[s3]\n"
+      "v_cndmask_b32 %[u], %[u], %[i2], %[s2]\n"
+      "v_cndmask_b32 %[u], %[u], %[i1], %[s1]\n"
+      "v_cndmask_b32 %[u], %[u], %[i0], %[s0]\n"
+      "s_nop 1\n"
+      "v_min_u32_dpp %[u], %[u], %[u] quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf bound_ctrl:1\n"
+      "s_nop 1\n"
+      "v_min_u32_dpp %[u], %[u], %[u] quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf bound_ctrl:1\n"
+      "s_nop 1\n"
+      "v_min_u32_dpp %[u], %[u], %[u] row_half_mirror row_mask:0xf bank_mask:0xf bound_ctrl:1\n"
+      "s_nop 1\n"
+      "v_min_u32_dpp %[w], %[u], %[u] row_mirror row_mask:0xf bank_mask:0xf bound_ctrl:1\n"
+      // clear the winner's key
+      "v_cmp_ne_u32 %[s0], %[i0], %[w]\n"
+      "v_cmp_ne_u32 %[s1], %[i1], %[w]\n"
+      "v_cmp_ne_u32 %[s2], %[i2], %[w]\n"
+      "v_cmp_ne_u32 %[s3], %[i3], %[w]\n"
+      "v_cmp_ne_u32 %[s4], %[i4], %[w]\n"
+      "v_cmp_ne_u32 %[s5], %[i5], %[w]\n"
+      "v_cmp_ne_u32 %[s6], %[i6], %[w]\n"
+      "v_cmp_ne_u32 %[s7], %[i7], %[w]\n"
+      "v_cndmask_b32 %[k0], 0, %[k0], %[s0]\n"
+      "v_cndmask_b32 %[k1], 0, %[k1], %[s1]\n"
+      "v_cndmask_b32 %[k2], 0, %[k2], %[s2]\n"
+      "v_cndmask_b32 %[k3], 0, %[k3], %[s3]\n"
+      "v_cndmask_b32 %[k4], 0, %[k4], %[s4]\n"
+      "v_cndmask_b32 %[k5], 0, %[k5], %[s5]\n"
+      "v_cndmask_b32 %[k6], 0, %[k6], %[s6]\n"
+      "v_cndmask_b32 %[k7], 0, %[k7], %[s7]\n"
+      : [k0] "+v"(key[0]), [k1] "+v"(key[1]), [k2] "+v"(key[2]), [k3] "+v"(key[3]), [k4] "+v"(key[4]),
+        [k5] "+v"(key[5]), [k6] "+v"(key[6]), [k7] "+v"(key[7]), [t] "=&v"(t), [u] "=&v"(u), [m] "=&v"(m),
+        [w] "=&v"(win), [s0] "=&s"(s0), [s1] "=&s"(s1), [s2] "=&s"(s2), [s3] "=&s"(s3), [s4] "=&s"(s4),
+        [s5] "=&s"(s5), [s6] "=&s"(s6), [s7] "=&s"(s7)
+      : [i0] "v"(id[0]), [i1] "v"(id[1]), [i2] "v"(id[2]), [i3] "v"(id[3]), [i4] "v"(id[4]), [i5] "v"(id[5]),
+        [i6] "v"(id[6]), [i7] "v"(id[7]));
+}
 
 // one round for all rows: pick the best remaining candidate of every row's token, store it at rank
 // `rank` (wave-uniform)
 template <int NK>
 __device__ __forceinline__ void row_pick(RowCarry<NK>& c, int li, int rank) {
-  uint32_t lm = c.key[0];
+  uint32_t m, win;
+#ifndef OEA_ROW_PICK_PLAIN
+  if constexpr (NK == 8) {
+    uint32_t id[8];
 #pragma unroll
-  for (int j = 1; j < NK; ++j) lm = c.key[j] > lm ? c.key[j] : lm;
-  const uint32_t m = row_max_u32(lm);
-  uint32_t cand = 0xffffu;  // lowest expert id among this lane's keys equal to m
+    for (int j = 0; j < 8; ++j) id[j] = uint32_t(li + 16 * j);
+    row_pick_core8(c.key, id, m, win);
+  } else
+#endif
+  {
+    uint32_t lm = c.key[0];
 #pragma unroll
-  for (int j = NK - 1; j >= 0; --j) cand = c.key[j] == m ? uint32_t(li + 16 * j) : cand;
-  const uint32_t win = row_min_u32(cand);
+    for (int j = 1; j < NK; ++j) lm = c.key[j] > lm ? c.key[j] : lm;
+    m = row_max_u32(lm);
+    uint32_t cand = 0xffffu;  // lowest expert id among this lane's keys equal to m
+#pragma unroll
+    for (int j = NK - 1; j >= 0; --j) cand = c.key[j] == m ? uint32_t(li + 16 * j) : cand;
+    win = row_min_u32(cand);
+#pragma unroll
+    for (int j = 0; j < NK; ++j) c.key[j] = uint32_t(li + 16 * j) == win ? 0u : c.key[j];
+  }
   const bool valid = m != 0;
-#pragma unroll
-  for (int j = 0; j < NK; ++j) c.key[j] = uint32_t(li + 16 * j) == win ? 0u : c.key[j];
   if (valid && li == rank) {
     c.sel_id = win;
     c.sel_key = m;
@@ -478,6 +591,10 @@ __device__ __forceinline__ void route_union_rows(const float* __restrict__ logit
   const bool live = have && !(token_mask && token_mask[t] == 0);
   c.t = have ? t : -1;
   c.any = wave * RPW < B;
+  // Wavefronts without tokens, if there are enough of them for one thread per expert, do the
+  // per-expert bookkeeping (active list, offsets) beside the selection rounds of the others
+  const int nbusy = (B + RPW - 1) / RPW;
+  c.ebase = (N <= 128 && (NW - nbusy) * 64 >= N) ? nbusy * 64 : 0;
   c.n = 0;
   c.sel_id = 0;
   c.sel_key = 0;
@@ -501,7 +618,7 @@ __device__ __forceinline__ void route_union_rows(const float* __restrict__ logit
   }
   __syncthreads();
   OEA_TL(4);
-  route_active<NT>(N, o, lds);
+  route_active<NT>(N, o, lds, c.ebase);
 }
 
 template <int NK, int NT, typename Hook = NoHook>
@@ -512,6 +629,7 @@ __device__ __forceinline__ void route_fill_rows(int B, int N, int k, int k0, Rou
   const int NWB = (B + 31) >> 5;
   uint32_t* U = lds;
   uint32_t* colmask = lds + 64;
+  const GroupPre gp = route_group_pre<NT>(N, lds, c.ebase);
   // ---- Phase 2 in closed form: continue on the candidates that are in U, up to k picks.
   // A live token holds exactly k0 picks here (k0 <= N), so the next rank is the round number.
   if (c.any) {
@@ -536,7 +654,7 @@ __device__ __forceinline__ void route_fill_rows(int B, int N, int k, int k0, Rou
   }
   __syncthreads();
   OEA_TL(5);
-  route_group<NT>(B, N, k, o, lds, after_offsets);
+  route_group_with<NT>(B, N, k, o, lds, gp, after_offsets);
 }
 
 template <int NV, int NT, int TPW>
