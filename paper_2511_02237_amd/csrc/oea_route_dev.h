@@ -106,6 +106,18 @@ __device__ __forceinline__ int wave_incl_scan_i32(int v, int lane) {
   return v + (row >= 1 ? r0 : 0) + (row >= 2 ? r1 : 0) + (row >= 3 ? r2 : 0);
 }
 
+// the same with the row totals passed on by DPP broadcasts (lane 15 of a row to the next row, lane 31
+// to the upper two rows) instead of scalar registers: six dependent steps, no lane reads
+__device__ __forceinline__ int wave_incl_scan_dpp_i32(int v) {
+  v += dpp_shr_i32<0x111>(v);  // row_shr:1
+  v += dpp_shr_i32<0x112>(v);  // row_shr:2
+  v += dpp_shr_i32<0x114>(v);  // row_shr:4
+  v += dpp_shr_i32<0x118>(v);  // row_shr:8
+  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, false);  // row_bcast:15 into rows 1 and 3
+  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false);  // row_bcast:31 into rows 2 and 3
+  return v;
+}
+
 // Tail of the first half: the members of the union bit mask U (lds[0..15]) in ascending order ->
 // o.active_list, their number -> *o.n_active.  Called by all NT threads after a barrier that
 // completes U; the results are complete after the caller's next barrier.
@@ -145,16 +157,24 @@ struct NoHook {
 };
 // What the offsets need from the union mask alone (complete since the end of Phase 1): computed
 // before the barrier that ends Phase 2, by the threads that will compute the offsets after it.
+// N <= 128: ONE wavefront (the one of thread ebase) computes the offsets, lane l those of experts
+// 2l and 2l+1, with a single scan.  Larger N: thread e expert e, scan across the wavefronts.
 struct GroupPre {
-  int e;      // this thread's expert (threadIdx.x - ebase); < 0: none
-  int T;      // members of U
-  int pos;    // members below e
-  bool in_u;  // e is a member
+  int e;           // this thread's (first) expert; < 0: none
+  int T;           // members of U
+  int pos;         // members below e
+  bool in_u, in1;  // e, e + 1 (N <= 128 only) is a member
 };
 template <int NT>
 __device__ __forceinline__ GroupPre route_group_pre(int N, const uint32_t* lds, int ebase) {
-  GroupPre g{int(threadIdx.x) - ebase, 0, 0, false};
-  if (g.e < 0) return g;
+  GroupPre g{-1, 0, 0, false, false};
+  const int rel = int(threadIdx.x) - ebase;
+  if (N <= 128) {
+    if (rel < 0 || rel >= 64) return g;
+    g.e = 2 * rel;
+  } else {
+    g.e = rel;  // ebase == 0
+  }
   const uint32_t* U = lds;
   const int nw = (N + 31) >> 5;
   for (int w = 0; w < nw; ++w) {
@@ -162,18 +182,19 @@ __device__ __forceinline__ GroupPre route_group_pre(int N, const uint32_t* lds, 
     g.T += c;
     g.pos += w < (g.e >> 5) ? c : 0;
   }
-  const uint32_t mine = g.e < N ? U[g.e >> 5] : 0u;
+  const uint32_t mine = g.e < N ? U[g.e >> 5] : 0u;  // e even: e + 1 is in the same word
   g.in_u = (mine >> (g.e & 31)) & 1u;
+  g.in1 = N <= 128 && g.e + 1 < N && ((mine >> ((g.e + 1) & 31)) & 1u);
   g.pos += __popc(mine & ((1u << (g.e & 31)) - 1u));
   return g;
 }
-template <int NT, typename Hook = NoHook>
+// LISTS = false: the caller fills the pair lists itself (route_fill_rows does, from registers).
+template <int NT, typename Hook = NoHook, bool LISTS = true>
 __device__ __forceinline__ void route_group_with(int B, int N, int k, RouteOut o, uint32_t* lds, const GroupPre g,
                                                  Hook after_offsets = Hook()) {
   constexpr int NW = NT / 64;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int NWB = (B + 31) >> 5;
-  uint32_t* U = lds;
   uint32_t* scan = lds + 16;
   uint32_t* colmask = lds + 64;
   uint32_t* eoff = colmask + N * NWB;
@@ -181,25 +202,32 @@ __device__ __forceinline__ void route_group_with(int B, int N, int k, RouteOut o
   // ---- pairs per expert, CSR offsets by position in the active list
   const int e = g.e, T = g.T, pos = g.pos;
   const bool in_u = g.in_u;
-  int cnt = 0, excl = 0;
   if (N <= 128) {
-    if (e >= 0) {  // uniform over a wavefront (the thread base is a multiple of 64)
-      if (in_u)
-        for (int w = 0; w < NWB; ++w) cnt += __popc(colmask[e * NWB + w]);
-      const int incl = wave_incl_scan_i32(cnt, lane);  // inclusive scan of cnt inside the wave
-      // the experts sit in two wavefronts: the second one counts the pairs of the first 64 experts
-      // itself instead of waiting for them at a barrier
-      int before = 0;
-      if ((e >> 6) == 1) {
-        int c0 = 0;
-        if ((U[lane >> 5] >> (lane & 31)) & 1u)
-          for (int w = 0; w < NWB; ++w) c0 += __popc(colmask[lane * NWB + w]);
-        before = __builtin_amdgcn_readlane(wave_incl_scan_i32(c0, lane), 63);
+    if (e >= 0) {  // one wavefront
+      // unconditional reads at clamped addresses (experts >= N have no words), all in flight together
+      const uint32_t* m0 = colmask + (e < N ? e : N - 1) * NWB;
+      const uint32_t* m1 = colmask + (e + 1 < N ? e + 1 : N - 1) * NWB;
+      int c0 = __popc(m0[0]), c1 = __popc(m1[0]);
+      for (int w = 1; w < NWB; ++w) {
+        c0 += __popc(m0[w]);
+        c1 += __popc(m1[w]);
       }
-      excl = before + incl - cnt;
-      if (e == N - 1) o.grp_off[T] = excl + cnt;  // all pairs
+      c0 = in_u ? c0 : 0;
+      c1 = g.in1 ? c1 : 0;
+      const int incl = wave_incl_scan_dpp_i32(c0 + c1);
+      const int excl0 = incl - c0 - c1, excl1 = excl0 + c0;
+      if (in_u) {
+        o.grp_off[pos] = excl0;
+        eoff[e] = uint32_t(excl0);
+      }
+      if (g.in1) {
+        o.grp_off[pos + (in_u ? 1 : 0)] = excl1;
+        eoff[e + 1] = uint32_t(excl1);
+      }
+      if (lane == 63) o.grp_off[T] = incl;  // all pairs
     }
   } else {  // thread base 0 (see route_union_rows): e == tid
+    int cnt = 0;
     if (in_u)
       for (int w = 0; w < NWB; ++w) cnt += __popc(colmask[e * NWB + w]);
     const int incl = wave_incl_scan_i32(cnt, lane);
@@ -211,17 +239,18 @@ __device__ __forceinline__ void route_group_with(int B, int N, int k, RouteOut o
       cnt_base += w < wave ? cw : 0;
       P += cw;
     }
-    excl = cnt_base + incl - cnt;
+    const int excl = cnt_base + incl - cnt;
     if (tid == 0) o.grp_off[T] = P;
-  }
-  if (in_u) {
-    o.grp_off[pos] = excl;
-    eoff[e] = uint32_t(excl);
+    if (in_u) {
+      o.grp_off[pos] = excl;
+      eoff[e] = uint32_t(excl);
+    }
   }
   __syncthreads();
   OEA_TL(6);
   after_offsets();
 
+  if (!LISTS) return;
   // ---- one thread per (token, slot) pair; inside an expert, pairs are in token order
   for (int p = tid; p < B * k; p += NT) {
     const int ex = o.expert_idx[p];
@@ -630,23 +659,25 @@ __device__ __forceinline__ void route_fill_rows(int B, int N, int k, int k0, Rou
   uint32_t* U = lds;
   uint32_t* colmask = lds + 64;
   const GroupPre gp = route_group_pre<NT>(N, lds, c.ebase);
+  float gate = 0.f;
   // ---- Phase 2 in closed form: continue on the candidates that are in U, up to k picks.
   // A live token holds exactly k0 picks here (k0 <= N), so the next rank is the round number.
   if (c.any) {
 #pragma unroll
     for (int j = 0; j < NK; ++j) {
-      const int e = li + 16 * j;  // e < 16*NK <= 512: inside U's 16 words
-      if (!((U[e >> 5] >> (e & 31)) & 1u)) c.key[j] = 0;
+      // expert li + 16 j (< 16*NK <= 512: inside U's 16 words): word j/2, bit li + 16 (j%2)
+      if (!((U[j >> 1] >> (li + 16 * (j & 1))) & 1u)) c.key[j] = 0;
     }
     for (int r = k0; r < k; ++r) row_pick<NK>(c, li, r);
     // weights: g_s = exp(l_s - l_top) / sum_s' exp(l_s' - l_top) (Eq. 1; the softmax denominator cancels)
     const float w = li < c.n ? expf(from_orderable(c.sel_key) - from_orderable(c.top_key)) : 0.f;
     const float z = row_sum_f32(w);
+    gate = li < c.n ? w / z : 0.f;
     if (c.t >= 0) {
       const int t = c.t;
       if (li < k) {
         o.expert_idx[(size_t)t * k + li] = li < c.n ? int(c.sel_id) : -1;
-        o.gate_w[(size_t)t * k + li] = li < c.n ? w / z : 0.f;
+        o.gate_w[(size_t)t * k + li] = gate;
       }
       if (li < c.n) atomicOr(&colmask[c.sel_id * NWB + (t >> 5)], 1u << (t & 31));
       if (li == 0) o.n_sel[t] = c.n;
@@ -654,7 +685,29 @@ __device__ __forceinline__ void route_fill_rows(int B, int N, int k, int k0, Rou
   }
   __syncthreads();
   OEA_TL(5);
-  route_group_with<NT>(B, N, k, o, lds, gp, after_offsets);
+  // The pair lists straight from the rows' registers: lane r of a token's row holds its pair of
+  // rank r.  Its place inside the expert's group (tokens in ascending order) comes from the token
+  // masks, which are complete here; only the expert's offset has to wait for the next barrier.
+  const bool pair = c.any && c.t >= 0 && li < c.n && o.grp_off;
+  int rank = 0;
+  if (c.any) {
+    const int t = pair ? c.t : 0;
+    const uint32_t* cm = colmask + (pair ? int(c.sel_id) : 0) * NWB;
+    rank = __popc(cm[t >> 5] & ((1u << (t & 31)) - 1u));
+    for (int wd = 0; wd < (t >> 5); ++wd) rank += __popc(cm[wd]);
+  }
+  route_group_with<NT, Hook, false>(B, N, k, o, lds, gp, after_offsets);
+  if (c.any && o.grp_off) {
+    const uint32_t* eoff = colmask + N * NWB;
+    if (pair) {
+      const int dst = int(eoff[c.sel_id]) + rank;
+      o.grp_tok[dst] = c.t;
+      o.grp_gw[dst] = gate;
+      if (o.grp_pos) o.grp_pos[(size_t)c.t * k + li] = dst;
+    } else if (o.grp_pos && c.t >= 0 && li < k) {
+      o.grp_pos[(size_t)c.t * k + li] = -1;
+    }
+  }
 }
 
 template <int NV, int NT, int TPW>
