@@ -26,7 +26,14 @@ __global__ __launch_bounds__(NT) void route_kernel(const float* logits, const ui
   o.n_sel += pos * B;
   o.active_list += pos * N;
   o.n_active += pos;
-  if (NV <= 2 && k <= 16 && B <= 4 * (NT / 64)) {
+  if constexpr (NT == 256) {
+    // launch_route picks this size only for NV <= 2, k <= 16, B <= 16: the row-per-token routing is
+    // the only path compiled in, which keeps the kernel at 8 wavefronts per SIMD (with many
+    // positions the launch is bound by how many are resident to hide each other's LDS round trips)
+    RowCarry<4 * NV> c;
+    route_union_rows<4 * NV, NT>(logits, token_mask, B, N, k0, o, lds, c);
+    route_fill_rows<4 * NV, NT>(B, N, k, k0, o, lds, c);
+  } else if (NV <= 2 && k <= 16 && B <= 4 * (NT / 64)) {
     // few experts: one DPP row of 16 lanes per token, four tokens per wavefront
     RowCarry<4 * NV> c;
     route_union_rows<4 * NV, NT>(logits, token_mask, B, N, k0, o, lds, c);

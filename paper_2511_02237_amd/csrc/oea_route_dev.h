@@ -565,12 +565,15 @@ __device__ __forceinline__ void row_pick_core8(uint32_t (&key)[8], const uint32_
 }
 
 // one round for all rows: pick the best remaining candidate of every row's token, store it at rank
-// `rank` (wave-uniform)
-template <int NK>
+// `rank` (wave-uniform).  ALONE: the wavefront has its SIMD (nearly) to itself, as in a workgroup
+// that fills a compute unit; the hand-scheduled block is then a quarter faster.  With many
+// wavefronts per SIMD (many small workgroups) the idle slots of the compiler's code are filled by
+// the other wavefronts and its shorter encodings win by 3 %.
+template <int NK, bool ALONE = true>
 __device__ __forceinline__ void row_pick(RowCarry<NK>& c, int li, int rank) {
   uint32_t m, win;
 #ifndef OEA_ROW_PICK_PLAIN
-  if constexpr (NK == 8) {
+  if constexpr (NK == 8 && ALONE) {
     uint32_t id[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) id[j] = uint32_t(li + 16 * j);
@@ -642,7 +645,7 @@ __device__ __forceinline__ void route_union_rows(const float* __restrict__ logit
   // ---- Phase 1 of Algorithm 1: S_i^base = the k0 best experts (wavefronts without tokens leave
   // the SIMDs to the others)
   if (c.any) {
-    for (int r = 0; r < k0; ++r) row_pick<NK>(c, li, r);
+    for (int r = 0; r < k0; ++r) row_pick<NK, (NT > 256)>(c, li, r);
     if (li < c.n) atomicOr(&U[c.sel_id >> 5], 1u << (c.sel_id & 31));
   }
   __syncthreads();
@@ -668,7 +671,7 @@ __device__ __forceinline__ void route_fill_rows(int B, int N, int k, int k0, Rou
       // expert li + 16 j (< 16*NK <= 512: inside U's 16 words): word j/2, bit li + 16 (j%2)
       if (!((U[j >> 1] >> (li + 16 * (j & 1))) & 1u)) c.key[j] = 0;
     }
-    for (int r = k0; r < k; ++r) row_pick<NK>(c, li, r);
+    for (int r = k0; r < k; ++r) row_pick<NK, (NT > 256)>(c, li, r);
     // weights: g_s = exp(l_s - l_top) / sum_s' exp(l_s' - l_top) (Eq. 1; the softmax denominator cancels)
     const float w = li < c.n ? expf(from_orderable(c.sel_key) - from_orderable(c.top_key)) : 0.f;
     const float z = row_sum_f32(w);
