@@ -503,6 +503,21 @@ def test_route_batched_positions(torch, B_, oracle):
     say("oea_route_batched: %d positions of B=16, N=128 in %.1f us (%.1f M positions/s)" % (L, us, L / us))
 
 
+@pytest.mark.parametrize("path", [2, 3])
+def test_three_kernel_paths_small_batches(torch, B_, oracle, path):
+    """The router + routing kernel with 16 wavefronts: for few tokens most of them hold no token row
+    and do the per-expert bookkeeping beside the selection rounds (B = 1, 5, 8: one row per
+    wavefront; B = 11: four rows per wavefront, three busy wavefronts)."""
+    L0, dev0 = big_layer(B_, "qwen3_30b", 2000)
+    for b in (1, 5, 8, 11):
+        L = W.Layer(**{**L0.__dict__, "x": np.ascontiguousarray(L0.x[:b]), "B": b})
+        dev = dict(dev0, x=B_.to_device(L.x))
+        for k0 in (3, 8):
+            out, tap = run_layer_dev(torch, B_, L, dev, k0, path=path)
+            err, ref = check_layer(oracle, L, k0, out, tap, "path %d B=%d k0=%d" % (path, b, k0))
+            say("path", path, "B", b, "k0", k0, "T=%d err=%.2e" % (ref["n_active"], err))
+
+
 # ---- larger batches: the expert stages as separate kernels
 
 def test_stage_kernels_at_b16(torch, B_, oracle):
