@@ -261,9 +261,42 @@ def route_general_latency(args):
     for p_, maxp in ((1.0, N), (0.5, N), (1.0, 8), (0.5, 8)):
         timed("Algorithm 2: k0=%d, p=%g, k_max=%d, maxP=%d" % (args.k0, p_, k, maxp),
               lambda o, p_=p_, maxp=maxp: binding.oea_route_general(lg, args.k0, p_, k, maxp, out=o))
+    # ---- the whole layer under the same routings (expert weights drawn on the device, rotating sets)
+    d, I = cfg["d"], cfg["I"]
+    base = workloads.make_layer(args.workload, 2000, B=B, I=8)  # x and router; their logits decide the routing
+    x, wr = binding.to_device(base.x), binding.to_device(base.w_router)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(12345)
+    sets = [tuple(torch.randn(sh, generator=g, device="cuda", dtype=torch.float32).mul_(0.02).to(torch.bfloat16)
+                  for sh in ((N, I, d), (N, I, d), (N, d, I))) for _ in range(8)]
+    ws = binding.new_workspace(B, d, N, I, k)
+    out = torch.empty((B, d), dtype=torch.float32, device="cuda")
+    layer_rows = []
+
+    def layer(name, **kw):
+        _, tap = binding.moe_decode(x, wr, *sets[0], k, args.k0, ws, out=out, taps=True, **kw)
+        for it in range(args.warmup):
+            binding.moe_decode(x, wr, *sets[it % 8], k, args.k0, ws, out=out, **kw)
+        torch.cuda.synchronize()
+        hip.record(e0, sptr)
+        for it in range(args.steps):
+            binding.moe_decode(x, wr, *sets[it % 8], k, args.k0, ws, out=out, **kw)
+        hip.record(e1, sptr)
+        torch.cuda.synchronize()
+        binding.workspace_check(ws)
+        layer_rows.append(dict(routing=name, us_per_layer=round(hip.elapsed_ms(e0, e1) / args.steps * 1e3, 2),
+                               unique_experts=int(tap["n_active"].item()),
+                               mean_experts_per_token=round(float(tap["n_sel"].float().mean().item()), 2)))
+
+    layer("Algorithm 1: k0=%d, k=%d" % (args.k0, k))
+    layer("Algorithm 1, three kernels", kernel_path=2)
+    for p_, maxp in ((0.1, None), (None, 8), (0.1, 24), (None, 32)):
+        layer("Algorithm 2: k0=%d, p=%s, k_max=%d, maxP=%s" % (args.k0, p_ if p_ else 1, k, maxp if maxp else N),
+              top_p=p_, max_p=maxp)
     print(json.dumps(dict(metric="OEA routing latency per decode batch (us), B=%d N=%d" % (B, N), unit="us", n_gpus=1,
                           steps=args.steps, warmup=args.warmup, dtype="f32", data="synthetic",
-                          config=dict(workload="%s routing, one batch per launch" % args.workload), rows=rows)))
+                          config=dict(workload="%s routing, one batch per launch" % args.workload), rows=rows,
+                          layer_rows=layer_rows)))
 
 
 def sweep(args):

@@ -189,13 +189,14 @@ typedef struct {
   int32_t *n_active_out;      /* [1]   */
   double top_p;               /* general OEA (Algorithm 2): top-p cut of the baseline; 0 or >= 1 = off */
   int32_t max_p;              /* general OEA: piggyback only among the max_p best ranks; 0 or >= N = off.
-                                 With either set, k plays the role of k_max and the layer runs as three
-                                 kernels. */
+                                 With either set, k plays the role of k_max.  Up to B = 32 (on the shapes the
+                                 single-kernel layer covers) the general routing runs inside that kernel;
+                                 beyond, the layer runs as three kernels. */
   int32_t deterministic;      /* non-zero: Eq. 1's sum over the selected experts is taken in slot order by
                                  one thread per output element (a last small kernel), instead of with
                                  floating-point atomics in arrival order: `out` is then bit-identical from
                                  call to call.  Needs oea_workspace_bytes_deterministic(...) bytes of
-                                 workspace; costs one more kernel launch (about 4 us at B=16). */
+                                 workspace; costs one more kernel launch (about 5 us at B=16). */
   int32_t cooperative;        /* non-zero: the single persistent kernel is launched as a cooperative
                                  launch, so the runtime guarantees that all its workgroups are resident
                                  together or refuses the launch (OEA_ERR_HIP) - for callers that share

@@ -217,11 +217,11 @@ static int decode_enqueue(const void* x, const void* W_router, const void* W_gat
 
   if (!mark(0)) return OEA_ERR_HIP;
   hipError_t e = hipErrorNotSupported;
-  if (path == 0 && !general)
+  if (path == 0)
     e = try_launch_fused(x, W_router, W_gate, W_up, W_down, ex ? ex->router_bias : nullptr,
                          ex ? ex->token_mask : nullptr, out, logits, h, ro,
                          reinterpret_cast<uint32_t*>(ws + w.ctrl), B, d, N, I, k, k0, dt, s,
-                         opts ? opts->spin_limit : 0u, ex && ex->cooperative != 0, y);
+                         opts ? opts->spin_limit : 0u, ex && ex->cooperative != 0, y, general ? &ga : nullptr);
   if (e == hipSuccess) {  // one kernel: the inner event pairs collapse onto its end
     for (int i = 1; i < 6; ++i)
       if (!mark(i)) return OEA_ERR_HIP;

@@ -57,6 +57,10 @@ struct FusedParams {
   int cap_vec1;    // large batches: vectors per piece in the down stage
   int ecap0, ecap1;  // floats of LDS result buffer per wavefront, gate/up and down stage (0 = none)
   uint32_t spin_limit;
+  // general OEA (Algorithm 2) in the kernel for B <= 32: top-p threshold and rank window; k is k_max
+  int general;
+  int gen_max_p;
+  double gen_p;
 };
 
 // words of LDS in front of the vector area (after the 16-byte dump slot)
@@ -425,7 +429,10 @@ __device__ __forceinline__ void signal_hidden_done(uint32_t* ctrl, int R0, int R
 }
 
 // d == LPR0*EPL*NCH0 and I == LPR1*EPL*NCH1 exactly; N <= 64*NV; B <= 32; k <= 16.
-template <typename WT, int LPR0, int NCH0, int LPR1, int NCH1, int NV>
+// GEN: the routing is the general OEA (Algorithm 2) instead of Algorithm 1; an instantiation of its
+// own, so that the code of the default kernel does not depend on it (as a run-time branch it
+// changed the register allocation of the stages and cost the default path 0.4 us).
+template <typename WT, int LPR0, int NCH0, int LPR1, int NCH1, int NV, bool GEN = false>
 __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   extern __shared__ uint4 lds4[];
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -573,11 +580,9 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
   const float* const frac = balanced ? l_frac : nullptr;
   uint32_t* const l_cut = l_route + 48;  // [4] inside the routing scratch's block-scan words, unused at N <= 128
   {
-    RowCarry<4 * NV> carry;  // one DPP row of 16 lanes per token, 4 * NV keys per lane
-    route_union_rows<4 * NV, kFfnThreads, true>(p.logits, p.token_mask, B, N, p.k0, lo, l_route, carry);
     // The four cut points of this workgroup (both ends, both stages) need only the CSR offsets: the
-    // last four wavefronts compute one each while the first ones fill the pair lists.
-    route_fill_rows<4 * NV, kFfnThreads>(B, N, k, p.k0, lo, l_route, carry, [&]() {
+    // last four wavefronts compute one each while the rows' lanes write the pair lists.
+    auto cuts = [&]() {
       if (wave >= kFfnWaves - 4) {
         const int q = wave - (kFfnWaves - 4);
         int T_ = uniform(l_nact[0]);
@@ -585,7 +590,15 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
         const int cut = wg_first_row(l_off, T_, q < 2 ? I : d, q < 2 ? kBetaUp : kBetaDown, wg + (q & 1), G, lane, frac);
         if (lane == 0) l_cut[q] = uint32_t(cut);
       }
-    });
+    };
+    if constexpr (GEN) {  // Algorithm 2: top-p cut of the baseline, rank window; k is k_max
+      route_rows_general<4 * NV, kFfnThreads, true>(p.logits, p.token_mask, B, N, p.k0,
+                                                    RouteGeneral{p.gen_p, k, p.gen_max_p, nullptr}, lo, l_route, cuts);
+    } else {
+      RowCarry<4 * NV> carry;  // one DPP row of 16 lanes per token, 4 * NV keys per lane
+      route_union_rows<4 * NV, kFfnThreads, true>(p.logits, p.token_mask, B, N, p.k0, lo, l_route, carry);
+      route_fill_rows<4 * NV, kFfnThreads>(B, N, k, p.k0, lo, l_route, carry, cuts);
+    }
   }
   __syncthreads();
   if (wg == 0) {  // publish the routing result
@@ -1092,6 +1105,11 @@ hipError_t launch_persistent(Kern kern, const FusedParams& p, int grid, size_t l
 
 template <typename WT, int LPR0, int NCH0, int LPR1, int NCH1, int NV>
 hipError_t launch_fused_one(const FusedParams& p, int grid, size_t lds_bytes, bool coop, hipStream_t s) {
+  if (p.general) {
+    static PerDevice attr_g, fits_g;
+    return launch_persistent(moe_fused_kernel<WT, LPR0, NCH0, LPR1, NCH1, NV, true>, p, grid, lds_bytes, attr_g,
+                             fits_g, coop, s);
+  }
   static PerDevice attr, fits;
   return launch_persistent(moe_fused_kernel<WT, LPR0, NCH0, LPR1, NCH1, NV>, p, grid, lds_bytes, attr, fits, coop, s);
 }
@@ -1110,8 +1128,9 @@ hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_g
                             const void* w_down, const float* bias, const uint8_t* token_mask, float* out,
                             float* logits, void* h, RouteOut ro, uint32_t* ctrl, int B, int d, int N, int I,
                             int k, int k0, oea_dtype dt, hipStream_t s, uint32_t spin_limit, bool cooperative,
-                            float* y_per_pair) {
+                            float* y_per_pair, const RouteGeneralArgs* general) {
   if (dt != OEA_BF16 || N > 128 || B > 128 || k > 16) return hipErrorNotSupported;
+  if (general && B > 32) return hipErrorNotSupported;  // Algorithm 2 is in the kernel for small batches only
   const bool shape30 = d == 2048 && I == 768, shape235 = d == 4096 && I == 1536;
   if (!shape30 && !shape235) return hipErrorNotSupported;
   int dev = 0, grid = 0;
@@ -1181,6 +1200,9 @@ hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_g
   p.I = I;
   p.k = k;
   p.k0 = k0;
+  p.general = general ? 1 : 0;
+  p.gen_p = general ? general->p : 1.0;
+  p.gen_max_p = general ? general->max_p : N;
   p.cap_vec = (int)cap_vec;
   p.cap_vec1 = (int)cap_vec1;
   p.ecap0 = ecap0;

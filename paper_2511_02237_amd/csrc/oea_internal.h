@@ -119,7 +119,8 @@ hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_g
                             const void* w_down, const float* bias, const uint8_t* token_mask, float* out,
                             float* logits, void* h, RouteOut ro, uint32_t* ctrl, int B, int d, int N, int I,
                             int k, int k0, oea_dtype dt, hipStream_t s, uint32_t spin_limit = 0,
-                            bool cooperative = false, float* y_per_pair = nullptr);
+                            bool cooperative = false, float* y_per_pair = nullptr,
+                            const RouteGeneralArgs* general = nullptr);
 
 // one expert stage (0 gate/up, 1 down) with the fused kernel's stage code, for larger batches
 hipError_t try_launch_stage_kernels(int stage, const void* vec, const void* wa, const void* wb, void* h_out,

@@ -14,6 +14,8 @@
 
 #include "oea_timeline.h"
 
+#include <type_traits>
+
 namespace oea {
 namespace {
 
@@ -477,6 +479,19 @@ __device__ __forceinline__ float row_sum_f32(float v) {
   return v;
 }
 
+__device__ __forceinline__ double row_sum_f64(double v) {  // the two halves travel by DPP
+  auto step = [&](auto ctrl) __attribute__((always_inline)) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), decltype(ctrl)::value, 0xF, 0xF, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), decltype(ctrl)::value, 0xF, 0xF, true);
+    v += __hiloint2double(hi, lo);
+  };
+  step(std::integral_constant<int, 0xB1>());
+  step(std::integral_constant<int, 0x4E>());
+  step(std::integral_constant<int, 0x141>());
+  step(std::integral_constant<int, 0x140>());
+  return v;
+}
+
 template <int NK>
 struct RowCarry {
   uint32_t key[NK];  // candidate keys of the row's token (0 = taken / not a candidate)
@@ -653,25 +668,17 @@ __device__ __forceinline__ void route_union_rows(const float* __restrict__ logit
   route_active<NT>(N, o, lds, c.ebase);
 }
 
+// Common tail of the row-per-token routings, entered with every row's selection complete (lane r of
+// a row: expert and key of rank r; c.n picks): gate weights, the selection written out, the
+// token masks per expert, then (after the barrier) offsets and pair lists.  gp: see route_group_pre.
 template <int NK, int NT, typename Hook = NoHook>
-__device__ __forceinline__ void route_fill_rows(int B, int N, int k, int k0, RouteOut o, uint32_t* lds,
-                                                RowCarry<NK>& c, Hook after_offsets = Hook()) {
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int li = lane & 15;
+__device__ __forceinline__ void route_rows_finish(int B, int N, int k, RouteOut o, uint32_t* lds, RowCarry<NK>& c,
+                                                  const GroupPre gp, Hook after_offsets = Hook()) {
+  const int li = threadIdx.x & 15;
   const int NWB = (B + 31) >> 5;
-  uint32_t* U = lds;
   uint32_t* colmask = lds + 64;
-  const GroupPre gp = route_group_pre<NT>(N, lds, c.ebase);
   float gate = 0.f;
-  // ---- Phase 2 in closed form: continue on the candidates that are in U, up to k picks.
-  // A live token holds exactly k0 picks here (k0 <= N), so the next rank is the round number.
   if (c.any) {
-#pragma unroll
-    for (int j = 0; j < NK; ++j) {
-      // expert li + 16 j (< 16*NK <= 512: inside U's 16 words): word j/2, bit li + 16 (j%2)
-      if (!((U[j >> 1] >> (li + 16 * (j & 1))) & 1u)) c.key[j] = 0;
-    }
-    for (int r = k0; r < k; ++r) row_pick<NK, (NT > 256)>(c, li, r);
     // weights: g_s = exp(l_s - l_top) / sum_s' exp(l_s' - l_top) (Eq. 1; the softmax denominator cancels)
     const float w = li < c.n ? expf(from_orderable(c.sel_key) - from_orderable(c.top_key)) : 0.f;
     const float z = row_sum_f32(w);
@@ -711,6 +718,25 @@ __device__ __forceinline__ void route_fill_rows(int B, int N, int k, int k0, Rou
       o.grp_pos[(size_t)c.t * k + li] = -1;
     }
   }
+}
+
+template <int NK, int NT, typename Hook = NoHook>
+__device__ __forceinline__ void route_fill_rows(int B, int N, int k, int k0, RouteOut o, uint32_t* lds,
+                                                RowCarry<NK>& c, Hook after_offsets = Hook()) {
+  const int li = threadIdx.x & 15;
+  uint32_t* U = lds;
+  const GroupPre gp = route_group_pre<NT>(N, lds, c.ebase);
+  // ---- Phase 2 in closed form: continue on the candidates that are in U, up to k picks.
+  // A live token holds exactly k0 picks here (k0 <= N), so the next rank is the round number.
+  if (c.any) {
+#pragma unroll
+    for (int j = 0; j < NK; ++j) {
+      // expert li + 16 j (< 16*NK <= 512: inside U's 16 words): word j/2, bit li + 16 (j%2)
+      if (!((U[j >> 1] >> (li + 16 * (j & 1))) & 1u)) c.key[j] = 0;
+    }
+    for (int r = k0; r < k; ++r) row_pick<NK, (NT > 256)>(c, li, r);
+  }
+  route_rows_finish<NK, NT>(B, N, k, o, lds, c, gp, after_offsets);
 }
 
 template <int NV, int NT, int TPW>
@@ -905,6 +931,133 @@ __device__ __forceinline__ double wave_sum_f64(double v) {
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
   return v;
+}
+
+// General OEA with one DPP row of 16 lanes per token (N <= 16*NK, max(k0, k_max) <= 16,
+// B <= 4*NT/64): the form the single-kernel layer uses.  Same decisions as route_block_general:
+// the baseline ends with the pick that brings the cumulative softmax mass (fp64) to p; a row that
+// has stopped takes no part in later rounds (its keys stay as they are); Phase 2 either continues
+// on the members of U (no window) or walks the ranks up to max_p, where an expert outside U uses
+// up its rank.  Slot r of a row is the r-th expert taken, so the output is in rank order.
+template <int NK, int NT, bool COHERENT = false, typename Hook = NoHook>
+__device__ __forceinline__ void route_rows_general(const float* __restrict__ logits,
+                                                   const uint8_t* __restrict__ token_mask, int B, int N, int k0,
+                                                   RouteGeneral g, RouteOut o, uint32_t* lds,
+                                                   Hook after_offsets = Hook()) {
+  constexpr int NW = NT / 64;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 15, row = lane >> 4;
+  const int kw = k0 > g.k_max ? k0 : g.k_max;
+  const int RPW = B <= NW / 2 ? 1 : 4;
+  uint32_t* U = lds;
+  RowCarry<NK> c;
+  for (int i = tid; i < int(route_lds_words(B, N)); i += NT) lds[i] = 0;
+  const int t = wave * RPW + row;
+  const bool have = row < RPW && t < B;
+  const bool live = have && !(token_mask && token_mask[t] == 0);
+  c.t = have ? t : -1;
+  c.any = wave * RPW < B;
+  const int nbusy = (B + RPW - 1) / RPW;
+  c.ebase = (N <= 128 && (NW - nbusy) * 64 >= N) ? nbusy * 64 : 0;
+  c.n = 0;
+  c.sel_id = c.sel_key = c.top_key = 0;
+  float lg[NK];
+#pragma unroll
+  for (int j = 0; j < NK; ++j) {
+    const int e = li + 16 * j;
+    const float* src = logits + (size_t)(live ? t : 0) * N + (e < N ? e : N - 1);
+    lg[j] = COHERENT ? __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *src;
+  }
+#pragma unroll
+  for (int j = 0; j < NK; ++j) c.key[j] = (live && li + 16 * j < N) ? make_key(lg[j]) : 0;
+  __syncthreads();  // U is cleared
+
+  // One round for the rows with `active` set: their best remaining candidate is removed; it is
+  // taken (next slot of the row) unless `members_only` and it is not in U.  Returns its key, 0 if
+  // the row was not active or had no candidate left.
+  auto pick = [&](bool active, bool members_only) __attribute__((always_inline)) {
+    uint32_t lm = c.key[0];
+#pragma unroll
+    for (int j = 1; j < NK; ++j) lm = c.key[j] > lm ? c.key[j] : lm;
+    const uint32_t m = row_max_u32(lm);
+    uint32_t cand = 0xffffu;
+#pragma unroll
+    for (int j = NK - 1; j >= 0; --j) cand = c.key[j] == m ? uint32_t(li + 16 * j) : cand;
+    const uint32_t win = row_min_u32(cand);
+    const bool valid = active && m != 0;
+    const uint32_t wq = valid ? win : 0u;  // < N when valid
+    const bool member = !members_only || ((U[wq >> 5] >> (wq & 31)) & 1u);
+    const bool rec = valid && member;
+#pragma unroll
+    for (int j = 0; j < NK; ++j) c.key[j] = (valid && uint32_t(li + 16 * j) == win) ? 0u : c.key[j];
+    if (rec && li == c.n) {
+      c.sel_id = win;
+      c.sel_key = m;
+    }
+    if (rec && c.n == 0) c.top_key = m;
+    c.n += rec ? 1 : 0;
+    return valid ? m : 0u;
+  };
+
+  // ---- Phase 1: the baseline, cut by the top-p rule as well
+  const bool capped = g.p < 1.0;
+  int nbase = 0;
+  if (c.any) {
+    double mtop = 0.0, z = 1.0;
+    if (capped) {  // softmax denominator over all experts of the row's token
+      uint32_t lm = c.key[0];
+#pragma unroll
+      for (int j = 1; j < NK; ++j) lm = c.key[j] > lm ? c.key[j] : lm;
+      mtop = double(from_orderable(row_max_u32(lm)));
+      double zl = 0.0;
+#pragma unroll
+      for (int j = 0; j < NK; ++j)
+        if (c.key[j] != 0) zl += exp(double(from_orderable(c.key[j])) - mtop);
+      z = row_sum_f64(zl);
+    }
+    bool active = true;
+    double cum = 0.0;
+    for (int r = 0; r < k0; ++r) {
+      if (__ballot(active) == 0) break;
+      const uint32_t m = pick(active, false);
+      if (m == 0) active = false;
+      if (capped && m != 0) {
+        cum += exp(double(from_orderable(m)) - mtop) / z;
+        if (cum >= g.p) active = false;
+      }
+    }
+    nbase = c.n;
+    if (li < nbase) atomicOr(&U[c.sel_id >> 5], 1u << (c.sel_id & 31));
+    if (g.n_base && c.t >= 0 && li == 0) g.n_base[c.t] = nbase;
+  }
+  __syncthreads();
+  route_active<NT>(N, o, lds, c.ebase);
+  const GroupPre gp = route_group_pre<NT>(N, lds, c.ebase);
+
+  // ---- Phase 2: piggyback on U in rank order, ranks below max_p, until k_max experts are held
+  if (c.any) {
+    if (g.max_p >= N) {  // no window: the best remaining members of U
+#pragma unroll
+      for (int j = 0; j < NK; ++j)
+        if (!((U[j >> 1] >> (li + 16 * (j & 1))) & 1u)) c.key[j] = 0;
+      for (int r = 0; r < g.k_max; ++r) {
+        const bool active = c.n < g.k_max;
+        if (__ballot(active) == 0) break;
+        pick(active, false);
+      }
+    } else {  // the ranks in order; rk = candidates removed so far = rank of the next one
+      int rk = nbase;
+      bool open = true;  // candidates left
+      for (int r = 0; r < g.max_p; ++r) {
+        const bool active = open && rk < g.max_p && c.n < g.k_max;
+        if (__ballot(active) == 0) break;
+        const uint32_t m = pick(active, true);
+        if (active && m == 0) open = false;
+        rk += m != 0 ? 1 : 0;
+      }
+    }
+  }
+  route_rows_finish<NK, NT>(B, N, kw, o, lds, c, gp, after_offsets);
 }
 
 // One workgroup of NT threads, one wavefront per token at a time, any B.  Output rows have

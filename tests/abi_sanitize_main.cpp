@@ -33,7 +33,7 @@ hipError_t launch_expert_down(const void*, const void*, float*, int, int, int, i
 }
 hipError_t try_launch_fused(const void*, const void*, const void*, const void*, const void*, const float*,
                             const uint8_t*, float*, float*, void*, RouteOut, uint32_t*, int, int, int, int, int, int,
-                            oea_dtype, hipStream_t, uint32_t, bool, float*) {
+                            oea_dtype, hipStream_t, uint32_t, bool, float*, const RouteGeneralArgs*) {
   return reached("fused");
 }
 hipError_t try_launch_stage_kernels(int, const void*, const void*, const void*, void*, float*, int, int, int, int, int,

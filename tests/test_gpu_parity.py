@@ -470,6 +470,45 @@ def test_layer_general_oea(torch, B_, oracle):
         assert err <= TOL[L.dtype], ctx
 
 
+def test_layer_general_oea_single_kernel(torch, B_, oracle):
+    """Algorithm 2 inside the single-kernel layer (30B shape, B <= 32): top-p cut, rank window, both,
+    with a padding mask, for several batch sizes; the three-kernel path must route identically."""
+    L0, dev0 = big_layer(B_, "qwen3_30b", 2000)
+    L32 = W.make_layer("qwen3_30b", 2100, B=32, I=8)  # token vectors only (the expert weights are L0's)
+    xs = {b: np.ascontiguousarray(L0.x[:b]) for b in (1, 5, 16)}
+    xs[32] = np.ascontiguousarray(L32.x)
+    cases = [(16, 3, 0.1, None, False), (16, 3, None, 8, False), (16, 3, 0.1, 24, False), (16, 4, 0.08, 12, True),
+             (16, 8, 0.3, None, False), (16, 2, None, 3, False), (1, 3, 0.1, 6, False), (5, 3, 0.12, 10, True),
+             (32, 3, 0.1, 16, True), (32, 5, None, 6, False)]
+    for b, k0, p, max_p, masked in cases:
+        L = W.Layer(**{**L0.__dict__, "x": xs[b], "B": b})
+        dev = dict(dev0, x=B_.to_device(L.x))
+        mask = None
+        if masked:
+            mask = np.ones(b, np.uint8)
+            mask[1::3] = 0
+        dmask = None if mask is None else torch.from_numpy(mask).cuda()
+        ws = B_.new_workspace(L.B, L.d, L.N, L.I, L.k)
+        taps = {}
+        for path in (None, 2):
+            out, tap = B_.moe_decode(dev["x"], dev["w_router"], dev["w_gate"], dev["w_up"], dev["w_down"], L.k, k0,
+                                     ws, taps=True, top_p=p, max_p=max_p, token_mask=dmask, kernel_path=path)
+            torch.cuda.synchronize()
+            B_.workspace_check(ws)
+            taps[path] = ({n: v.cpu().numpy() for n, v in tap.items()}, out.cpu().numpy().astype(np.float64))
+        tap, got = taps[None]
+        pp, mp = (1.0 if p is None else p), (L.N if max_p is None else max_p)
+        ctx = "single-kernel general B=%d k0=%d p=%s max_p=%s mask=%s" % (b, k0, p, max_p, masked)
+        assert top_p_is_clear(tap["logits"], k0, pp), ctx
+        ref = oracle.route_general(tap["logits"], k0, pp, L.k, mp, token_mask=mask)
+        assert_routing_equal(tap, ref, ctx)
+        assert_routing_equal(taps[2][0], ref, ctx + " (three kernels)")
+        ref_out = oracle.moe_combine(L.x, L.w_gate, L.w_up, L.w_down, ref["expert_idx"], ref["gate_w"])
+        err = np.abs(got - ref_out).max() / np.abs(ref_out).max()
+        say("%s: T=%d, mean |S_i| %.2f, max|d|/max|ref| = %.2e" % (ctx, ref["n_active"], ref["n_sel"].mean(), err))
+        assert err <= TOL[L.dtype], ctx
+
+
 # ---- many decode positions in one launch
 
 def test_route_batched_positions(torch, B_, oracle):
