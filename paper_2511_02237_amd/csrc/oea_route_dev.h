@@ -9,6 +9,16 @@
 //           (softmax scores renormalised over S_i: Eq. 1 / Section 3.2 "Weighting after rerouting")
 //   pass 3: ascending active list, and the expert -> (token, weight) grouping the FFN kernels use.
 // Ranking is on the fp32 logits, ties to the lower expert id, -0.0 equal to +0.0.
+//
+// Variants, all with the same results:
+//   route_block             one wavefront per token, any N <= 512 (routing kernels, large expert counts)
+//   route_union_rows +      one DPP row of 16 lanes per token, four tokens per wavefront, N <= 128,
+//   route_fill_rows         B <= 4 * wavefronts: the single-kernel layer (B <= 32) and the routing kernels
+//   route_rows_groups / _any  the same for more tokens, in groups of 4 * wavefronts
+//   route_rows_general      Algorithm 2 (top-p cut, rank window) in the row form, for the single-kernel layer
+//   route_block_general     Algorithm 2, one wavefront per token (routing kernels)
+// The row forms end in route_rows_finish / route_group_with: gate weights, token masks per expert,
+// CSR offsets (one wavefront), pair lists (from the rows' registers).
 #pragma once
 #include "oea_internal.h"
 
@@ -587,7 +597,7 @@ __device__ __forceinline__ void row_pick_core8(uint32_t (&key)[8], const uint32_
 template <int NK, bool ALONE = true>
 __device__ __forceinline__ void row_pick(RowCarry<NK>& c, int li, int rank) {
   uint32_t m, win;
-#ifndef OEA_ROW_PICK_PLAIN
+#ifndef OEA_ROW_PICK_PLAIN  // (build switch: the compiler's code everywhere, for comparison)
   if constexpr (NK == 8 && ALONE) {
     uint32_t id[8];
 #pragma unroll
