@@ -542,6 +542,39 @@ def test_route_batched_positions(torch, B_, oracle):
     say("oea_route_batched: %d positions of B=16, N=128 in %.1f us (%.1f M positions/s)" % (L, us, L / us))
 
 
+def test_single_kernel_routing_many_batches(torch, B_, oracle):
+    """The routing inside the single-kernel layer (rows of 16 lanes, hand-scheduled selection round,
+    bookkeeping on the wavefronts without tokens) over many token batches: B = 1..32, every k0, with
+    and without a padding mask, compared with the oracle on the logits the kernel computed.  The
+    expert weights do not enter the routing: random ones drawn on the device."""
+    d, N, I, k = 2048, 128, 768, 8
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    wts = tuple(torch.randn(sh, generator=g, device="cuda", dtype=torch.float32).mul_(0.02).to(torch.bfloat16)
+                for sh in ((N, I, d), (N, I, d), (N, d, I)))
+    rng = np.random.default_rng(123)
+    n = 0
+    for b in (1, 2, 3, 5, 8, 11, 16, 24, 32):
+        ws = B_.new_workspace(b, d, N, I, k)
+        for seed in range(6):
+            L = W.make_layer("qwen3_30b", 50000 + 100 * b + seed, B=b, I=8)  # token vectors and router
+            x, wr = B_.to_device(L.x), B_.to_device(L.w_router)
+            mask = None
+            if seed % 3 == 2 and b > 1:
+                mask = (rng.random(b) > 0.3).astype(np.uint8)
+                mask[0] = 1
+            dm = None if mask is None else torch.from_numpy(mask).cuda()
+            for k0 in range(1, 9):
+                _, tap = B_.moe_decode(x, wr, *wts, k, k0, ws, taps=True, token_mask=dm)
+                torch.cuda.synchronize()
+                tap = {m: v.cpu().numpy() for m, v in tap.items()}
+                assert_routing_equal(tap, oracle.route(tap["logits"], k, k0, token_mask=mask),
+                                     "single-kernel routing B=%d seed=%d k0=%d" % (b, seed, k0))
+                n += 1
+        B_.workspace_check(ws)
+    say("single-kernel routing cases checked:", n)
+
+
 @pytest.mark.parametrize("path", [2, 3])
 def test_three_kernel_paths_small_batches(torch, B_, oracle, path):
     """The router + routing kernel with 16 wavefronts: for few tokens most of them hold no token row
