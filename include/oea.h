@@ -189,9 +189,8 @@ typedef struct {
   int32_t *n_active_out;      /* [1]   */
   double top_p;               /* general OEA (Algorithm 2): top-p cut of the baseline; 0 or >= 1 = off */
   int32_t max_p;              /* general OEA: piggyback only among the max_p best ranks; 0 or >= N = off.
-                                 With either set, k plays the role of k_max.  Up to B = 32 (on the shapes the
-                                 single-kernel layer covers) the general routing runs inside that kernel;
-                                 beyond, the layer runs as three kernels. */
+                                 With either set, k plays the role of k_max.  Where the single-kernel layer
+                                 applies (see moe_decode) the general routing runs inside that kernel. */
   int32_t deterministic;      /* non-zero: Eq. 1's sum over the selected experts is taken in slot order by
                                  one thread per output element (a last small kernel), instead of with
                                  floating-point atomics in arrival order: `out` is then bit-identical from

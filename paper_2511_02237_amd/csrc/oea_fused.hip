@@ -57,7 +57,7 @@ struct FusedParams {
   int cap_vec1;    // large batches: vectors per piece in the down stage
   int ecap0, ecap1;  // floats of LDS result buffer per wavefront, gate/up and down stage (0 = none)
   uint32_t spin_limit;
-  // general OEA (Algorithm 2) in the kernel for B <= 32: top-p threshold and rank window; k is k_max
+  // general OEA (Algorithm 2) in the kernel: top-p threshold and rank window; k is k_max
   int general;
   int gen_max_p;
   double gen_p;
@@ -713,7 +713,7 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_kernel(FusedParams p) {
 // for the gate/up stage, rows of h for the down stage) and, should they exceed its LDS share, walks
 // them in pieces (streaming its weight rows once per piece).  The routing takes the tokens in groups
 // of 32 (four per wavefront).
-template <typename WT, int LPR0, int NCH0, int LPR1, int NCH1, int NV>
+template <typename WT, int LPR0, int NCH0, int LPR1, int NCH1, int NV, bool GEN = false>
 __global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedParams p) {
   extern __shared__ uint4 lds4[];
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -799,7 +799,11 @@ __global__ __launch_bounds__(kFfnThreads) void moe_fused_gather_kernel(FusedPara
   if (tid == 0) l_nact[1] = l_nact[2] = 0;
   // (the positions of the pairs in the grouped order go straight to memory, from workgroup 0 only)
   const RouteOut lo{l_idx, l_gatew, l_nsel, l_active, l_nact, l_off, l_tok, l_gw, wg == 0 ? p.ro.grp_pos : nullptr};
-  route_rows_groups<4 * NV, kFfnThreads, 4, true>(p.logits, p.token_mask, B, N, k, p.k0, lo, l_route);  // B <= 128
+  if constexpr (GEN)  // Algorithm 2 (see moe_fused_kernel)
+    route_rows_general_any<4 * NV, kFfnThreads, true>(p.logits, p.token_mask, B, N, p.k0,
+                                                      RouteGeneral{p.gen_p, k, p.gen_max_p, nullptr}, lo, l_route);
+  else
+    route_rows_groups<4 * NV, kFfnThreads, 4, true>(p.logits, p.token_mask, B, N, k, p.k0, lo, l_route);  // B <= 128
   __syncthreads();
   if (wg == 0) {  // publish the routing result
     for (int i = tid; i < P; i += kFfnThreads) {
@@ -1116,6 +1120,11 @@ hipError_t launch_fused_one(const FusedParams& p, int grid, size_t lds_bytes, bo
 
 template <typename WT, int LPR0, int NCH0, int LPR1, int NCH1, int NV>
 hipError_t launch_fused_gather_one(const FusedParams& p, int grid, size_t lds_bytes, bool coop, hipStream_t s) {
+  if (p.general) {
+    static PerDevice attr_g, fits_g;
+    return launch_persistent(moe_fused_gather_kernel<WT, LPR0, NCH0, LPR1, NCH1, NV, true>, p, grid, lds_bytes,
+                             attr_g, fits_g, coop, s);
+  }
   static PerDevice attr, fits;
   return launch_persistent(moe_fused_gather_kernel<WT, LPR0, NCH0, LPR1, NCH1, NV>, p, grid, lds_bytes, attr, fits,
                            coop, s);
@@ -1130,7 +1139,6 @@ hipError_t try_launch_fused(const void* x, const void* w_router, const void* w_g
                             int k, int k0, oea_dtype dt, hipStream_t s, uint32_t spin_limit, bool cooperative,
                             float* y_per_pair, const RouteGeneralArgs* general) {
   if (dt != OEA_BF16 || N > 128 || B > 128 || k > 16) return hipErrorNotSupported;
-  if (general && B > 32) return hipErrorNotSupported;  // Algorithm 2 is in the kernel for small batches only
   const bool shape30 = d == 2048 && I == 768, shape235 = d == 4096 && I == 1536;
   if (!shape30 && !shape235) return hipErrorNotSupported;
   int dev = 0, grid = 0;

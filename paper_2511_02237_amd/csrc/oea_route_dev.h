@@ -1070,6 +1070,146 @@ __device__ __forceinline__ void route_rows_general(const float* __restrict__ log
   route_rows_finish<NK, NT>(B, N, kw, o, lds, c, gp, after_offsets);
 }
 
+// General OEA in the row form for any B (the single-kernel layer for larger batches): the tokens are
+// taken in groups of 4*NT/64, nothing but the baseline sizes (parked in o.n_sel) is carried between
+// the phases; Phase 2 reloads a group's logits, takes the baseline again and goes on from there.
+// N <= 16*NK, max(k0, k_max) <= 16.
+template <int NK, int NT, bool COHERENT = false>
+__device__ void route_rows_general_any(const float* __restrict__ logits, const uint8_t* __restrict__ token_mask,
+                                       int B, int N, int k0, RouteGeneral g, RouteOut o, uint32_t* lds) {
+  constexpr int GROUP = 4 * (NT / 64);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 15, row = lane >> 4;
+  const int NWB = (B + 31) >> 5;
+  const int kw = k0 > g.k_max ? k0 : g.k_max;
+  uint32_t* U = lds;
+  uint32_t* colmask = lds + 64;
+  const bool capped = g.p < 1.0;
+  for (int i = tid; i < int(route_lds_words(B, N)); i += NT) lds[i] = 0;
+  __syncthreads();
+
+  RowCarry<NK> c;
+  auto load_keys = [&](int t, bool live) __attribute__((always_inline)) {
+    const float* src = logits + (size_t)(t < B ? t : B - 1) * N;
+#pragma unroll
+    for (int j = 0; j < NK; ++j) {
+      const int e = li + 16 * j;
+      const float* q = src + (e < N ? e : N - 1);
+      const float v = COHERENT ? __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *q;
+      c.key[j] = (live && e < N) ? make_key(v) : 0;
+    }
+    c.n = 0;
+    c.sel_id = c.sel_key = c.top_key = 0;
+  };
+  // one round for the rows with `active` set (see route_rows_general)
+  auto pick = [&](bool active, bool members_only) __attribute__((always_inline)) {
+    uint32_t lm = c.key[0];
+#pragma unroll
+    for (int j = 1; j < NK; ++j) lm = c.key[j] > lm ? c.key[j] : lm;
+    const uint32_t m = row_max_u32(lm);
+    uint32_t cand = 0xffffu;
+#pragma unroll
+    for (int j = NK - 1; j >= 0; --j) cand = c.key[j] == m ? uint32_t(li + 16 * j) : cand;
+    const uint32_t win = row_min_u32(cand);
+    const bool valid = active && m != 0;
+    const uint32_t wq = valid ? win : 0u;
+    const bool member = !members_only || ((U[wq >> 5] >> (wq & 31)) & 1u);
+    const bool rec = valid && member;
+#pragma unroll
+    for (int j = 0; j < NK; ++j) c.key[j] = (valid && uint32_t(li + 16 * j) == win) ? 0u : c.key[j];
+    if (rec && li == c.n) {
+      c.sel_id = win;
+      c.sel_key = m;
+    }
+    if (rec && c.n == 0) c.top_key = m;
+    c.n += rec ? 1 : 0;
+    return valid ? m : 0u;
+  };
+
+  // ---- Phase 1: baselines (top-p cut) and their union; the baseline size of token t -> o.n_sel[t]
+  for (int t0 = 0; t0 < B; t0 += GROUP) {
+    const int t = t0 + wave * 4 + row;
+    const bool live = t < B && !(token_mask && token_mask[t] == 0);
+    load_keys(t, live);
+    double mtop = 0.0, z = 1.0;
+    if (capped) {
+      uint32_t lm = c.key[0];
+#pragma unroll
+      for (int j = 1; j < NK; ++j) lm = c.key[j] > lm ? c.key[j] : lm;
+      mtop = double(from_orderable(row_max_u32(lm)));
+      double zl = 0.0;
+#pragma unroll
+      for (int j = 0; j < NK; ++j)
+        if (c.key[j] != 0) zl += exp(double(from_orderable(c.key[j])) - mtop);
+      z = row_sum_f64(zl);
+    }
+    bool active = true;
+    double cum = 0.0;
+    for (int r = 0; r < k0; ++r) {
+      if (__ballot(active) == 0) break;
+      const uint32_t m = pick(active, false);
+      if (m == 0) active = false;
+      if (capped && m != 0) {
+        cum += exp(double(from_orderable(m)) - mtop) / z;
+        if (cum >= g.p) active = false;
+      }
+    }
+    if (li < c.n) atomicOr(&U[c.sel_id >> 5], 1u << (c.sel_id & 31));
+    if (t < B && li == 0) {
+      o.n_sel[t] = c.n;
+      if (g.n_base) g.n_base[t] = c.n;
+    }
+  }
+  __syncthreads();
+  route_active<NT>(N, o, lds);
+
+  // ---- Phase 2 per group: the baseline again, then piggybacking as in route_rows_general
+  for (int t0 = 0; t0 < B; t0 += GROUP) {
+    const int t = t0 + wave * 4 + row;
+    const bool have = t < B;
+    const bool live = have && !(token_mask && token_mask[t] == 0);
+    const int nbase = have ? o.n_sel[t] : 0;  // written by this row's lane 0 before the barrier above
+    load_keys(t, live);
+    for (int r = 0; r < k0; ++r) {
+      const bool active = c.n < nbase;
+      if (__ballot(active) == 0) break;
+      pick(active, false);
+    }
+    if (g.max_p >= N) {
+#pragma unroll
+      for (int j = 0; j < NK; ++j)
+        if (!((U[j >> 1] >> (li + 16 * (j & 1))) & 1u)) c.key[j] = 0;
+      for (int r = 0; r < g.k_max; ++r) {
+        const bool active = c.n < g.k_max;
+        if (__ballot(active) == 0) break;
+        pick(active, false);
+      }
+    } else {
+      int rk = nbase;
+      bool open = true;
+      for (int r = 0; r < g.max_p; ++r) {
+        const bool active = open && rk < g.max_p && c.n < g.k_max;
+        if (__ballot(active) == 0) break;
+        const uint32_t m = pick(active, true);
+        if (active && m == 0) open = false;
+        rk += m != 0 ? 1 : 0;
+      }
+    }
+    const float w = li < c.n ? expf(from_orderable(c.sel_key) - from_orderable(c.top_key)) : 0.f;
+    const float z = row_sum_f32(w);
+    if (have) {
+      if (li < kw) {
+        o.expert_idx[(size_t)t * kw + li] = li < c.n ? int(c.sel_id) : -1;
+        o.gate_w[(size_t)t * kw + li] = li < c.n ? w / z : 0.f;
+      }
+      if (li < c.n) atomicOr(&colmask[c.sel_id * NWB + (t >> 5)], 1u << (t & 31));
+      if (li == 0) o.n_sel[t] = c.n;
+    }
+  }
+  __syncthreads();
+  route_group<NT>(B, N, kw, o, lds);
+}
+
 // One workgroup of NT threads, one wavefront per token at a time, any B.  Output rows have
 // kw = max(k0, k_max) slots.  lds: route_lds_words(B,N) + B words.
 // The top-p decision compares fp64 sums of fp64 softmax values (the softmax of Section 2 taken in

@@ -471,15 +471,20 @@ def test_layer_general_oea(torch, B_, oracle):
 
 
 def test_layer_general_oea_single_kernel(torch, B_, oracle):
-    """Algorithm 2 inside the single-kernel layer (30B shape, B <= 32): top-p cut, rank window, both,
-    with a padding mask, for several batch sizes; the three-kernel path must route identically."""
+    """Algorithm 2 inside the single-kernel layer (30B shape, both kernel variants: B <= 32 and
+    larger): top-p cut, rank window, both, with a padding mask, for several batch sizes; the
+    three-kernel path must route identically."""
     L0, dev0 = big_layer(B_, "qwen3_30b", 2000)
     L32 = W.make_layer("qwen3_30b", 2100, B=32, I=8)  # token vectors only (the expert weights are L0's)
     xs = {b: np.ascontiguousarray(L0.x[:b]) for b in (1, 5, 16)}
     xs[32] = np.ascontiguousarray(L32.x)
+    for b in (50, 64, 128):  # the kernel variant for larger batches: token groups, baselines parked between the phases
+        xs[b] = np.ascontiguousarray(W.make_layer("qwen3_30b", 2100 + b, B=b, I=8).x)
     cases = [(16, 3, 0.1, None, False), (16, 3, None, 8, False), (16, 3, 0.1, 24, False), (16, 4, 0.08, 12, True),
              (16, 8, 0.3, None, False), (16, 2, None, 3, False), (1, 3, 0.1, 6, False), (5, 3, 0.12, 10, True),
-             (32, 3, 0.1, 16, True), (32, 5, None, 6, False)]
+             (32, 3, 0.1, 16, True), (32, 5, None, 6, False),
+             (50, 3, 0.1, 12, True), (64, 3, 0.1, None, False), (64, 4, None, 8, True), (128, 3, 0.12, 24, False),
+             (128, 2, None, 5, True)]
     for b, k0, p, max_p, masked in cases:
         L = W.Layer(**{**L0.__dict__, "x": xs[b], "B": b})
         dev = dict(dev0, x=B_.to_device(L.x))
