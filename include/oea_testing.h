@@ -23,7 +23,9 @@ typedef struct {
                                2 = three kernels, streaming expert kernels with fixed shares when
                                    the token vectors fit in LDS, else generic ones
                                3 = three kernels, the fused kernel's stage code as expert kernels
-                                   where the shape allows */
+                                   where the shape allows
+                               4 = three kernels, expert stages on the matrix cores where the shape
+                                   allows (bf16; the automatic choice uses them above B = 128) */
   uint32_t spin_limit;    /* polls after which a wait inside the single kernel gives up
                              (0 = the default, about a second); 1 forces every wait to give up */
   void **h_kernel_events; /* HOST array of 6 hipEvent_t created by the caller, or NULL: recorded on
@@ -34,7 +36,7 @@ typedef struct {
 
 /*
  * moe_decode_ex (oea.h) with the switches above; ex and opts may each be NULL.
- * Errors as moe_decode_ex, and OEA_ERR_SHAPE for a kernel_path outside 0..3.
+ * Errors as moe_decode_ex, and OEA_ERR_SHAPE for a kernel_path outside 0..4.
  */
 int moe_decode_test(const void *x, const void *W_router, const void *W_gate, const void *W_up,
                     const void *W_down, float *out, int B, int d, int N, int I, int k, int k0,

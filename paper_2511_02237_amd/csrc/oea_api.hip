@@ -45,6 +45,9 @@ static int check_route_sizes(int B, int N, int k, int k0) {
   return OEA_OK;
 }
 
+// batches above this run their expert stages on the matrix cores (three-kernel path)
+static constexpr int kDenseFromBatch = 128;
+
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace oea
@@ -189,7 +192,7 @@ static int decode_enqueue(const void* x, const void* W_router, const void* W_gat
                           const oea_test_opts* opts = nullptr) {
   const oea_dtype dt = dt_checked == OEA_F32 ? OEA_F32 : OEA_BF16;  // check_decode_args has seen it
   const int path = opts ? opts->kernel_path : 0;
-  if (path < 0 || path > 3) return OEA_ERR_SHAPE;
+  if (path < 0 || path > 4) return OEA_ERR_SHAPE;
   const WsLayout w = ws_layout(B, d, N, I, k, elem_bytes_of(dt));
   char* ws = static_cast<char*>(workspace);
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -234,13 +237,18 @@ static int decode_enqueue(const void* x, const void* W_router, const void* W_gat
     if (e != hipSuccess || !mark(1) || !mark(2)) return OEA_ERR_HIP;
     const bool stage_kernels = path == 0 || path == 3;
     const bool generic_only = path == 1;
-    e = stage_kernels ? try_launch_stage_kernels(0, x, W_gate, W_up, h, nullptr, B, d, N, I, k, dt, g, false, s)
-                      : hipErrorNotSupported;
+    // matrix cores once an expert serves many tokens: above the single kernel's batch range
+    const bool dense = path == 4 || (path == 0 && B > kDenseFromBatch);
+    e = dense ? try_launch_dense_stage(0, x, W_gate, W_up, h, nullptr, B, d, N, I, k, dt, g, false, s)
+              : hipErrorNotSupported;
+    if (e == hipErrorNotSupported && stage_kernels)
+      e = try_launch_stage_kernels(0, x, W_gate, W_up, h, nullptr, B, d, N, I, k, dt, g, false, s);
     if (e == hipErrorNotSupported) e = launch_expert_gate_up(x, W_gate, W_up, h, B, d, N, I, k, dt, g, generic_only, s);
     if (e != hipSuccess || !mark(3) || !mark(4)) return OEA_ERR_HIP;
-    e = stage_kernels ? try_launch_stage_kernels(1, h, W_down, nullptr, nullptr, y ? y : out, B, d, N, I, k, dt, g,
-                                                 y != nullptr, s)
-                      : hipErrorNotSupported;
+    e = dense ? try_launch_dense_stage(1, h, W_down, nullptr, nullptr, y ? y : out, B, d, N, I, k, dt, g, y != nullptr, s)
+              : hipErrorNotSupported;
+    if (e == hipErrorNotSupported && stage_kernels)
+      e = try_launch_stage_kernels(1, h, W_down, nullptr, nullptr, y ? y : out, B, d, N, I, k, dt, g, y != nullptr, s);
     if (e == hipErrorNotSupported)
       e = launch_expert_down(h, W_down, y ? y : out, B, d, N, I, k, dt, g, generic_only, y != nullptr, s);
     if (e != hipSuccess || !mark(5)) return OEA_ERR_HIP;

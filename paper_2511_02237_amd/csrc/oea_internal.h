@@ -127,6 +127,11 @@ hipError_t try_launch_stage_kernels(int stage, const void* vec, const void* wa, 
                                     float* out, int B, int d, int N, int I, int k, oea_dtype dt, Grouping g,
                                     bool per_pair, hipStream_t s);
 
+// one expert stage (0 gate/up, 1 down) on the matrix cores, for batches in which experts serve many tokens
+hipError_t try_launch_dense_stage(int stage, const void* vec, const void* wa, const void* wb, void* h_out,
+                                  float* out, int B, int d, int N, int I, int k, oea_dtype dt, Grouping g,
+                                  bool per_pair, hipStream_t s);
+
 hipError_t launch_read_probe(const void* buf, size_t bytes, uint32_t* sink, hipStream_t s);
 size_t route_lds_bytes(int B, int N);
 

@@ -40,6 +40,10 @@ hipError_t try_launch_stage_kernels(int, const void*, const void*, const void*, 
                                     oea_dtype, Grouping, bool, hipStream_t) {
   return reached("stage_kernels");
 }
+hipError_t try_launch_dense_stage(int, const void*, const void*, const void*, void*, float*, int, int, int, int, int,
+                                  oea_dtype, Grouping, bool, hipStream_t) {
+  return reached("dense_stage");
+}
 hipError_t launch_combine(const float*, const int32_t*, const int32_t*, float*, int, int, int, hipStream_t) {
   return reached("combine");
 }

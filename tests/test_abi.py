@@ -140,7 +140,7 @@ def test_decode_argument_checks(L):
 
     class Opts(C.Structure):
         _fields_ = [("kernel_path", C.c_int32), ("spin_limit", C.c_uint32), ("h_kernel_events", C.c_void_p)]
-    bad = Opts(kernel_path=4)
+    bad = Opts(kernel_path=5)
     assert L.moe_decode_test(*(ok + [None, C.addressof(bad)])) == -2  # refused before any enqueue
 
 

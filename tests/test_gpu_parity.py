@@ -625,6 +625,62 @@ def test_many_tokens_per_expert(torch, B_, oracle):
             assert cnt.max() >= 32
 
 
+def test_matrix_core_stages(torch, B_, oracle):
+    """The expert stages on the matrix cores (kernel path 4; the automatic choice above B=128): batches
+    in which an expert serves a few tokens (one partly filled group of 16), many (several groups), and
+    more than one pass holds (over 64); the skewed workload; padding; the deterministic combine."""
+    L0 = W.make_layer("qwen3_30b", 2100, B=160)
+    dev_w = {f: B_.to_device(getattr(L0, f)) for f in ("w_router", "w_gate", "w_up", "w_down")}
+
+    def case(ctx, x, k0, path, bias=None, mask=None, min_pairs=0):
+        L = W.Layer(**{**L0.__dict__, "B": x.shape[0], "x": np.ascontiguousarray(x)})
+        dev = dict(dev_w, x=B_.to_device(L.x))
+        say(ctx)
+        out, tap = run_layer_dev(torch, B_, L, dev, k0, bias=bias, mask=mask, path=path)
+        err, ref = check_layer(oracle, L, k0, out, tap, ctx, bias=bias, mask=mask)
+        cnt = np.bincount(ref["expert_idx"][ref["expert_idx"] >= 0], minlength=L.N)
+        say("   T=%d, most pairs on one expert %d, err=%.2e" % (ref["n_active"], cnt.max(), err))
+        assert cnt.max() >= min_pairs
+        return L, dev
+
+    for k0 in (3, 5, 8):
+        case("matrix cores B=128 k0=%d" % k0, L0.x[:128], k0, 4)
+    for B in (1, 5, 16, 37):
+        case("matrix cores B=%d k0=3" % B, L0.x[:B], 3, 4)
+    # two distinct tokens, alternating: every active expert serves 32 of the 64 tokens
+    x = np.repeat(L0.x[:1], 64, axis=0).copy()
+    x[1::2] = L0.x[1:2]
+    for k0 in (2, 8):
+        case("matrix cores B=64 duplicated tokens k0=%d" % k0, x, k0, 4, min_pairs=32)
+    # the skewed-popularity workload: few experts, up to all 16 tokens on one
+    Ls = W.make_layer("qwen3_30b_skew", 2000, I=8)  # its token batch, router and bias; expert weights of L0
+    Lsk = W.Layer(**{**L0.__dict__, "B": Ls.B, "x": Ls.x, "w_router": Ls.w_router})
+    devs = dict(dev_w, x=B_.to_device(Lsk.x), w_router=B_.to_device(Lsk.w_router))
+    for k0 in (2, 4):
+        out, tap = run_layer_dev(torch, B_, Lsk, devs, k0, bias=Ls.router_bias, path=4)
+        err, ref = check_layer(oracle, Lsk, k0, out, tap, "matrix cores skew k0=%d" % k0, bias=Ls.router_bias)
+        say("matrix cores skew k0=%d: T=%d err=%.2e" % (k0, ref["n_active"], err))
+    # automatic choice above B=128: three distinct tokens in turn, so experts serve about 85 of the 256
+    # tokens (a pass of 64 and one of the rest); padding mask
+    x = np.ascontiguousarray(L0.x[np.arange(256) % 3])
+    mask = np.ones(256, np.uint8)
+    mask[[0, 100, 255]] = 0
+    L, dev = case("matrix cores B=256, three distinct tokens, automatic path, mask", x, 3, None, mask=mask, min_pairs=65)
+    # deterministic combine through the same stages: one row per pair, bit-identical from call to call
+    ws = B_.new_workspace(L.B, L.d, L.N, L.I, L.k, deterministic=True)
+    first = None
+    for it in range(4):
+        out, tap = B_.moe_decode(dev["x"], dev["w_router"], dev["w_gate"], dev["w_up"], dev["w_down"], L.k, 3, ws,
+                                 taps=True, deterministic=True)
+        torch.cuda.synchronize()
+        o = out.cpu().numpy()
+        if first is None:
+            first = o
+            check_layer(oracle, L, 3, o, {n: v.cpu().numpy() for n, v in tap.items()}, "matrix cores deterministic B=256")
+        else:
+            assert np.array_equal(o.view(np.uint32), first.view(np.uint32)), "call %d differs" % it
+
+
 # ---- capture into a HIP graph
 
 def test_graph_capture_and_replay(torch, B_, oracle):
