@@ -43,7 +43,8 @@ def parse():
                     help="time the layer with oea_decode_ex.deterministic (slot-ordered combine in a last kernel)")
     ap.add_argument("--no-other", action="store_true",
                     help="skip the other_workloads block (235B shape, skewed routing, other batch sizes)")
-    ap.add_argument("--kernel-path", type=int, default=0, help="0 automatic (fused kernel), 1 generic, 2 three kernels")
+    ap.add_argument("--kernel-path", type=int, default=0, help="oea_test_opts.kernel_path: 0 automatic, 1 generic, 2 streaming, 3 dot-product stage kernels, "
+                                                                  "4 matrix-core stage kernels")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain device copy of known size (reference for rocprofv3 --pmc byte counters)")
     ap.add_argument("--sweep", default="", help="comma list of batch sizes: time each (k0 from --k0s, default 3,5,8) "

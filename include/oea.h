@@ -153,9 +153,11 @@ int oea_route_general(const float *router_logits, const uint8_t *token_mask, int
  * workgroup that cannot be placed delays the others; every wait is bounded, after about a second
  * the call gives up, its output is undefined and oea_workspace_check reports OEA_ERR_TIMEOUT).
  * A caller that runs other kernels beside the layer (a second stream) sets
- * oea_decode_ex.cooperative, which makes co-residency the runtime's guarantee.  Still larger batches of these shapes run as
- * three kernels (router + routing, gate/up stage, down stage) that share the fused kernel's stage
- * code; every other shape, and fp32 storage, runs as three kernels with generic expert kernels.
+ * oea_decode_ex.cooperative, which makes co-residency the runtime's guarantee.  Still larger batches run as
+ * three kernels (router + routing, gate/up stage, down stage) with the expert stages on the matrix
+ * cores (bf16, I a multiple of 128, d of 256: an expert then serves 16 and more tokens and the
+ * arithmetic per pair, Eq. 2's second term, would bound the vector ALUs); every other shape, and fp32
+ * storage, runs as three kernels with dot-product expert kernels.
  * Arithmetic: router logits are accumulated in fp64 and rounded once to fp32; expert mat-vecs
  * multiply in the storage type and accumulate in fp32; with bf16 storage the hidden vector is
  * rounded to bf16 between the two mat-vecs (as a bf16 model does).
