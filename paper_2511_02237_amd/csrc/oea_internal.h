@@ -17,6 +17,11 @@ namespace oea {
 constexpr int kCtrlErrWord = 3;    // set by a workgroup whose bounded wait ran out
 constexpr int kCtrlMagicWord = 4;  // kWsMagic on a prepared workspace
 constexpr uint32_t kWsMagic = 0x4F454131u;
+// Large batches route in several kernels over many workgroups; between them the union bit mask of
+// Phase 1 and the number of pairs per expert live in control words that are otherwise unused (the
+// first of these kernels clears them).
+constexpr int kCtrlWideUnion = 5120;  // [16]  bit e % 32 of word e / 32: expert e is in the union
+constexpr int kCtrlWideCount = 5152;  // [OEA_MAX_N]
 
 // State that is looked up or set once per DEVICE (a process may drive several): indexed by the
 // HIP device id of the calling thread's current device.
@@ -44,7 +49,8 @@ struct WsLayout {
                        // weights of the workgroups, adapted from call to call); [4] holds kWsMagic; the rest is zero
                        // between calls: [0] arrival counter of the router kernel, [3] error flag, [32], [64] and
                        // [256 + 32 i] grid-barrier words of the fused kernel, [1024..) its per-expert completion
-                       // counters, one 128-byte line each (as many lines again are unused)
+                       // counters, one 128-byte line each; [5120..5664) union mask and pair counts of the
+                       // several-kernel routing of large batches (kCtrlWideUnion, kCtrlWideCount)
   size_t logits;       // float [B,N]
   size_t expert_idx;   // int32 [B,k]
   size_t gate_w;       // float [B,k]

@@ -7,6 +7,7 @@ namespace oea {
 namespace {
 
 constexpr int kRouteThreads = 1024;
+constexpr int kWideFromBatch = 128;  // larger batches route over many workgroups (see wide_logits_kernel)
 
 // One workgroup routes one decode position (blockIdx.x): its B rows of logits and its own output slices.
 // Positions are independent (Section 4: every position and layer is routed separately), so a grid
@@ -151,6 +152,240 @@ __global__ __launch_bounds__(kRouteThreads) void router_route_kernel(
     route_block<NV, kRouteThreads, 0>(logits, token_mask, B, N, k, k0, o, lds);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Batches above 128 tokens: router and routing over many workgroups, as four kernels in stream
+// order (a kernel boundary is the grid-wide synchronisation Algorithm 1 needs twice: the union of
+// Phase 1 before Phase 2, all pair counts before the grouped lists).  The union and the counts live
+// in control words of the workspace that the first kernel clears.  With one workgroup per expert
+// for the logits and one workgroup routing the whole batch this step took 50 / 104 / 230 us at
+// B = 256 / 512 / 1024.
+//
+// 1. wide_logits_kernel: a workgroup of four wavefronts computes the logits of 8 tokens x 16 experts,
+//    each wavefront a 4 x 8 block: operands are widened to fp64 once per block and multiplied with
+//    fused multiply-adds (a bf16 or fp32 product is exact in fp64, so this is the same arithmetic,
+//    in the same order, as the other router kernels: the same bits), 1.75 instructions per
+//    multiply-add instead of 3.  It also clears a slice of what the down stage adds into, and the
+//    control words of the routing kernels that follow.
+constexpr int kWideThreads = 256;
+
+// element q of a 16-byte piece, widened to fp64 (exact)
+template <typename WT>
+__device__ __forceinline__ double widen_elem(const uint4& v, int q);
+template <>
+__device__ __forceinline__ double widen_elem<uint16_t>(const uint4& v, int q) {
+  const uint32_t w = q < 2 ? v.x : q < 4 ? v.y : q < 6 ? v.z : v.w;
+  return double((q & 1) ? __uint_as_float(w & 0xffff0000u) : bf16_bits_to_f32(w & 0xffffu));
+}
+template <>
+__device__ __forceinline__ double widen_elem<float>(const uint4& v, int q) {
+  return double(__uint_as_float(q == 0 ? v.x : q == 1 ? v.y : q == 2 ? v.z : v.w));
+}
+
+template <typename WT>
+__global__ __launch_bounds__(kWideThreads) void wide_logits_kernel(const WT* __restrict__ x,
+                                                                   const WT* __restrict__ w_router,
+                                                                   const float* __restrict__ bias, int B, int d, int N,
+                                                                   float* logits, float* out_to_zero, size_t n_zero,
+                                                                   uint32_t* ctrl, int32_t* n_active) {
+  constexpr int EPL = 16 / int(sizeof(WT));
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wg = blockIdx.y * gridDim.x + blockIdx.x, n_wg = gridDim.x * gridDim.y;
+  {
+    const size_t total4 = n_zero / 4;
+    const size_t per = (total4 + n_wg - 1) / n_wg;
+    const size_t lo = per * wg, hi = lo + per < total4 ? lo + per : total4;
+    float4* o4 = reinterpret_cast<float4*>(out_to_zero);
+    for (size_t i = lo + tid; i < hi; i += kWideThreads) o4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  if (ctrl[kCtrlMagicWord] != kWsMagic) {  // unprepared workspace: an empty routing, out = 0
+    if (wg == 0 && tid == 0) *n_active = 0;
+    return;
+  }
+  if (wg == 0) {
+    if (tid < 16) ctrl[kCtrlWideUnion + tid] = 0u;
+    for (int i = tid; i < OEA_MAX_N; i += kWideThreads) ctrl[kCtrlWideCount + i] = 0u;
+  }
+  const int t0 = blockIdx.x * 8 + (wave >> 1) * 4, e0 = blockIdx.y * 16 + (wave & 1) * 8;
+  if (t0 >= B || e0 >= N) return;
+  double acc[4][8];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[i][j] = 0.0;
+  for (int c = lane * EPL; c < d; c += 64 * EPL) {
+    uint4 a[4], b[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int t = t0 + i < B ? t0 + i : B - 1;
+      a[i] = *reinterpret_cast<const uint4*>(x + (size_t)t * d + c);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int e = e0 + j < N ? e0 + j : N - 1;
+      b[j] = *reinterpret_cast<const uint4*>(w_router + (size_t)e * d + c);
+    }
+#pragma unroll
+    for (int q = 0; q < EPL; ++q) {  // element by element: every sum takes its terms in ascending order
+      double af[4], bf[8];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) af[i] = widen_elem<WT>(a[i], q);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) bf[j] = widen_elem<WT>(b[j], q);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = fma(af[i], bf[j], acc[i][j]);
+    }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1)
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[i][j] += __shfl_xor(acc[i][j], off, 64);
+  if (lane == 0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (t0 + i < B && e0 + j < N)
+          logits[(size_t)(t0 + i) * N + e0 + j] = float(acc[i][j] + (bias ? double(bias[e0 + j]) : 0.0));
+  }
+}
+
+// 2. wide_phase1_kernel: a wavefront per token takes its k0 best experts (Phase 1 of Algorithm 1); the
+//    workgroup's 16 tokens are united in LDS first, and only bits that the union in memory does not
+//    show yet are added there (one atomic per token and pick on the same few words serialises: 60 us
+//    at B = 1024).
+template <int NV>
+__global__ __launch_bounds__(kRouteThreads) void wide_phase1_kernel(const float* __restrict__ logits,
+                                                                    const uint8_t* __restrict__ token_mask, int B, int N,
+                                                                    int k0, uint32_t* ctrl) {
+  __shared__ uint32_t s_u[16];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int t = blockIdx.x * (kRouteThreads / 64) + (tid >> 6);
+  if (ctrl[kCtrlMagicWord] != kWsMagic) return;
+  if (tid < 16) s_u[tid] = 0u;
+  __syncthreads();
+  if (t < B && !(token_mask && token_mask[t] == 0)) {
+    uint32_t key[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int e = lane + 64 * j;
+      key[j] = e < N ? make_key(logits[(size_t)t * N + e]) : 0;
+    }
+    for (int r = 0; r < k0; ++r) {
+      uint32_t bk;
+      int id;
+      if (!pick_best<NV>(key, lane, bk, id)) break;
+      if (lane == 0) atomicOr(&s_u[id >> 5], 1u << (id & 31));
+    }
+  }
+  __syncthreads();
+  if (tid < 16) {
+    uint32_t* const g = ctrl + kCtrlWideUnion + tid;
+    const uint32_t fresh = s_u[tid] & ~__hip_atomic_load(g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (fresh) atomicOr(g, fresh);
+  }
+}
+
+// 3. wide_phase2_kernel: a wavefront per token takes its best members of the union, up to k (Phase 2
+//    in closed form), computes the weights of Eq. 1, and draws a place in each chosen expert's group
+//    from that expert's counter (kept in grp_pos until the last kernel knows where the group starts).
+//    The order of the pairs inside a group is the order of arrival: nothing depends on it.
+template <int NV>
+__global__ __launch_bounds__(kRouteThreads) void wide_phase2_kernel(const float* __restrict__ logits,
+                                                                    const uint8_t* __restrict__ token_mask, int B, int N,
+                                                                    int k, uint32_t* ctrl, RouteOut o) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * (kRouteThreads / 64) + (threadIdx.x >> 6);
+  if (ctrl[kCtrlMagicWord] != kWsMagic || t >= B) return;
+  const bool live = !(token_mask && token_mask[t] == 0);
+  const uint32_t* U = ctrl + kCtrlWideUnion;
+  uint32_t key[NV];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int e = lane + 64 * j;
+    const bool cand = live && e < N && ((U[e >> 5] >> (e & 31)) & 1u);
+    key[j] = cand ? make_key(logits[(size_t)t * N + e]) : 0;
+  }
+  int n = 0, my_id = -1;
+  float my_logit = 0.f;
+  for (int r = 0; r < k; ++r) {
+    uint32_t bk;
+    int id;
+    if (!pick_best<NV>(key, lane, bk, id)) break;
+    if (lane == r) {
+      my_id = id;
+      my_logit = from_orderable(bk);
+    }
+    ++n;
+  }
+  // g_s = exp(l_s - m) / sum_{s'} exp(l_s' - m): the softmax denominator cancels in Eq. 1
+  const float m = __shfl(my_logit, 0, 64);
+  const float w = lane < n ? expf(my_logit - m) : 0.f;
+  const float z = wave_sum_f32(w);
+  if (lane < k) {
+    o.expert_idx[(size_t)t * k + lane] = lane < n ? my_id : -1;
+    o.gate_w[(size_t)t * k + lane] = lane < n ? w / z : 0.f;
+    o.grp_pos[(size_t)t * k + lane] = lane < n ? int(atomicAdd(ctrl + kCtrlWideCount + my_id, 1u)) : -1;
+  }
+  if (lane == 0) o.n_sel[t] = n;
+}
+
+// 4. wide_group_kernel: every workgroup derives the active list and the group offsets from the union
+//    and the counts (workgroup 0 writes them out), then sends its share of the pairs to their places.
+__global__ __launch_bounds__(kRouteThreads) void wide_group_kernel(int B, int N, int k, const uint32_t* ctrl, RouteOut o) {
+  __shared__ int s_off[OEA_MAX_N];   // first pair of expert e's group
+  __shared__ int s_wave[2][kRouteThreads / 64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (ctrl[kCtrlMagicWord] != kWsMagic) return;
+  // thread e: member of the union?  how many pairs?  (N <= 512 <= threads)
+  const bool member = tid < N && ((ctrl[kCtrlWideUnion + (tid >> 5)] >> (tid & 31)) & 1u);
+  const int cnt = member ? int(ctrl[kCtrlWideCount + tid]) : 0;
+  const int inc_m = wave_incl_scan_i32(member ? 1 : 0, lane), inc_c = wave_incl_scan_i32(cnt, lane);
+  if (lane == 63) {
+    s_wave[0][wave] = inc_m;
+    s_wave[1][wave] = inc_c;
+  }
+  __syncthreads();
+  int base_m = 0, base_c = 0, T = 0, total = 0;
+  for (int w = 0; w < kRouteThreads / 64; ++w) {
+    if (w < wave) {
+      base_m += s_wave[0][w];
+      base_c += s_wave[1][w];
+    }
+    T += s_wave[0][w];
+    total += s_wave[1][w];
+  }
+  const int a = base_m + inc_m - 1, off = base_c + inc_c - cnt;
+  if (tid < N) s_off[tid] = off;
+  if (blockIdx.x == 0) {
+    if (member) {
+      o.active_list[a] = tid;
+      o.grp_off[a] = off;
+    }
+    if (tid >= T && tid < N) o.active_list[tid] = -1;
+    if (tid == 0) {
+      *o.n_active = T;
+      o.grp_off[T] = total;
+    }
+  }
+  __syncthreads();
+  const int P = B * k;
+  for (int i = blockIdx.x * kRouteThreads + tid; i < P; i += gridDim.x * kRouteThreads) {
+    const int e = o.expert_idx[i];
+    if (e >= 0 && e < N) {
+      const int dst = s_off[e] + o.grp_pos[i];
+      if (dst >= 0 && dst < P) {  // always true; bounds the stores
+        o.grp_tok[dst] = i / k;
+        o.grp_gw[dst] = o.gate_w[i];
+        o.grp_pos[i] = dst;
+      }
+    }
+  }
+}
+
 __global__ void ws_prepare_kernel(uint32_t* p, size_t n) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = i == (size_t)kCtrlMagicWord ? kWsMagic : 0u;
@@ -205,6 +440,30 @@ static hipError_t launch_rr(const void* x, const void* w_router, const float* bi
   RouteGeneral g{1.0, k, N, nullptr};
   const int general = ga && (ga->p < 1.0 || ga->max_p < N) ? 1 : 0;
   if (general) g = RouteGeneral{ga->p, k, ga->max_p, nullptr};
+  if (!general && B > kWideFromBatch && o.grp_off && o.grp_tok && o.grp_gw && o.grp_pos) {
+    // large batch: router and routing over many workgroups, four kernels in stream order
+    const int per_wg = kRouteThreads / 64;
+    hipLaunchKernelGGL((wide_logits_kernel<WT>), dim3((B + 7) / 8, (N + 15) / 16), dim3(kWideThreads), 0, s,
+                       static_cast<const WT*>(x), static_cast<const WT*>(w_router), bias, B, d, N, logits, out_to_zero,
+                       n_zero, counter, o.n_active);
+    switch (nv_for(N)) {
+#define OEA_CASE(NV)                                                                                                 \
+  case NV:                                                                                                           \
+    hipLaunchKernelGGL((wide_phase1_kernel<NV>), dim3((B + per_wg - 1) / per_wg), dim3(kRouteThreads), 0, s, logits, \
+                       token_mask, B, N, k0, counter);                                                               \
+    hipLaunchKernelGGL((wide_phase2_kernel<NV>), dim3((B + per_wg - 1) / per_wg), dim3(kRouteThreads), 0, s, logits, \
+                       token_mask, B, N, k, counter, o);                                                             \
+    break;
+      OEA_CASE(1)
+      OEA_CASE(2)
+      OEA_CASE(4)
+      OEA_CASE(8)
+#undef OEA_CASE
+    }
+    const int group_wgs = (B * k + 2 * kRouteThreads - 1) / (2 * kRouteThreads);
+    hipLaunchKernelGGL(wide_group_kernel, dim3(group_wgs), dim3(kRouteThreads), 0, s, B, N, k, counter, o);
+    return hipGetLastError();
+  }
   const size_t lds = route_lds_bytes(B, N);
   switch (nv_for(N)) {
 #define OEA_CASE(NV)                                                                                       \
