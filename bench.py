@@ -387,7 +387,7 @@ def other_workloads(args, hip, sptr, stream, sets_30b):
             rows.append(dict(workload=tag, B=B, k0=k0, unique_experts=T, pairs=pairs, latency_us=round(us, 2),
                              layer_GBps=round(nbytes / us / 1e3, 1), frac_of_hbm_peak=round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4)))
 
-    for B in (1, 32, 128):
+    for B in (1, 32, 128, 512):  # 512: above the single kernel's range (router/routing kernels, matrix-core stages)
         timed("qwen3_30b", "qwen3_30b", B, (3,), sets_30b, 2100)
     timed("qwen3_30b_skew", "qwen3_30b_skew", 16, (2, 4), sets_30b, 2000)
     cfg = workloads.CONFIGS["qwen3_235b"]
@@ -725,7 +725,7 @@ def run(args):
     fit2 = None
     if others is not None:
         cells = [(v["unique_experts"], v["pairs"], v["latency_us"]) for v in table.values()] + \
-                [(r_["unique_experts"], r_["pairs"], r_["latency_us"]) for r_ in others if r_["workload"] == "qwen3_30b"]
+                [(r_["unique_experts"], r_["pairs"], r_["latency_us"]) for r_ in others if r_["workload"] == "qwen3_30b" and r_["B"] <= 128]  # the single kernel's range
         A2 = np.array([[1.0, c[0], c[1]] for c in cells])
         y2 = np.array([c[2] for c in cells])
         coef, *_ = np.linalg.lstsq(A2, y2, rcond=None)
