@@ -189,8 +189,10 @@ typedef struct {
   int32_t *n_sel_out;         /* [B]   */
   int32_t *active_list_out;   /* [N]   */
   int32_t *n_active_out;      /* [1]   */
-  double top_p;               /* general OEA (Algorithm 2): top-p cut of the baseline; 0 or >= 1 = off */
-  int32_t max_p;              /* general OEA: piggyback only among the max_p best ranks; 0 or >= N = off.
+  double top_p;               /* general OEA (Algorithm 2): top-p cut of the baseline; 0 or >= 1 = off
+                                 (negative or NaN: OEA_ERR_K) */
+  int32_t max_p;              /* general OEA: piggyback only among the max_p best ranks; 0 or >= N = off
+                                 (negative: OEA_ERR_K).
                                  With either set, k plays the role of k_max.  Where the single-kernel layer
                                  applies (see moe_decode) the general routing runs inside that kernel. */
   int32_t deterministic;      /* non-zero: Eq. 1's sum over the selected experts is taken in slot order by

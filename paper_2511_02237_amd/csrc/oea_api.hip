@@ -180,6 +180,13 @@ static int check_decode_args(const void* x, const void* W_router, const void* W_
   return OEA_OK;
 }
 
+// The extras' numeric fields: a negative or NaN top_p and a negative max_p mean nothing.
+static int check_extras(const oea_decode_ex* ex) {
+  if (!ex) return OEA_OK;
+  if (!(ex->top_p >= 0.0) || ex->max_p < 0) return OEA_ERR_K;
+  return OEA_OK;
+}
+
 // workspace bytes a call needs: more with the deterministic combine
 static size_t workspace_need(int B, int d, int N, int I, int k, const oea_decode_ex* ex) {
   return ex && ex->deterministic ? oea_workspace_bytes_deterministic(B, d, N, I, k) : oea_workspace_bytes(B, d, N, I, k);
@@ -280,6 +287,7 @@ extern "C" int moe_decode_ex(const void* x, const void* W_router, const void* W_
   int rc = check_decode_args(x, W_router, W_gate, W_up, W_down, out, B, d, N, I, k, k0, dt);
   if (rc != OEA_OK) return rc;
   if (!aligned16(workspace)) return OEA_ERR_ALIGN;
+  if ((rc = check_extras(ex)) != OEA_OK) return rc;
   if (workspace_bytes < workspace_need(B, d, N, I, k, ex)) return OEA_ERR_WORKSPACE;
   return decode_enqueue(x, W_router, W_gate, W_up, W_down, out, B, d, N, I, k, k0, dt, workspace, stream, ex);
 }
@@ -292,6 +300,7 @@ extern "C" int moe_decode_test(const void* x, const void* W_router, const void* 
   int rc = check_decode_args(x, W_router, W_gate, W_up, W_down, out, B, d, N, I, k, k0, dt);
   if (rc != OEA_OK) return rc;
   if (!aligned16(workspace)) return OEA_ERR_ALIGN;
+  if ((rc = check_extras(ex)) != OEA_OK) return rc;
   if (workspace_bytes < workspace_need(B, d, N, I, k, ex)) return OEA_ERR_WORKSPACE;
   return decode_enqueue(x, W_router, W_gate, W_up, W_down, out, B, d, N, I, k, k0, dt, workspace, stream, ex, opts);
 }
@@ -325,6 +334,7 @@ extern "C" int moe_decode_static(const void* x, const void* W_router, const void
                                  int dt, void* stream, const oea_decode_ex* ex) {
   int rc = check_decode_args(x, W_router, W_gate, W_up, W_down, out, B, d, N, I, k, k0, dt);
   if (rc != OEA_OK) return rc;
+  if ((rc = check_extras(ex)) != OEA_OK) return rc;
   const size_t need = workspace_need(B, d, N, I, k, ex);
   if (need == 0 || need > (size_t)OEA_STATIC_SCRATCH_BYTES) return OEA_ERR_LIMIT;  // before any HIP call
   int dev = -1;

@@ -33,8 +33,9 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
-constexpr int kDenseGroups = 4;     // groups of 16 tokens per pass
+constexpr int kDenseGroups = 8;     // groups of 16 tokens per pass
 constexpr int kDenseTokens = 16 * kDenseGroups;
+constexpr int kDenseBLoads = kDenseTokens / 64;  // token-row pieces a lane loads per slab (8 rows per wavefront and load)
 constexpr int kDenseSlab = 64;      // columns per slab: two matrix-core steps of 32
 constexpr int kDenseLook = 4;       // slabs requested ahead
 constexpr int kDenseRowQuads = 9;   // 16-byte pieces between consecutive rows of a slab in LDS (8 + 1 of padding)
@@ -68,14 +69,13 @@ struct DenseJob {
 
 // Token and gate weight of the pairs of the workgroup's experts are copied to LDS before the first
 // weight request: a load from memory inside the pipeline would have to wait for every weight load
-// issued before it (the memory counter completes in order).  A workgroup whose experts hold more
-// pairs than the copy has room for (extreme skew) copies them job by job instead and pays that
-// wait once per job.
+// issued before it (the memory counter completes in order).  A workgroup's units span at most
+// ceil(N / workgroups) + 1 experts of at most B pairs each; the launcher only starts the kernel if
+// that many fit.
 struct DenseMeta {
   int* tok;     // LDS [kDenseMeta]: tokens, clamped to [0, B)
   float* gw;    // LDS [kDenseMeta]
-  int first;    // whole copy: pair number of entry 0
-  bool whole;   // every pair of the workgroup's experts is in the copy
+  int first;    // pair number of entry 0
 };
 
 // Where one wavefront finds a job's operands: wave-uniform base addresses (they stay in scalar
@@ -84,7 +84,7 @@ struct DenseMeta {
 struct DenseOperands {
   const char* a0;   // first row of the wavefront's tile 0
   const char* a1;   // ... of tile 1: W_up (gate/up stage) or the next 16 rows of W_down
-  uint32_t off_b;   // per lane: its piece of its token row
+  uint32_t off_b[kDenseBLoads];  // per lane: its piece of its token rows
 };
 
 __device__ __forceinline__ u32x4_t load_stream_q(const char* base, uint32_t off) {
@@ -130,18 +130,22 @@ __device__ __forceinline__ DenseOperands dense_operands(const DenseParams& p, co
   const size_t first = ((size_t)j.e * p.rows + (size_t)(j.row0 + wave * kWaveRows)) * p.L * sizeof(uint16_t);
   o.a0 = reinterpret_cast<const char*>(p.wa) + first;
   o.a1 = STAGE == 0 ? reinterpret_cast<const char*>(p.wb) + first : o.a0 + (size_t)16 * p.L * sizeof(uint16_t);
-  const int n = wave * 8 + (lane >> 3);  // the token row this lane helps to load; past the last one: the last again
-  const int nn = n < j.cnt ? n : j.cnt - 1;
-  int pi = j.pair0 + nn;
-  pi = pi < 0 ? 0 : (pi >= p.pairs_max ? p.pairs_max - 1 : pi);
-  const int vrow = STAGE == 0 ? mv.tok[j.mbase + nn] : pi;
-  o.off_b = (uint32_t(vrow) * uint32_t(p.L) + (lane & 7) * 8) * uint32_t(sizeof(uint16_t));  // < 2^31 (launcher)
+#pragma unroll
+  for (int h = 0; h < kDenseBLoads; ++h) {
+    const int n = h * 64 + wave * 8 + (lane >> 3);  // a token row this lane helps to load; past the last one: the last again
+    const int nn = n < j.cnt ? n : j.cnt - 1;
+    int pi = j.pair0 + nn;
+    pi = pi < 0 ? 0 : (pi >= p.pairs_max ? p.pairs_max - 1 : pi);
+    const int vrow = STAGE == 0 ? mv.tok[j.mbase + nn] : pi;
+    // below 2^31 by the entry points' limits on B, k, d and I
+    o.off_b[h] = (uint32_t(vrow) * uint32_t(p.L) + (lane & 7) * 8) * uint32_t(sizeof(uint16_t));
+  }
   return o;
 }
 
 // registers of one slab in flight: four pieces of weight rows (tile 0 rows 0-7, 8-15, tile 1 likewise), one of a token row
 struct DenseSlab {
-  u32x4_t a[4], b;
+  u32x4_t a[4], b[kDenseBLoads];
 };
 
 template <int STAGE>
@@ -153,7 +157,8 @@ __device__ __forceinline__ void dense_request(DenseSlab& r, const DenseParams& p
   r.a[1] = load_stream_q(q.a0 + rows8 + col, off_a);
   r.a[2] = load_stream_q(q.a1 + col, off_a);
   r.a[3] = load_stream_q(q.a1 + rows8 + col, off_a);
-  r.b = load_plain_q(reinterpret_cast<const char*>(p.vec) + col, q.off_b);
+#pragma unroll
+  for (int h = 0; h < kDenseBLoads; ++h) r.b[h] = load_plain_q(reinterpret_cast<const char*>(p.vec) + col, q.off_b[h]);
 }
 
 // The slab loop of one job with ng token groups.  ring[] holds the slabs in flight (slot = slab % 4).
@@ -178,12 +183,14 @@ __device__ __forceinline__ void dense_run(DenseSlab (&ring)[kDenseLook], const D
       wa_[(wrow + 8) * kDenseRowQuads + wcol] = ring[s].a[1];
       wa_[(16 + wrow) * kDenseRowQuads + wcol] = ring[s].a[2];
       wa_[(24 + wrow) * kDenseRowQuads + wcol] = ring[s].a[3];
-      wb_[(wave * 8 + wrow) * kDenseRowQuads + wcol] = ring[s].b;
+#pragma unroll
+      for (int h = 0; h < kDenseBLoads; ++h) wb_[(h * 64 + wave * 8 + wrow) * kDenseRowQuads + wcol] = ring[s].b[h];
       {  // selected without a branch: the bases are scalars
         DenseOperands src;
         src.a0 = last ? nxt.a0 : cur.a0;
         src.a1 = last ? nxt.a1 : cur.a1;
-        src.off_b = last ? nxt.off_b : cur.off_b;
+#pragma unroll
+        for (int h = 0; h < kDenseBLoads; ++h) src.off_b[h] = last ? nxt.off_b[h] : cur.off_b[h];
         dense_request<STAGE>(ring[s], p, src, off_a, last ? s : sl + kDenseLook + s);
       }
       __syncthreads();
@@ -293,22 +300,15 @@ __global__ __launch_bounds__(kFfnThreads) void expert_dense_kernel(DenseParams p
     const int a_first = u0 / upe, a_last = (u1 - 1) / upe;  // u1 > u0: there is a valid job
     const int m0 = sgpr(l_off[a_first]), m1 = sgpr(l_off[a_last + 1]);
     mv.first = m0;
-    mv.whole = m0 >= 0 && m1 >= m0 && m1 - m0 <= kDenseMeta && m1 <= p.pairs_max;
-  }
-  auto copy_meta = [&](int first, int n, int at) {  // pairs [first, first + n) -> entries [at, at + n)
-    for (int i = tid; i < n; i += kFfnThreads) {
-      const int t = p.g.grp_tok[first + i];
-      mv.tok[at + i] = t < 0 ? 0 : (t >= p.B ? p.B - 1 : t);
-      mv.gw[at + i] = p.g.grp_gw[first + i];
+    // never false after a valid routing (see DenseMeta); keeps the copy inside its LDS area
+    if (!(m0 >= 0 && m1 >= m0 && m1 - m0 <= kDenseMeta && m1 <= p.pairs_max)) return;
+    for (int i = tid; i < m1 - m0; i += kFfnThreads) {
+      const int t = p.g.grp_tok[m0 + i];
+      mv.tok[i] = t < 0 ? 0 : (t >= p.B ? p.B - 1 : t);
+      mv.gw[i] = p.g.grp_gw[m0 + i];
     }
-  };
-  if (mv.whole) {
-    copy_meta(mv.first, sgpr(l_off[(u1 - 1) / upe + 1]) - mv.first, 0);
-    cur.mbase = cur.pair0 - mv.first;
-  } else {
-    copy_meta(cur.pair0, cur.cnt, 0);
-    cur.mbase = 0;
   }
+  cur.mbase = cur.pair0 - mv.first;
   __syncthreads();
   DenseOperands pc = dense_operands<STAGE>(p, mv, cur, wave, lane);
   // per lane: row lane / 8 of a group of eight rows, 16-byte piece lane % 8 of the slab's 128 bytes
@@ -319,16 +319,7 @@ __global__ __launch_bounds__(kFfnThreads) void expert_dense_kernel(DenseParams p
   while (cur.valid) {
     // the job after this one; without one the last refills read this job's first slabs again (unused)
     DenseJob nxt = dense_job<STAGE>(l_active, l_off, cur.u, cur.pass + 1, u1, upe, p.pairs_max);
-    if (nxt.valid) {
-      if (mv.whole) {
-        nxt.mbase = nxt.pair0 - mv.first;
-      } else {  // the two jobs' entries alternate between the halves of the first 128
-        nxt.mbase = cur.mbase ^ kDenseTokens;
-        __syncthreads();  // the job before this one is done with that half
-        copy_meta(nxt.pair0, nxt.cnt, nxt.mbase);
-        __syncthreads();
-      }
-    }
+    nxt.mbase = nxt.pair0 - mv.first;
     const DenseOperands pn = nxt.valid ? dense_operands<STAGE>(p, mv, nxt, wave, lane) : pc;
     f32x4_t acc[kDenseGroups][2];
 #pragma unroll
@@ -353,6 +344,8 @@ hipError_t try_launch_dense_stage(int stage, const void* vec, const void* wa, co
   int dev = 0, grid = 0;
   if (!current_device(&dev, &grid)) return hipErrorUnknown;
   if (grid < 1) return hipErrorNotSupported;
+  // the pairs of the experts one workgroup can touch must fit its LDS copy of their tokens and weights
+  if (((long long)(N + grid - 1) / grid + 1) * B > kDenseMeta) return hipErrorNotSupported;
   DenseParams p{};
   p.wa = static_cast<const uint16_t*>(wa);
   p.wb = static_cast<const uint16_t*>(wb);

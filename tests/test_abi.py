@@ -143,6 +143,14 @@ def test_decode_argument_checks(L):
     bad = Opts(kernel_path=5)
     assert L.moe_decode_test(*(ok + [None, C.addressof(bad)])) == -2  # refused before any enqueue
 
+    # extras with a meaningless top_p / max_p are refused with the k-range error, before any enqueue
+    class Ex(C.Structure):
+        _fields_ = [(n, C.c_void_p) for n in ("router_bias", "token_mask", "logits_out", "expert_idx_out", "gate_w_out",
+                                              "n_sel_out", "active_list_out", "n_active_out")] + \
+                   [("top_p", C.c_double), ("max_p", C.c_int32), ("deterministic", C.c_int32), ("cooperative", C.c_int32)]
+    for bad_ex in (Ex(top_p=-0.5), Ex(top_p=float("nan")), Ex(max_p=-1)):
+        assert L.moe_decode_ex(*(ok + [C.addressof(bad_ex)])) == -3
+
 
 def test_decode_static_argument_checks(L):
     """The allocation-free entry point: the same checks, and sizes beyond its built-in scratch are

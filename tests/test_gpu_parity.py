@@ -666,6 +666,14 @@ def test_matrix_core_stages(torch, B_, oracle):
     mask = np.ones(256, np.uint8)
     mask[[0, 100, 255]] = 0
     L, dev = case("matrix cores B=256, three distinct tokens, automatic path, mask", x, 3, None, mask=mask, min_pairs=65)
+    # a ragged batch above 128 with a router bias and padded tokens, Phase 2 with and without rounds (the
+    # router and the routing then run as four kernels over many workgroups)
+    rng = np.random.Generator(np.random.PCG64(78))
+    bias = (rng.standard_normal(L0.N) * 0.7).astype(np.float32)
+    x = np.ascontiguousarray(np.concatenate([L0.x, L0.x[:43][::-1]]))  # 203 tokens
+    mask = (rng.integers(0, 6, size=x.shape[0]) != 0).astype(np.uint8)
+    for k0 in (3, 8):
+        case("matrix cores B=203 k0=%d, bias and mask" % k0, x, k0, None, bias=bias, mask=mask)
     # deterministic combine through the same stages: one row per pair, bit-identical from call to call
     ws = B_.new_workspace(L.B, L.d, L.N, L.I, L.k, deterministic=True)
     first = None
