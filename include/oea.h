@@ -155,7 +155,7 @@ int oea_route_general(const float *router_logits, const uint8_t *token_mask, int
  * A caller that runs other kernels beside the layer (a second stream) sets
  * oea_decode_ex.cooperative, which makes co-residency the runtime's guarantee.  Still larger batches run as
  * three kernels (router + routing, gate/up stage, down stage) with the expert stages on the matrix
- * cores (bf16, I a multiple of 128, d of 256: an expert then serves 16 and more tokens and the
+ * cores (bf16, d and I multiples of 256: an expert then serves 16 and more tokens and the
  * arithmetic per pair, Eq. 2's second term, would bound the vector ALUs); every other shape, and fp32
  * storage, runs as three kernels with dot-product expert kernels.
  * Arithmetic: router logits are accumulated in fp64 and rounded once to fp32; expert mat-vecs

@@ -666,6 +666,14 @@ def test_matrix_core_stages(torch, B_, oracle):
     mask = np.ones(256, np.uint8)
     mask[[0, 100, 255]] = 0
     L, dev = case("matrix cores B=256, three distinct tokens, automatic path, mask", x, 3, None, mask=mask, min_pairs=65)
+    # small shapes: both stages on the matrix cores (several experts per workgroup, more workgroups than
+    # units), and one where only the gate/up stage qualifies (I = 128: the down stage keeps the dot products)
+    for (d, I, N, B, k) in [(512, 256, 6, 200, 3), (256, 256, 3, 40, 2), (256, 128, 8, 40, 2), (1024, 512, 20, 300, 4)]:
+        Lt = W.make_layer("toy", 640, d=d, I=I, N=N, B=B, k=k, dtype="bf16")
+        for k0 in (1, k):
+            for path in (4, None):
+                out, tap = run_layer(torch, B_, Lt, k0, path=path)
+                check_layer(oracle, Lt, k0, out, tap, "matrix cores d=%d I=%d N=%d B=%d k0=%d path %s" % (d, I, N, B, k0, path))
     # a ragged batch above 128 with a router bias and padded tokens, Phase 2 with and without rounds (the
     # router and the routing then run as four kernels over many workgroups)
     rng = np.random.Generator(np.random.PCG64(78))
