@@ -380,6 +380,13 @@ def test_full_size_235b_shape(torch, B_, oracle):
     out, tap = run_layer_dev(torch, B_, Lb, devb, 3)
     err, ref = check_layer(oracle, Lb, 3, out, tap, "qwen3_235b B=48 k0=3")
     say("qwen3_235b B=48 k0=3 T=%d err=%.2e" % (ref["n_active"], err))
+    # the same batch through the matrix-core expert stages (this shape: 12 and 16 units per expert, 64 and
+    # 24 slabs per unit); the oracle's result of the run above serves again
+    out4, tap4 = run_layer_dev(torch, B_, Lb, devb, 3, path=4)
+    assert np.array_equal(tap4["expert_idx"], tap["expert_idx"]) and np.array_equal(tap4["logits"], tap["logits"])
+    err4 = np.abs(out4.astype(np.float64) - ref["out"]).max() / np.abs(ref["out"]).max()
+    say("qwen3_235b B=48 k0=3 matrix-core stages err=%.2e" % err4)
+    assert err4 <= TOL[Lb.dtype]
 
 
 # ---- general OEA (Algorithm 2): top-p cut of the baseline, k_max, rank window max_p
