@@ -9,8 +9,8 @@
 //
 // A workgroup (8 wavefronts) takes units of 128 rows of W_gate AND W_up of one expert (gate/up
 // stage; 16 rows of each per wavefront) or 256 rows of W_down (down stage; 32 per wavefront) and
-// walks the inner dimension in slabs of 64 columns, against up to 64 tokens of the expert at a
-// time (accumulators for 4 groups of 16 tokens x 2 weight tiles stay in registers; an expert with
+// walks the inner dimension in slabs of 64 columns, against up to 128 tokens of the expert at a
+// time (accumulators for 8 groups of 16 tokens x 2 weight tiles stay in registers; an expert with
 // more tokens takes further passes over the same rows).
 //   * Every operand is loaded from memory with whole 128-byte row pieces per 8 lanes (a lane
 //     pattern in the instruction's operand layout, 16 different rows per 16 lanes, costs several
@@ -55,14 +55,14 @@ struct DenseParams {
   int per_pair;
 };
 
-// One job of a workgroup: a unit (expert, block of rows) against one pass of at most 64 pairs.
+// One job of a workgroup: a unit (expert, block of rows) against one pass of at most kDenseTokens pairs.
 struct DenseJob {
   int u;      // unit number; units are numbered expert-major over the active list
   int pass;
   int e;      // expert id
   int row0;   // first row of the unit inside the expert
   int pair0;  // first pair of the pass (grouped order)
-  int cnt;    // pairs in the pass, 1..64
+  int cnt;    // pairs in the pass, 1..kDenseTokens
   int mbase;  // entry of pair0 in the token / gate-weight copy in LDS
   bool valid;
 };
