@@ -253,73 +253,141 @@ __global__ __launch_bounds__(kWideThreads) void wide_logits_kernel(const WT* __r
   }
 }
 
-// 2. wide_phase1_kernel: a wavefront per token takes its k0 best experts (Phase 1 of Algorithm 1); the
-//    workgroup's 16 tokens are united in LDS first, and only bits that the union in memory does not
-//    show yet are added there (one atomic per token and pick on the same few words serialises: 60 us
-//    at B = 1024).
-template <int NV>
+// 2. wide_phase1_kernel: a wavefront per token takes its k0 best experts (Phase 1 of Algorithm 1; with
+//    GEN the baseline of Algorithm 2: cut where the cumulative softmax mass, fp64, reaches p, its size
+//    parked in n_sel for the next kernel); the workgroup's 16 tokens are united in LDS first, and
+//    only bits that the union in memory does not show yet are added there (one atomic per token and
+//    pick on the same few words serialises: 60 us at B = 1024).
+template <int NV, bool GEN>
 __global__ __launch_bounds__(kRouteThreads) void wide_phase1_kernel(const float* __restrict__ logits,
                                                                     const uint8_t* __restrict__ token_mask, int B, int N,
-                                                                    int k0, uint32_t* ctrl) {
+                                                                    int k0, RouteGeneral g, uint32_t* ctrl, int32_t* n_sel) {
   __shared__ uint32_t s_u[16];
   const int tid = threadIdx.x, lane = tid & 63;
   const int t = blockIdx.x * (kRouteThreads / 64) + (tid >> 6);
   if (ctrl[kCtrlMagicWord] != kWsMagic) return;
   if (tid < 16) s_u[tid] = 0u;
   __syncthreads();
-  if (t < B && !(token_mask && token_mask[t] == 0)) {
-    uint32_t key[NV];
+  if (t < B) {
+    const bool live = !(token_mask && token_mask[t] == 0);
+    int n = 0;
+    if (live) {
+      uint32_t key[NV];
+      float lg[NV];
 #pragma unroll
-    for (int j = 0; j < NV; ++j) {
-      const int e = lane + 64 * j;
-      key[j] = e < N ? make_key(logits[(size_t)t * N + e]) : 0;
+      for (int j = 0; j < NV; ++j) {
+        const int e = lane + 64 * j;
+        lg[j] = e < N ? logits[(size_t)t * N + e] : 0.f;
+        key[j] = e < N ? make_key(lg[j]) : 0;
+      }
+      const bool capped = GEN && g.p < 1.0;
+      double m = 0.0, z = 1.0;
+      if (capped) {  // softmax denominator over all N experts
+        uint32_t lm = key[0];
+#pragma unroll
+        for (int j = 1; j < NV; ++j) lm = key[j] > lm ? key[j] : lm;
+        m = double(from_orderable(wave_max_u32(lm)));
+        double zl = 0.0;
+#pragma unroll
+        for (int j = 0; j < NV; ++j)
+          if (key[j] != 0) zl += exp(double(lg[j]) - m);
+        z = wave_sum_f64(zl);
+      }
+      double cum = 0.0;
+      for (int r = 0; r < k0; ++r) {
+        uint32_t bk;
+        int id;
+        if (!pick_best<NV>(key, lane, bk, id)) break;
+        if (lane == 0) atomicOr(&s_u[id >> 5], 1u << (id & 31));
+        ++n;
+        if (capped) {
+          cum += exp(double(from_orderable(bk)) - m) / z;
+          if (cum >= g.p) break;
+        }
+      }
     }
-    for (int r = 0; r < k0; ++r) {
-      uint32_t bk;
-      int id;
-      if (!pick_best<NV>(key, lane, bk, id)) break;
-      if (lane == 0) atomicOr(&s_u[id >> 5], 1u << (id & 31));
-    }
+    if (GEN && lane == 0) n_sel[t] = n;
   }
   __syncthreads();
   if (tid < 16) {
-    uint32_t* const g = ctrl + kCtrlWideUnion + tid;
-    const uint32_t fresh = s_u[tid] & ~__hip_atomic_load(g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (fresh) atomicOr(g, fresh);
+    uint32_t* const gu = ctrl + kCtrlWideUnion + tid;
+    const uint32_t fresh = s_u[tid] & ~__hip_atomic_load(gu, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (fresh) atomicOr(gu, fresh);
   }
 }
 
 // 3. wide_phase2_kernel: a wavefront per token takes its best members of the union, up to k (Phase 2
-//    in closed form), computes the weights of Eq. 1, and draws a place in each chosen expert's group
+//    in closed form; with GEN the baseline again, then the walk over the ranks below max_p of
+//    Algorithm 2), computes the weights of Eq. 1, and draws a place in each chosen expert's group
 //    from that expert's counter (kept in grp_pos until the last kernel knows where the group starts).
 //    The order of the pairs inside a group is the order of arrival: nothing depends on it.
-template <int NV>
+template <int NV, bool GEN>
 __global__ __launch_bounds__(kRouteThreads) void wide_phase2_kernel(const float* __restrict__ logits,
                                                                     const uint8_t* __restrict__ token_mask, int B, int N,
-                                                                    int k, uint32_t* ctrl, RouteOut o) {
+                                                                    int k, RouteGeneral g, uint32_t* ctrl, RouteOut o) {
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * (kRouteThreads / 64) + (threadIdx.x >> 6);
   if (ctrl[kCtrlMagicWord] != kWsMagic || t >= B) return;
   const bool live = !(token_mask && token_mask[t] == 0);
   const uint32_t* U = ctrl + kCtrlWideUnion;
+  auto in_union = [&](int e) { return e < N && ((U[e >> 5] >> (e & 31)) & 1u); };
   uint32_t key[NV];
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
     const int e = lane + 64 * j;
-    const bool cand = live && e < N && ((U[e >> 5] >> (e & 31)) & 1u);
+    const bool cand = live && e < N && (GEN || in_union(e));
     key[j] = cand ? make_key(logits[(size_t)t * N + e]) : 0;
   }
   int n = 0, my_id = -1;
   float my_logit = 0.f;
-  for (int r = 0; r < k; ++r) {
-    uint32_t bk;
-    int id;
-    if (!pick_best<NV>(key, lane, bk, id)) break;
-    if (lane == r) {
+  auto take = [&](int id, uint32_t bk) __attribute__((always_inline)) {
+    if (lane == n) {
       my_id = id;
       my_logit = from_orderable(bk);
     }
     ++n;
+  };
+  if (!GEN) {
+    for (int r = 0; r < k; ++r) {
+      uint32_t bk;
+      int id;
+      if (!pick_best<NV>(key, lane, bk, id)) break;
+      take(id, bk);
+    }
+  } else {
+    const int nbase = live ? o.n_sel[t] : 0;
+    if (g.max_p >= N) {
+      // no window: after the baseline, the piggybacked experts are the best remaining members of the union
+      for (int r = 0; r < nbase; ++r) {
+        uint32_t bk;
+        int id;
+        if (!pick_best<NV>(key, lane, bk, id)) break;
+        take(id, bk);
+      }
+#pragma unroll
+      for (int j = 0; j < NV; ++j)
+        if (!in_union(lane + 64 * j)) key[j] = 0;
+      while (n < g.k_max) {
+        uint32_t bk;
+        int id;
+        if (!pick_best<NV>(key, lane, bk, id)) break;
+        take(id, bk);
+      }
+    } else {
+      // walk the ranks in order; an expert outside the union uses up its rank without being taken
+      const int last = nbase > g.max_p ? nbase : g.max_p;
+      for (int r = 0; r < last; ++r) {
+        uint32_t bk;
+        int id;
+        if (!pick_best<NV>(key, lane, bk, id)) break;
+        if (r < nbase) {
+          take(id, bk);
+        } else {
+          if (n >= g.k_max) break;
+          if (in_union(id)) take(id, bk);
+        }
+      }
+    }
   }
   // g_s = exp(l_s - m) / sum_{s'} exp(l_s' - m): the softmax denominator cancels in Eq. 1
   const float m = __shfl(my_logit, 0, 64);
@@ -440,19 +508,26 @@ static hipError_t launch_rr(const void* x, const void* w_router, const float* bi
   RouteGeneral g{1.0, k, N, nullptr};
   const int general = ga && (ga->p < 1.0 || ga->max_p < N) ? 1 : 0;
   if (general) g = RouteGeneral{ga->p, k, ga->max_p, nullptr};
-  if (!general && B > kWideFromBatch && o.grp_off && o.grp_tok && o.grp_gw && o.grp_pos) {
+  if (B > kWideFromBatch && o.grp_off && o.grp_tok && o.grp_gw && o.grp_pos) {
     // large batch: router and routing over many workgroups, four kernels in stream order
     const int per_wg = kRouteThreads / 64;
     hipLaunchKernelGGL((wide_logits_kernel<WT>), dim3((B + 7) / 8, (N + 15) / 16), dim3(kWideThreads), 0, s,
                        static_cast<const WT*>(x), static_cast<const WT*>(w_router), bias, B, d, N, logits, out_to_zero,
                        n_zero, counter, o.n_active);
     switch (nv_for(N)) {
-#define OEA_CASE(NV)                                                                                                 \
-  case NV:                                                                                                           \
-    hipLaunchKernelGGL((wide_phase1_kernel<NV>), dim3((B + per_wg - 1) / per_wg), dim3(kRouteThreads), 0, s, logits, \
-                       token_mask, B, N, k0, counter);                                                               \
-    hipLaunchKernelGGL((wide_phase2_kernel<NV>), dim3((B + per_wg - 1) / per_wg), dim3(kRouteThreads), 0, s, logits, \
-                       token_mask, B, N, k, counter, o);                                                             \
+#define OEA_CASE(NV)                                                                                           \
+  case NV:                                                                                                     \
+    if (general) {                                                                                             \
+      hipLaunchKernelGGL((wide_phase1_kernel<NV, true>), dim3((B + per_wg - 1) / per_wg), dim3(kRouteThreads), \
+                         0, s, logits, token_mask, B, N, k0, g, counter, o.n_sel);                             \
+      hipLaunchKernelGGL((wide_phase2_kernel<NV, true>), dim3((B + per_wg - 1) / per_wg), dim3(kRouteThreads), \
+                         0, s, logits, token_mask, B, N, k, g, counter, o);                                    \
+    } else {                                                                                                   \
+      hipLaunchKernelGGL((wide_phase1_kernel<NV, false>), dim3((B + per_wg - 1) / per_wg),                     \
+                         dim3(kRouteThreads), 0, s, logits, token_mask, B, N, k0, g, counter, o.n_sel);        \
+      hipLaunchKernelGGL((wide_phase2_kernel<NV, false>), dim3((B + per_wg - 1) / per_wg),                     \
+                         dim3(kRouteThreads), 0, s, logits, token_mask, B, N, k, g, counter, o);               \
+    }                                                                                                          \
     break;
       OEA_CASE(1)
       OEA_CASE(2)

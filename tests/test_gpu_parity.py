@@ -455,9 +455,14 @@ def test_route_general_reduces_to_algorithm_1(torch, B_):
 
 
 def test_layer_general_oea(torch, B_, oracle):
-    """The whole layer under Algorithm 2 (top-p cut and rank window), three-kernel path."""
-    for name, k0, p, max_p in (("mid_bf16", 3, 0.2, None), ("mid_bf16", 4, None, 6), ("qwen3_30b", 3, 0.1, 24)):
-        L = W.make_layer(name, 11)
+    """The whole layer under Algorithm 2 (top-p cut and rank window), three-kernel path; above B = 128
+    the router and the routing run as four kernels over many workgroups."""
+    for name, B, k0, p, max_p in (("mid_bf16", None, 3, 0.2, None), ("mid_bf16", None, 4, None, 6),
+                                  ("qwen3_30b", None, 3, 0.1, 24),
+                                  ("mid_bf16", 200, 3, 0.2, None), ("mid_bf16", 300, 4, None, 6),
+                                  ("mid_bf16", 150, 3, 0.15, 8), ("mid_bf16", 1024, 2, 0.3, 5),
+                                  ("qwen3_30b", 160, 3, 0.1, 24)):
+        L = W.make_layer(name, 11, B=B)
         dev = {f: B_.to_device(getattr(L, f)) for f in ("x", "w_router", "w_gate", "w_up", "w_down")}
         ws = B_.new_workspace(L.B, L.d, L.N, L.I, L.k)
         out, tap = B_.moe_decode(dev["x"], dev["w_router"], dev["w_gate"], dev["w_up"], dev["w_down"], L.k, k0, ws,
@@ -465,7 +470,7 @@ def test_layer_general_oea(torch, B_, oracle):
         torch.cuda.synchronize()
         tap = {n: v.cpu().numpy() for n, v in tap.items()}
         pp, mp = (1.0 if p is None else p), (L.N if max_p is None else max_p)
-        ctx = "layer general %s k0=%d p=%s max_p=%s" % (name, k0, p, max_p)
+        ctx = "layer general %s B=%d k0=%d p=%s max_p=%s" % (name, L.B, k0, p, max_p)
         assert top_p_is_clear(tap["logits"], k0, pp), ctx
         ref = oracle.route_general(tap["logits"], k0, pp, L.k, mp)
         assert_routing_equal(tap, ref, ctx)
