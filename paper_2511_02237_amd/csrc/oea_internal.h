@@ -21,7 +21,13 @@ constexpr uint32_t kWsMagic = 0x4F454131u;
 // Phase 1 and the number of pairs per expert live in control words that are otherwise unused (the
 // first of these kernels clears them).
 constexpr int kCtrlWideUnion = 5120;  // [16]  bit e % 32 of word e / 32: expert e is in the union
-constexpr int kCtrlWideCount = 5152;  // [OEA_MAX_N]
+constexpr int kCtrlWideCount = 5152;  // counter of expert e at word e * wide_count_stride(N): atomics on one
+                                      // 128-byte line execute one after the other, so the counters are spread out
+constexpr int kCtrlWideCountWords = 9216 - kCtrlWideCount;
+__host__ __device__ inline int wide_count_stride(int N) {
+  const int s = kCtrlWideCountWords / (N > 0 ? N : 1);
+  return s > 32 ? 32 : (s < 1 ? 1 : s);
+}
 
 // State that is looked up or set once per DEVICE (a process may drive several): indexed by the
 // HIP device id of the calling thread's current device.
@@ -49,7 +55,7 @@ struct WsLayout {
                        // weights of the workgroups, adapted from call to call); [4] holds kWsMagic; the rest is zero
                        // between calls: [0] arrival counter of the router kernel, [3] error flag, [32], [64] and
                        // [256 + 32 i] grid-barrier words of the fused kernel, [1024..) its per-expert completion
-                       // counters, one 128-byte line each; [5120..5664) union mask and pair counts of the
+                       // counters, one 128-byte line each; [5120..9216) union mask and pair counts of the
                        // several-kernel routing of large batches (kCtrlWideUnion, kCtrlWideCount)
   size_t logits;       // float [B,N]
   size_t expert_idx;   // int32 [B,k]

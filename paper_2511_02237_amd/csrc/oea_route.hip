@@ -203,7 +203,7 @@ __global__ __launch_bounds__(kWideThreads) void wide_logits_kernel(const WT* __r
   }
   if (wg == 0) {
     if (tid < 16) ctrl[kCtrlWideUnion + tid] = 0u;
-    for (int i = tid; i < OEA_MAX_N; i += kWideThreads) ctrl[kCtrlWideCount + i] = 0u;
+    for (int i = tid; i < N; i += kWideThreads) ctrl[kCtrlWideCount + i * wide_count_stride(N)] = 0u;
   }
   const int t0 = blockIdx.x * 8 + (wave >> 1) * 4, e0 = blockIdx.y * 16 + (wave & 1) * 8;
   if (t0 >= B || e0 >= N) return;
@@ -255,16 +255,16 @@ __global__ __launch_bounds__(kWideThreads) void wide_logits_kernel(const WT* __r
 
 // 2. wide_phase1_kernel: a wavefront per token takes its k0 best experts (Phase 1 of Algorithm 1; with
 //    GEN the baseline of Algorithm 2: cut where the cumulative softmax mass, fp64, reaches p, its size
-//    parked in n_sel for the next kernel); the workgroup's 16 tokens are united in LDS first, and
+//    parked in n_sel for the next kernel); the workgroup's four tokens are united in LDS first, and
 //    only bits that the union in memory does not show yet are added there (one atomic per token and
 //    pick on the same few words serialises: 60 us at B = 1024).
 template <int NV, bool GEN>
-__global__ __launch_bounds__(kRouteThreads) void wide_phase1_kernel(const float* __restrict__ logits,
+__global__ __launch_bounds__(kWideThreads) void wide_phase1_kernel(const float* __restrict__ logits,
                                                                     const uint8_t* __restrict__ token_mask, int B, int N,
                                                                     int k0, RouteGeneral g, uint32_t* ctrl, int32_t* n_sel) {
   __shared__ uint32_t s_u[16];
   const int tid = threadIdx.x, lane = tid & 63;
-  const int t = blockIdx.x * (kRouteThreads / 64) + (tid >> 6);
+  const int t = blockIdx.x * (kWideThreads / 64) + (tid >> 6);
   if (ctrl[kCtrlMagicWord] != kWsMagic) return;
   if (tid < 16) s_u[tid] = 0u;
   __syncthreads();
@@ -319,14 +319,16 @@ __global__ __launch_bounds__(kRouteThreads) void wide_phase1_kernel(const float*
 // 3. wide_phase2_kernel: a wavefront per token takes its best members of the union, up to k (Phase 2
 //    in closed form; with GEN the baseline again, then the walk over the ranks below max_p of
 //    Algorithm 2), computes the weights of Eq. 1, and draws a place in each chosen expert's group
-//    from that expert's counter (kept in grp_pos until the last kernel knows where the group starts).
+//    from that expert's counter (kept in grp_pos until the last kernel knows where the group starts;
+//    the counters lie on cache lines of their own where they fit: side by side, their atomics took
+//    16 us at B = 1024 instead of 5).
 //    The order of the pairs inside a group is the order of arrival: nothing depends on it.
 template <int NV, bool GEN>
-__global__ __launch_bounds__(kRouteThreads) void wide_phase2_kernel(const float* __restrict__ logits,
+__global__ __launch_bounds__(kWideThreads) void wide_phase2_kernel(const float* __restrict__ logits,
                                                                     const uint8_t* __restrict__ token_mask, int B, int N,
                                                                     int k, RouteGeneral g, uint32_t* ctrl, RouteOut o) {
   const int lane = threadIdx.x & 63;
-  const int t = blockIdx.x * (kRouteThreads / 64) + (threadIdx.x >> 6);
+  const int t = blockIdx.x * (kWideThreads / 64) + (threadIdx.x >> 6);
   if (ctrl[kCtrlMagicWord] != kWsMagic || t >= B) return;
   const bool live = !(token_mask && token_mask[t] == 0);
   const uint32_t* U = ctrl + kCtrlWideUnion;
@@ -396,7 +398,8 @@ __global__ __launch_bounds__(kRouteThreads) void wide_phase2_kernel(const float*
   if (lane < k) {
     o.expert_idx[(size_t)t * k + lane] = lane < n ? my_id : -1;
     o.gate_w[(size_t)t * k + lane] = lane < n ? w / z : 0.f;
-    o.grp_pos[(size_t)t * k + lane] = lane < n ? int(atomicAdd(ctrl + kCtrlWideCount + my_id, 1u)) : -1;
+    uint32_t* const counter_of_mine = ctrl + kCtrlWideCount + (lane < n ? my_id : 0) * wide_count_stride(N);
+    o.grp_pos[(size_t)t * k + lane] = lane < n ? int(atomicAdd(counter_of_mine, 1u)) : -1;
   }
   if (lane == 0) o.n_sel[t] = n;
 }
@@ -410,7 +413,7 @@ __global__ __launch_bounds__(kRouteThreads) void wide_group_kernel(int B, int N,
   if (ctrl[kCtrlMagicWord] != kWsMagic) return;
   // thread e: member of the union?  how many pairs?  (N <= 512 <= threads)
   const bool member = tid < N && ((ctrl[kCtrlWideUnion + (tid >> 5)] >> (tid & 31)) & 1u);
-  const int cnt = member ? int(ctrl[kCtrlWideCount + tid]) : 0;
+  const int cnt = member ? int(ctrl[kCtrlWideCount + tid * wide_count_stride(N)]) : 0;
   const int inc_m = wave_incl_scan_i32(member ? 1 : 0, lane), inc_c = wave_incl_scan_i32(cnt, lane);
   if (lane == 63) {
     s_wave[0][wave] = inc_m;
@@ -510,7 +513,7 @@ static hipError_t launch_rr(const void* x, const void* w_router, const float* bi
   if (general) g = RouteGeneral{ga->p, k, ga->max_p, nullptr};
   if (B > kWideFromBatch && o.grp_off && o.grp_tok && o.grp_gw && o.grp_pos) {
     // large batch: router and routing over many workgroups, four kernels in stream order
-    const int per_wg = kRouteThreads / 64;
+    const int per_wg = kWideThreads / 64;  // a wavefront per token; small workgroups spread them over the compute units
     hipLaunchKernelGGL((wide_logits_kernel<WT>), dim3((B + 7) / 8, (N + 15) / 16), dim3(kWideThreads), 0, s,
                        static_cast<const WT*>(x), static_cast<const WT*>(w_router), bias, B, d, N, logits, out_to_zero,
                        n_zero, counter, o.n_active);
@@ -518,15 +521,15 @@ static hipError_t launch_rr(const void* x, const void* w_router, const float* bi
 #define OEA_CASE(NV)                                                                                           \
   case NV:                                                                                                     \
     if (general) {                                                                                             \
-      hipLaunchKernelGGL((wide_phase1_kernel<NV, true>), dim3((B + per_wg - 1) / per_wg), dim3(kRouteThreads), \
+      hipLaunchKernelGGL((wide_phase1_kernel<NV, true>), dim3((B + per_wg - 1) / per_wg), dim3(kWideThreads),  \
                          0, s, logits, token_mask, B, N, k0, g, counter, o.n_sel);                             \
-      hipLaunchKernelGGL((wide_phase2_kernel<NV, true>), dim3((B + per_wg - 1) / per_wg), dim3(kRouteThreads), \
+      hipLaunchKernelGGL((wide_phase2_kernel<NV, true>), dim3((B + per_wg - 1) / per_wg), dim3(kWideThreads),  \
                          0, s, logits, token_mask, B, N, k, g, counter, o);                                    \
     } else {                                                                                                   \
       hipLaunchKernelGGL((wide_phase1_kernel<NV, false>), dim3((B + per_wg - 1) / per_wg),                     \
-                         dim3(kRouteThreads), 0, s, logits, token_mask, B, N, k0, g, counter, o.n_sel);        \
+                         dim3(kWideThreads), 0, s, logits, token_mask, B, N, k0, g, counter, o.n_sel);        \
       hipLaunchKernelGGL((wide_phase2_kernel<NV, false>), dim3((B + per_wg - 1) / per_wg),                     \
-                         dim3(kRouteThreads), 0, s, logits, token_mask, B, N, k, g, counter, o);               \
+                         dim3(kWideThreads), 0, s, logits, token_mask, B, N, k, g, counter, o);               \
     }                                                                                                          \
     break;
       OEA_CASE(1)
