@@ -750,6 +750,41 @@ def test_graph_capture_and_replay(torch, B_, oracle):
     say("graph replays match the eager result")
 
 
+def test_graph_capture_large_batch(torch, B_, oracle):
+    """A batch above 128 (router and routing as four kernels, expert stages on the matrix cores: six
+    kernels per layer) captured into a graph; every replay must reproduce the eager routing, and the
+    deterministic combine the eager output bit for bit."""
+    L = W.make_layer("toy", 92, d=512, I=256, N=12, B=200, k=4, dtype="bf16")
+    dev = {f: B_.to_device(getattr(L, f)) for f in ("x", "w_router", "w_gate", "w_up", "w_down")}
+    ws = B_.new_workspace(L.B, L.d, L.N, L.I, L.k, deterministic=True)
+    out = torch.empty((L.B, L.d), dtype=torch.float32, device="cuda")
+
+    def layer():
+        B_.moe_decode(dev["x"], dev["w_router"], dev["w_gate"], dev["w_up"], dev["w_down"], L.k, 2, ws, out=out,
+                      deterministic=True)
+
+    layer()
+    torch.cuda.synchronize()
+    eager = out.cpu().numpy().copy()
+    ref = oracle.moe_decode(L.x, L.w_router, L.w_gate, L.w_up, L.w_down, L.k, 2)
+    assert np.abs(eager - ref["out"]).max() / np.abs(ref["out"]).max() <= TOL[L.dtype]
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(g, stream=s):
+            layer()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        out.fill_(7.0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy().view(np.uint32), eager.view(np.uint32)), "replay %d" % rep
+    B_.workspace_check(ws)
+    say("graph replays of a large batch match the eager result bit for bit")
+
+
 def test_unprepared_workspace_is_reported_at_once(torch, B_, oracle):
     """A layer on a workspace that oea_workspace_init never saw (or that was overwritten since) does not
     spin: its kernels return early and oea_workspace_check names the cause.  Both the single-kernel
