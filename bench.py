@@ -683,7 +683,10 @@ def run(args):
     else:
         dom_us = kern[args.k0][1]
         dom_bytes = T0 * 2 * d * I * 2 + pairs0 * d * 2 + pairs0 * I * 2  # weights + gathered x + hidden written
-        dom_name = "expert_stream_kernel<bf16, gate/up>"
+        # which gate/up kernel that is follows the library's choice (see include/oea_testing.h, kernel_path)
+        dom_name = ("expert_dense_kernel<gate/up> (matrix cores)" if (args.kernel_path == 4 or (args.kernel_path == 0 and B > 128))
+                    else "expert_stage_kernel<bf16, gate/up>" if args.kernel_path in (0, 3)
+                    else "expert_stream_kernel<bf16, gate/up>" if args.kernel_path == 2 else "expert_kernel<bf16, gate/up>")
     achieved = dom_bytes / dom_us / 1e3
     # traffic: HBM bytes per launch from the rocprofv3 --pmc passes over this same command, RECORDED in
     # profiles/ (counters cannot be read from inside the run); quoted only if the kernel sources are the ones
