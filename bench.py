@@ -700,8 +700,10 @@ def run(args):
         if rec.get("kernel_sources_sha256_16") == sources_digest() and key in rec:
             traffic = float(rec[key])
             traffic_source = "recorded: profiles/pmc_traffic_%s.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes)" % args.workload
-        else:
+        elif rec.get("kernel_sources_sha256_16") != sources_digest():
             traffic_source = "none: the recorded counters in profiles/ belong to other kernel sources"
+        else:
+            traffic_source = "none: profiles/ holds no byte counters for this kernel and k0 (they cover the default command)"
     roofline = dict(bound="hbm", kernel=dom_name, achieved=round(achieved, 1),
                     peak=HBM_PEAK_GBS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4), traffic=traffic,
                     traffic_source=traffic_source,
